@@ -1,0 +1,485 @@
+"""Pins of the CPU oracle against things other than itself: closed forms, invariants, brute force on tiny
+inputs, library routines (torch CPU) and a third-party implementation of the decoder family the paper names
+(Section 4.2: Qwen2.5), so that a dropped term, a wrong sign or index, or a transposed operand fails here.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_07878_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+SEED = 7878
+
+
+def small_shape(**kw):
+    base = dict(name="pin", n_layers=2, d_model=32, n_q_heads=4, n_kv_heads=2, head_dim=8, d_ffn=48, vocab=97,
+                rms_eps=1e-6, rope_theta=1e4, dtype=synth.F32, kv_dtype=synth.F32, tie_lm_head=1, router_hidden=16,
+                threshold=0.5)
+    base.update(kw)
+    return synth.ModelShape(**base)
+
+
+def as_f32(a, dtype):
+    return a if dtype == synth.F32 else synth.bf16_bits_to_f32(a)
+
+
+# ------------------------------------------------------------------ P1 softmax confidence / argmax
+
+def test_softmax_uniform_logits_closed_form(tro):
+    for V in (1, 2, 97, 4096):
+        tok, conf = tro.softmax_stats(np.full(V, 3.25, np.float32))
+        assert tok == 0 and conf == pytest.approx(1.0 / V, rel=1e-6)
+
+
+def test_softmax_two_logits_closed_form(tro):
+    tok, conf = tro.softmax_stats(np.array([0.5, 2.0], np.float32))
+    assert tok == 1 and conf == pytest.approx(1.0 / (1.0 + math.exp(-1.5)), rel=1e-6)
+
+
+def test_softmax_ties_take_lowest_index(tro):
+    z = np.zeros(50, np.float32); z[[7, 19, 33]] = 4.0
+    assert tro.softmax_stats(z)[0] == 7
+
+
+def test_softmax_against_torch(tro):
+    g = np.random.default_rng(1)
+    for V in (5, 1000, 151936):
+        z = (g.standard_normal(V) * 3).astype(np.float32)
+        tok, conf = tro.softmax_stats(z)
+        p = torch.softmax(torch.from_numpy(z).double(), 0)
+        assert tok == int(torch.argmax(p)) and conf == pytest.approx(float(p.max()), rel=1e-6)
+        assert 1.0 / V <= conf <= 1.0
+
+
+def test_softmax_large_logits_do_not_overflow(tro):
+    tok, conf = tro.softmax_stats(np.array([1e4, 1e4 - 1.0, -1e4], np.float32))
+    assert tok == 0 and conf == pytest.approx(1.0 / (1.0 + math.exp(-1.0)), rel=1e-6)
+
+
+# ------------------------------------------------------------------ P2 rotary embedding
+
+def test_rope_position_zero_is_identity(tro):
+    u = np.random.default_rng(2).standard_normal(64).astype(np.float32)
+    assert np.array_equal(tro.rope(u, 0, 1e4), u)
+
+
+def test_rope_explicit_rotation_direction_and_frequencies(tro):
+    # head_dim 4: pairs (0,2) and (1,3); frequency of pair j is theta^(-2j/4)
+    theta, pos = 100.0, 3
+    u = np.array([1.0, 0.0, 0.0, 1.0], np.float32)
+    r = tro.rope(u, pos, theta)
+    a0, a1 = pos * 1.0, pos * theta ** -0.5
+    want = [math.cos(a0), -math.sin(a1), math.sin(a0), math.cos(a1)]
+    assert np.allclose(r, want, atol=1e-7)
+
+
+def test_rope_preserves_norm_and_is_relative(tro):
+    g = np.random.default_rng(3)
+    q, k = g.standard_normal(64).astype(np.float32), g.standard_normal(64).astype(np.float32)
+    for theta in (1e4, 1e6):
+        for pos in (1, 17, 1535):
+            assert np.linalg.norm(tro.rope(q, pos, theta).astype(np.float64)) == pytest.approx(np.linalg.norm(q.astype(np.float64)), rel=1e-6)
+        d0 = float(np.dot(tro.rope(q, 40, theta).astype(np.float64), tro.rope(k, 25, theta).astype(np.float64)))
+        d1 = float(np.dot(tro.rope(q, 140, theta).astype(np.float64), tro.rope(k, 125, theta).astype(np.float64)))
+        d2 = float(np.dot(tro.rope(q, 15, theta).astype(np.float64), k.astype(np.float64)))
+        assert d0 == pytest.approx(d1, abs=2e-5) and d0 == pytest.approx(d2, abs=2e-5)
+
+
+# ------------------------------------------------------------------ RMSNorm, linear, SiLU
+
+def test_rmsnorm_constant_vector_closed_form(tro):
+    d, eps = 40, 1e-6
+    gain = np.linspace(0.5, 1.5, d).astype(np.float32)
+    for c in (3.0, -0.25):
+        out = tro.rmsnorm(np.full(d, c, np.float32), gain, synth.F32, eps)
+        want = gain * np.sign(c) / math.sqrt(1.0 + eps / (c * c))
+        assert np.allclose(out, want, rtol=1e-6)
+
+
+def test_rmsnorm_eps_dominates_for_tiny_input(tro):
+    # x -> 0: out = x * g / sqrt(eps)
+    x = np.array([1e-12, -2e-12, 0.0, 3e-12], np.float32)
+    out = tro.rmsnorm(x, np.ones(4, np.float32), synth.F32, 1e-6)
+    assert np.allclose(out, x / 1e-3, rtol=1e-5)
+
+
+def test_rmsnorm_against_torch_and_bf16_gain(tro):
+    g = np.random.default_rng(4)
+    x = g.standard_normal(896).astype(np.float32)
+    gain = synth.f32_to_bf16_bits((1 + 0.1 * g.standard_normal(896)).astype(np.float32))
+    out = tro.rmsnorm(x, gain, synth.BF16, 1e-6)
+    xt = torch.from_numpy(x).double()
+    want = torch.nn.functional.rms_norm(xt, (896,), torch.from_numpy(synth.bf16_bits_to_f32(gain)).double(), 1e-6)
+    assert np.allclose(out, want.numpy(), rtol=1e-6, atol=1e-7)
+
+
+def test_linear_is_row_major_out_by_in(tro):
+    # a transposed operand or swapped N/K fails: W is [3][5]
+    W = np.arange(15, dtype=np.float32).reshape(3, 5)
+    x = np.array([1, 0, 0, 0, 2], np.float32)
+    b = np.array([10, 20, 30], np.float32)
+    assert np.array_equal(tro.linear(W, b, synth.F32, x), W[:, 0] + 2 * W[:, 4] + b)
+    assert np.array_equal(tro.linear(W, None, synth.F32, x), W[:, 0] + 2 * W[:, 4])
+
+
+def test_linear_against_torch_fp64_both_dtypes(tro):
+    g = np.random.default_rng(5)
+    x = g.standard_normal(300).astype(np.float32)
+    for dt in (synth.F32, synth.BF16):
+        W = synth.normal(SEED, "pinW", (70, 300), 0.02, dt)
+        b = synth.normal(SEED, "pinb", (70,), 0.02, dt)
+        want = torch.nn.functional.linear(torch.from_numpy(x).double(), torch.from_numpy(as_f32(W, dt)).double(),
+                                          torch.from_numpy(as_f32(b, dt)).double())
+        assert np.allclose(tro.linear(W, b, dt, x), want.numpy(), rtol=1e-6, atol=1e-7)
+
+
+def test_bf16_widening_and_rounding(tro):
+    assert tro.bf16_to_f32(0x3F80) == 1.0 and tro.bf16_to_f32(0xC000) == -2.0 and tro.bf16_to_f32(0x3DCD) == pytest.approx(0.1, rel=4e-3)
+    # nearest-even: 1 + 2^-8 is exactly half way between 1 and 1 + 2^-7 -> even mantissa (1.0); 1 + 3*2^-8 -> 1 + 2^-6
+    assert tro.round_to_bf16(1.0 + 2.0 ** -8) == 1.0
+    assert tro.round_to_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    assert tro.round_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -20) == 1.0 + 2.0 ** -7
+    vals = np.random.default_rng(6).standard_normal(2000).astype(np.float32)
+    want = torch.from_numpy(vals).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(np.array([tro.round_to_bf16(v) for v in vals], np.float32), want)
+
+
+def test_silu_against_torch_and_limits(tro):
+    for u in (-30.0, -1.5, 0.0, 0.3, 4.0, 30.0):
+        assert tro.silu(u) == pytest.approx(float(torch.nn.functional.silu(torch.tensor(u, dtype=torch.float64))), rel=1e-6, abs=1e-12)
+    assert tro.silu(0.0) == 0.0 and tro.silu(40.0) == pytest.approx(40.0) and abs(tro.silu(-40.0)) < 1e-15
+
+
+# ------------------------------------------------------------------ P7 attention special cases, P8 library
+
+def test_attention_single_key_returns_its_value(tro):
+    g = np.random.default_rng(7)
+    q, k, v = (g.standard_normal(64).astype(np.float32) for _ in range(3))
+    assert np.array_equal(tro.attend(q, k[None], v[None]), v)
+
+
+def test_attention_equal_keys_returns_mean_of_values(tro):
+    g = np.random.default_rng(8)
+    q, k = g.standard_normal(16).astype(np.float32), g.standard_normal(16).astype(np.float32)
+    V = g.standard_normal((9, 16)).astype(np.float32)
+    assert np.allclose(tro.attend(q, np.tile(k, (9, 1)), V), V.astype(np.float64).mean(0), rtol=1e-6, atol=1e-7)
+
+
+def test_attention_scale_is_inverse_sqrt_head_dim(tro):
+    # two keys, q.k = (dh, 0) -> weights softmax(sqrt(dh), 0)
+    dh = 16
+    q = np.ones(dh, np.float32)
+    K = np.stack([np.ones(dh, np.float32), np.zeros(dh, np.float32)])
+    V = np.stack([np.full(dh, 1.0, np.float32), np.full(dh, -1.0, np.float32)])
+    p = 1.0 / (1.0 + math.exp(-math.sqrt(dh)))
+    assert np.allclose(tro.attend(q, K, V), p - (1 - p), rtol=1e-6)
+
+
+def test_attention_against_torch_sdpa(tro):
+    g = np.random.default_rng(9)
+    ctx, dh = 37, 64
+    q, K, V = g.standard_normal(dh).astype(np.float32), g.standard_normal((ctx, dh)).astype(np.float32), g.standard_normal((ctx, dh)).astype(np.float32)
+    want = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q).double()[None, None], torch.from_numpy(K).double()[None],
+                                                            torch.from_numpy(V).double()[None])
+    assert np.allclose(tro.attend(q, K, V), want[0, 0].numpy(), rtol=1e-6, atol=1e-7)
+
+
+# ------------------------------------------------------------------ router and flag (Section 3.1)
+
+def test_router_closed_forms(tro):
+    d, rh = 6, 3
+    u = np.zeros(d, np.float32); u[0] = 2.0
+    w1 = np.zeros((rh, d), np.float32); w1[0, 0] = 1.0; w1[1, 0] = -1.0; w1[2, 1] = 5.0  # pre-activations 2, -2, 0
+    b1 = np.array([0.0, 0.0, 0.5], np.float32)
+    w2 = np.array([0.25, 100.0, -1.0], np.float32)  # the negative unit must be cut by the ReLU
+    b2 = np.array([0.125], np.float32)
+    want = 1.0 / (1.0 + math.exp(-(0.25 * 2.0 - 1.0 * 0.5 + 0.125)))
+    assert tro.router_score(u, w1, b1, w2, b2, synth.F32) == pytest.approx(want, rel=1e-6)
+    # no biases given
+    assert tro.router_score(u, w1, None, w2, None, synth.F32) == pytest.approx(1.0 / (1.0 + math.exp(-0.5)), rel=1e-6)
+
+
+def test_router_against_torch_module(tro):
+    g = np.random.default_rng(10)
+    d, rh = 896, 256
+    for dt in (synth.F32, synth.BF16):
+        w1 = synth.normal(SEED, "rw1", (rh, d), 0.05, dt); b1 = synth.normal(SEED, "rb1", (rh,), 0.1, dt)
+        w2 = synth.normal(SEED, "rw2", (rh,), 0.2, dt); b2 = synth.normal(SEED, "rb2", (1,), 0.1, dt)
+        u = g.standard_normal(d).astype(np.float32)
+        mlp = torch.nn.Sequential(torch.nn.Linear(d, rh), torch.nn.ReLU(), torch.nn.Linear(rh, 1), torch.nn.Sigmoid()).double()
+        with torch.no_grad():
+            mlp[0].weight.copy_(torch.from_numpy(as_f32(w1, dt))); mlp[0].bias.copy_(torch.from_numpy(as_f32(b1, dt)))
+            mlp[2].weight.copy_(torch.from_numpy(as_f32(w2, dt))[None]); mlp[2].bias.copy_(torch.from_numpy(as_f32(b2, dt)))
+            want = float(mlp(torch.from_numpy(u).double()))
+        assert tro.router_score(u, w1, b1, w2, b2, dt) == pytest.approx(want, rel=1e-5)
+
+
+def test_flag_is_strict_score_below_threshold(tro):
+    assert tro.route_flag(0.69, 0.7) == 1 and tro.route_flag(0.71, 0.7) == 0
+    assert tro.route_flag(0.7, 0.7) == 0            # a tie is not routed
+    assert tro.route_flag(float("nan"), 0.7) == 0   # NaN compares false
+    assert tro.route_flag(0.1, 0.7, mode=tro.SMALL_ONLY) == 0   # Section 3.1: small_only disables routing
+    assert tro.route_flag(0.71, 0.7, route_dir=tro.ROUTE_IF_ABOVE) == 1 and tro.route_flag(0.69, 0.7, route_dir=tro.ROUTE_IF_ABOVE) == 0
+
+
+def test_routing_number_grows_with_threshold_as_in_table_1(tro):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table1_routing_number.txt")) if l.strip() and not l.startswith("#")]
+    thr = [float(a) for a, _ in rows]; cnt = [int(b) for _, b in rows]
+    assert cnt == sorted(cnt)
+    # 100 scores placed so that exactly cnt[i] of them lie below thr[i] (as many as the paper counted), the rest above 0.9
+    scores, prev_t, prev_c = [], 0.0, 0
+    for t, c in zip(thr, cnt):
+        scores += list(np.linspace(prev_t, t, c - prev_c + 2)[1:-1])
+        prev_t, prev_c = t, c
+    scores += [0.95] * (100 - len(scores))
+    for t, c in zip(thr, cnt):
+        assert sum(tro.route_flag(s, t) for s in scores) == c
+        assert sum(tro.route_flag(s, t, mode=tro.SMALL_ONLY) for s in scores) == 0
+    assert sum(tro.route_flag(s, 0.0) for s in scores) == 0 and sum(tro.route_flag(s, 1.0) for s in scores) == 100
+
+
+# ------------------------------------------------------------------ whole model
+
+def build(tro, shape, max_batch=2, max_seq=64, bias_std=0.05, gain_std=0.1, std=0.08, **kw):
+    w = synth.make_weights(shape, SEED, std=std, bias_std=bias_std, gain_std=gain_std)
+    return tro.Model(shape.asdict(), w, max_batch, max_seq, **kw), w
+
+
+def test_model_matches_third_party_qwen2_implementation(tro):
+    """Logits and last hidden state equal those of the transformers Qwen2 decoder (random weights, CPU, fp64)."""
+    from transformers import Qwen2Config, Qwen2ForCausalLM
+    s = small_shape()
+    m, w = build(tro, s)
+    cfg = Qwen2Config(vocab_size=s.vocab, hidden_size=s.d_model, intermediate_size=s.d_ffn, num_hidden_layers=s.n_layers,
+                      num_attention_heads=s.n_q_heads, num_key_value_heads=s.n_kv_heads, max_position_embeddings=64,
+                      rms_norm_eps=s.rms_eps, rope_theta=s.rope_theta, tie_word_embeddings=True, attn_implementation="eager",
+                      use_sliding_window=False)
+    hf = Qwen2ForCausalLM(cfg).double().eval()
+    sd = {"model.embed_tokens.weight": w["tok_emb"], "model.norm.weight": w["final_norm"], "lm_head.weight": w["tok_emb"]}
+    for i in range(s.n_layers):
+        p, q = f"model.layers.{i}.", f"l{i}."
+        for a, b in (("self_attn.q_proj.weight", "wq"), ("self_attn.k_proj.weight", "wk"), ("self_attn.v_proj.weight", "wv"),
+                     ("self_attn.q_proj.bias", "bq"), ("self_attn.k_proj.bias", "bk"), ("self_attn.v_proj.bias", "bv"),
+                     ("self_attn.o_proj.weight", "wo"), ("mlp.gate_proj.weight", "wg"), ("mlp.up_proj.weight", "wu"),
+                     ("mlp.down_proj.weight", "wd"), ("input_layernorm.weight", "ln1"), ("post_attention_layernorm.weight", "ln2")):
+            sd[p + a] = w[q + b]
+    hf.load_state_dict({k: torch.from_numpy(v).double() for k, v in sd.items()}, strict=True)
+    toks = synth.prompt_tokens(SEED, "hfprompt", 23, s.vocab)
+    with torch.no_grad():
+        o = hf(torch.from_numpy(toks).long()[None], output_hidden_states=True)
+    hid, lg = m.forward_all(toks)
+    assert np.allclose(lg, o.logits[0].numpy(), rtol=2e-5, atol=2e-5)
+    assert np.allclose(hid, o.hidden_states[-1][0].numpy(), rtol=2e-5, atol=2e-5)
+    # and the cached path gives the same last position
+    out = m.prefill([0], [toks[:-1]])
+    out = m.decode_step([0], [toks[-1]], want_logits=True)
+    assert np.allclose(out.logits[0], o.logits[0, -1].numpy(), rtol=2e-5, atol=2e-5)
+    assert out.token[0] == int(o.logits[0, -1].argmax())
+
+
+def test_causal_mask_by_brute_force(tro):
+    s = small_shape()
+    m, _ = build(tro, s)
+    toks = synth.prompt_tokens(SEED, "causal", 12, s.vocab)
+    hid, lg = m.forward_all(toks)
+    for j in (5, 11):
+        t2 = toks.copy(); t2[j:] = (t2[j:] + 1 + np.arange(12 - j)) % s.vocab
+        hid2, lg2 = m.forward_all(t2)
+        assert np.array_equal(hid[:j], hid2[:j]) and np.array_equal(lg[:j], lg2[:j])   # the past is untouched, bit for bit
+        assert not np.array_equal(hid[j], hid2[j])
+
+
+def test_every_position_of_full_forward_equals_forward_of_its_prefix(tro):
+    s = small_shape()
+    m, _ = build(tro, s)
+    toks = synth.prompt_tokens(SEED, "prefix", 9, s.vocab)
+    hid, lg = m.forward_all(toks)
+    for T in (1, 4, 9):
+        h2, l2 = m.forward_all(toks[:T])
+        assert np.array_equal(h2[-1], hid[T - 1]) and np.array_equal(l2[-1], lg[T - 1])
+
+
+@pytest.mark.parametrize("kv_dtype", [synth.F32, synth.BF16])
+def test_prefill_equals_shorter_prefill_plus_decode(tro, kv_dtype):
+    """Re-prefilling the whole sequence (what the paper's system does, Section 4.1) equals cached decoding."""
+    s = small_shape(kv_dtype=kv_dtype)
+    m, _ = build(tro, s)
+    toks = synth.prompt_tokens(SEED, "incr", 20, s.vocab)
+    full = m.prefill([0], [toks], want_logits=True)
+    m.prefill([1], [toks[:14]])
+    for t in toks[14:]:
+        step = m.decode_step([1], [t], want_logits=True)
+    assert np.allclose(step.logits, full.logits, rtol=1e-6, atol=1e-6) and np.allclose(step.hidden, full.hidden, rtol=1e-6, atol=1e-6)
+    assert step.token[0] == full.token[0] and step.flag[0] == full.flag[0]
+    assert step.score[0] == pytest.approx(full.score[0], rel=1e-6) and step.conf[0] == pytest.approx(full.conf[0], rel=1e-6)
+    assert m.seq_len(0) == m.seq_len(1) == 20
+    for layer in range(s.n_layers):
+        k0, v0 = m.read_kv(0, layer); k1, v1 = m.read_kv(1, layer)
+        assert np.allclose(k0, k1, rtol=1e-6, atol=1e-6) and np.allclose(v0, v1, rtol=1e-6, atol=1e-6)
+
+
+def test_bf16_cache_entries_are_bf16_values(tro):
+    s = small_shape(kv_dtype=synth.BF16)
+    m, _ = build(tro, s)
+    m.prefill([0], [synth.prompt_tokens(SEED, "kvr", 7, s.vocab)])
+    k, v = m.read_kv(0, 1)
+    for a in (k, v):
+        assert np.array_equal(a, torch.from_numpy(a).to(torch.bfloat16).float().numpy()) and np.abs(a).max() > 0
+
+
+def test_zero_output_projections_make_layers_identity(tro):
+    """With Wo = Wd = 0 every layer adds nothing: logits = E . RMSNorm(E[t_last]) in closed form."""
+    s = small_shape()
+    w = synth.make_weights(s, SEED, std=0.08, gain_std=0.1)
+    for i in range(s.n_layers):
+        w[f"l{i}.wo"][:] = 0; w[f"l{i}.wd"][:] = 0
+    m = tro.Model(s.asdict(), w, 1, 32)
+    toks = synth.prompt_tokens(SEED, "ident", 6, s.vocab)
+    out = m.prefill([0], [toks], want_logits=True)
+    E = w["tok_emb"].astype(np.float64); x = E[toks[-1]]
+    hn = x / np.sqrt((x * x).mean() + s.rms_eps) * w["final_norm"].astype(np.float64)
+    assert np.allclose(out.hidden[0], hn, rtol=1e-6, atol=1e-7) and np.allclose(out.logits[0], E @ hn, rtol=1e-5, atol=1e-6)
+    assert out.token[0] == int(np.argmax(E @ hn))
+
+
+def test_grouped_query_attention_equals_multi_head_with_duplicated_kv(tro):
+    s = small_shape()
+    w = synth.make_weights(s, SEED, std=0.08, bias_std=0.05, gain_std=0.1)
+    grouped = tro.Model(s.asdict(), w, 1, 32)
+    group, dh = s.n_q_heads // s.n_kv_heads, s.head_dim
+    s2 = s.with_(n_kv_heads=s.n_q_heads)
+    w2 = dict(w)
+    for i in range(s.n_layers):
+        for nm in ("wk", "wv", "bk", "bv"):
+            a = w[f"l{i}.{nm}"]
+            a = a.reshape(s.n_kv_heads, dh, *a.shape[1:])
+            w2[f"l{i}.{nm}"] = np.ascontiguousarray(np.repeat(a, group, axis=0).reshape(s.n_q_heads * dh, *a.shape[2:]))
+    mha = tro.Model(s2.asdict(), w2, 1, 32)
+    toks = synth.prompt_tokens(SEED, "gqa", 10, s.vocab)
+    a, b = grouped.prefill([0], [toks], want_logits=True), mha.prefill([0], [toks], want_logits=True)
+    assert np.array_equal(a.logits, b.logits) and np.array_equal(a.hidden, b.hidden)
+
+
+def test_batch_invariance_and_slot_independence(tro):
+    s = small_shape()
+    m, _ = build(tro, s, max_batch=3)
+    pa, pb = synth.prompt_tokens(SEED, "pa", 9, s.vocab), synth.prompt_tokens(SEED, "pb", 5, s.vocab)
+    both = m.prefill([2, 0], [pa, pb], want_logits=True)
+    alone = m.prefill([1], [pa], want_logits=True)
+    assert np.array_equal(both.logits[0], alone.logits[0])
+    d2 = m.decode_step([0, 2], [3, 4], want_logits=True)
+    d1 = m.decode_step([1], [4], want_logits=True)
+    assert np.array_equal(d2.logits[1], d1.logits[0]) and d2.token[1] == d1.token[0]
+
+
+def test_hidden_tap_and_route_direction_options(tro):
+    s = small_shape()
+    w = synth.make_weights(s, SEED, std=0.08, gain_std=0.1)
+    toks = synth.prompt_tokens(SEED, "tap", 6, s.vocab)
+    post = tro.Model(s.asdict(), w, 1, 16).prefill([0], [toks])
+    pre = tro.Model(s.asdict(), w, 1, 16, hidden_tap=tro.PRE_FINAL_NORM).prefill([0], [toks])
+    assert np.allclose(tro.rmsnorm(pre.hidden[0], w["final_norm"], s.dtype, s.rms_eps), post.hidden[0], rtol=1e-6, atol=1e-7)
+    assert pre.token[0] == post.token[0]
+    assert post.score[0] == pytest.approx(tro.router_score(post.hidden[0], w["r_w1"], w["r_b1"], w["r_w2"], w["r_b2"], s.dtype), rel=1e-6)
+    assert pre.score[0] == pytest.approx(tro.router_score(pre.hidden[0], w["r_w1"], w["r_b1"], w["r_w2"], w["r_b2"], s.dtype), rel=1e-6)
+    above = tro.Model(s.asdict(), w, 1, 16, route_dir=tro.ROUTE_IF_ABOVE)
+    above.set_threshold(float(post.score[0]) - 1e-3)
+    assert above.prefill([0], [toks]).flag[0] == 1
+
+
+def test_model_without_router_reports_no_routing(tro):
+    s = small_shape(router_hidden=0, tie_lm_head=0)
+    w = synth.make_weights(s, SEED, std=0.08)
+    out = tro.Model(s.asdict(), w, 1, 16).prefill([0], [[1, 2, 3]], want_logits=True)
+    assert out.flag[0] == 0 and out.score[0] == 1.0
+    hn = out.hidden[0].astype(np.float64)
+    assert np.allclose(out.logits[0], w["lm_head"].astype(np.float64) @ hn, rtol=1e-5, atol=1e-6)   # the untied head is used
+
+
+# ------------------------------------------------------------------ P6 / P9 state machine (Figure 5: token_index, history)
+
+def test_bookkeeping_matches_a_plain_state_machine(tro):
+    s = small_shape()
+    m, _ = build(tro, s, max_batch=3, max_seq=12)
+    model = {}   # slot -> [len, n_generated, n_routed]
+    g = np.random.default_rng(11)
+
+    def check():
+        for slot, (ln, ng, nr) in model.items():
+            assert m.seq_len(slot) == ln and m.counters(slot) == (ng, nr)
+
+    m.set_threshold(0.5)
+    o = m.prefill([0, 2], [[1, 2, 3, 4], [5, 6]])
+    model[0] = [4, 1, int(o.flag[0])]; model[2] = [2, 1, int(o.flag[1])]
+    check()
+    for step in range(6):
+        toks = g.integers(0, s.vocab, 2)
+        m.set_threshold(0.9 if step % 2 else 0.1)
+        o = m.decode_step([2, 0], toks)
+        for i, slot in enumerate((2, 0)):
+            model[slot][0] += 1; model[slot][1] += 1; model[slot][2] += int(o.flag[i])
+            assert int(o.flag[i]) == int(o.score[i] < (0.9 if step % 2 else 0.1))
+        check()
+    assert m.counters(0)[1] > 0            # some tokens were routed at the high threshold
+    # errors leave the state alone
+    for bad in (lambda: m.decode_step([1], [0]),              # never prefilled
+                lambda: m.decode_step([0, 0], [1, 1]),        # duplicate slot
+                lambda: m.decode_step([0], [s.vocab]),        # token out of range
+                lambda: m.decode_step([3], [0]),              # slot out of range
+                lambda: m.prefill([1], [list(range(13))])):   # longer than max_seq
+        with pytest.raises(tro.OracleError):
+            bad()
+        check()
+    assert m.seq_len(1) == 0
+    # fill slot 0 to capacity, then one more step must fail
+    while m.seq_len(0) < 12:
+        m.decode_step([0], [1]); model[0][0] += 1; model[0][1] += 1; model[0][2] = m.counters(0)[1]
+    with pytest.raises(tro.OracleError) as e:
+        m.decode_step([0], [1])
+    assert e.value.code == tro.ERR_CAPACITY
+    check()
+    # small_only: nothing is routed, whatever the threshold
+    m.set_mode(tro.SMALL_ONLY); m.set_threshold(1.0)
+    before = m.counters(2)
+    o = m.decode_step([2], [7])
+    assert o.flag[0] == 0 and m.counters(2) == (before[0] + 1, before[1])
+
+
+def test_truncate_then_decode_reproduces_the_same_step(tro):
+    """Replacing the next input token (a routed token coming back, Section 4.1) needs no recompute of the history."""
+    s = small_shape()
+    m, _ = build(tro, s)
+    toks = synth.prompt_tokens(SEED, "trunc", 8, s.vocab)
+    m.prefill([0], [toks])
+    a = m.decode_step([0], [11], want_logits=True)
+    k_before, _ = m.read_kv(0, 0)
+    m.decode_step([0], [12])
+    m.seq_truncate(0, 9)
+    b = m.decode_step([0], [55], want_logits=True)       # a different token at position 9
+    m.seq_truncate(0, 8)
+    c = m.decode_step([0], [11], want_logits=True)
+    assert np.array_equal(a.logits, c.logits) and not np.array_equal(a.logits, b.logits)
+    k_after, _ = m.read_kv(0, 0)
+    assert np.array_equal(k_before[:, :8], k_after[:, :8])
+
+
+def test_fig5_example_fields_map_onto_counters():
+    rows = dict(l.split(None, 1) for l in open(os.path.join(GOLDEN, "fig5_api_example.txt")) if l.strip() and not l.startswith("#"))
+    routes = rows["history_routes"].split()
+    assert int(rows["token_index"]) == 15 and float(rows["routing_threshold"]) == 0.7
+    assert (len(routes), routes.count("LLM")) == (2, 1)   # n_generated, n_routed of that history
+
+
+def test_load_kv_then_decode_equals_prefilled_cache(tro):
+    s = small_shape()
+    m, _ = build(tro, s)
+    toks = synth.prompt_tokens(SEED, "load", 6, s.vocab)
+    m.prefill([0], [toks])
+    ks, vs = zip(*[m.read_kv(0, l) for l in range(s.n_layers)])
+    m.load_kv(1, np.stack(ks), np.stack(vs))
+    a, b = m.decode_step([0], [3], want_logits=True), m.decode_step([1], [3], want_logits=True)
+    assert np.array_equal(a.logits, b.logits) and m.seq_len(1) == 7
