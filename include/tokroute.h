@@ -1,0 +1,151 @@
+/*
+ * tokroute — token-level routing decode path for AMD MI355X (gfx950), C ABI.
+ *
+ * The library runs the on-device small model of a token-level routing system
+ * (arxiv 2504.07878, Section 3: "on-device small model inference module" + "token routing
+ * selection module") as a batched decode step with a key/value cache, followed by the
+ * routing tail: final RMSNorm, LM head over the full vocabulary, softmax confidence and greedy
+ * argmax, the MLP router on the exposed last-layer hidden state (Section 3.3, Figure 4) and the
+ * rule "route the token to the large model when its score falls below the threshold"
+ * (Section 3.1). A context without a router runs the same step for the large model that
+ * generates the routed tokens (Section 3.3, Section 4).
+ *
+ * General conventions
+ *  - Every function returns a status: TR_OK (0) or a negative TR_ERR_* code; nothing throws,
+ *    aborts or prints. tr_last_error() gives the text of the last failure on a context.
+ *  - On any error the context state (cache, sequence lengths, counters) is unchanged and no
+ *    work has been enqueued.
+ *  - "device" pointers are HIP device memory of the current device; "host" pointers are
+ *    ordinary host memory. The library allocates no device memory and creates no stream: the
+ *    caller hands in a workspace and a hipStream_t (as void*; NULL = the default stream).
+ *  - tr_prefill / tr_decode_step / tr_tail / tr_seq_load_kv only enqueue work on the stream and
+ *    return; outputs are valid once the caller has synchronised that stream. Calls on one
+ *    context must be issued from one thread at a time and on streams that are ordered with
+ *    respect to each other.
+ *  - Positions and token indices are 0-based (Figure 5, "token_index"): the token at cache
+ *    index i is rotated with RoPE position i; a sequence's length is the number of tokens whose
+ *    keys/values are cached; the token emitted by a step has index equal to that length.
+ */
+#ifndef TOKROUTE_H
+#define TOKROUTE_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { TR_OK = 0, TR_ERR_INVALID_ARG = -1, TR_ERR_SHAPE = -2, TR_ERR_CAPACITY = -3, TR_ERR_STATE = -4, TR_ERR_HIP = -5 };
+enum { TR_F32 = 0, TR_BF16 = 1 };
+enum { TR_JOINT = 0, TR_SMALL_ONLY = 1 };                 /* inference modes of Section 3.1 */
+enum { TR_ROUTE_IF_BELOW = 0, TR_ROUTE_IF_ABOVE = 1 };    /* Section 3.1 rule | the deferral rule of Section 2.2 */
+enum { TR_POST_FINAL_NORM = 0, TR_PRE_FINAL_NORM = 1 };   /* which tensor is the "last-layer hidden state" */
+
+typedef struct tr_ctx tr_ctx;
+
+/* Model and capacity description. The decoder is the pre-norm GQA / RoPE (half-split pairing) / SwiGLU
+ * stack of the model family named in Section 4.2. */
+typedef struct tr_config {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rms_eps, rope_theta;
+    int32_t dtype;         /* storage type of every weight tensor: TR_F32 or TR_BF16 */
+    int32_t kv_dtype;      /* storage type of the key/value cache (values are rounded to nearest-even on write) */
+    int32_t tie_lm_head;   /* 1: the LM head is the token embedding matrix */
+    int32_t router_hidden; /* width of the router's hidden layer; 0 = no router (score = 1, flag = 0) */
+    float threshold;       /* initial routing threshold */
+    int32_t route_dir;     /* TR_ROUTE_IF_BELOW: flag = score < threshold (strict) */
+    int32_t hidden_tap;    /* tensor returned as hidden state and fed to the router */
+    int32_t max_batch;     /* number of sequence slots */
+    int32_t max_seq;       /* cache capacity per slot, in tokens */
+} tr_config;
+
+/* DEVICE pointers, row-major [out][in], all in tr_config.dtype. BORROWED: they must stay valid and
+ * unchanged for the life of the context; the library never writes them. The pointer arrays
+ * themselves are HOST arrays of n_layers device pointers and are copied by tr_create.
+ * bq/bk/bv (arrays or single entries) and r_b1/r_b2 may be NULL = no bias. */
+typedef struct tr_weights {
+    const void *tok_emb;    /* [vocab][d_model] */
+    const void *lm_head;    /* [vocab][d_model]; NULL when tie_lm_head */
+    const void *final_norm; /* [d_model] */
+    const void *const *ln1, *const *wq, *const *wk, *const *wv, *const *bq, *const *bk, *const *bv;
+    const void *const *wo, *const *ln2, *const *wg, *const *wu, *const *wd;
+    const void *r_w1, *r_b1, *r_w2, *r_b2; /* router: [rh][d_model], [rh], [rh], [1] */
+} tr_weights;
+
+/* Caller-owned DEVICE output buffers; row i belongs to the i-th sequence of the call.
+ * token/conf/score/flag are required; hidden and logits may be NULL. */
+typedef struct tr_out {
+    int32_t *token; /* greedy next token: lowest index attaining the maximum logit */
+    float *conf;    /* its softmax probability (Figure 1: "low confidence") */
+    float *score;   /* router output in (0,1) (Section 3.1) */
+    int32_t *flag;  /* 1 = route this token to the large model */
+    float *hidden;  /* [n][d_model] exposed last-layer hidden state (Section 3.3) */
+    float *logits;  /* [n][vocab] full logits, for debugging and parity checks; costs a write of n*vocab*4 bytes */
+} tr_out;
+
+/* Bytes of device workspace tr_create needs for this configuration (cache, tables, scratch); 0 if the
+ * configuration is invalid. */
+size_t tr_workspace_bytes(const tr_config *cfg);
+
+/* Build a context over a caller-provided device workspace (256-byte aligned, at least
+ * tr_workspace_bytes(cfg) bytes, owned by the caller and dedicated to this context until tr_destroy).
+ * Synchronous: uploads small tables and clears counters with blocking copies.
+ * Errors: TR_ERR_INVALID_ARG (NULL/misaligned), TR_ERR_SHAPE (unsupported shape), TR_ERR_CAPACITY
+ * (workspace too small), TR_ERR_HIP. */
+int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t workspace_bytes, tr_ctx **out);
+
+/* Frees the host-side context only. The caller must have synchronised all streams it used. */
+void tr_destroy(tr_ctx *ctx);
+
+/* Prefill (the paper's TTFT phase, Section 4.1): run the prompts of n distinct slots through the model,
+ * fill their caches from position 0, reset their counters, and return the outputs of each prompt's LAST
+ * position (the prediction of the first generated token and its route flag).
+ * slots [n], tokens_flat [offsets[n]], offsets [n+1] (offsets[0] = 0) are HOST arrays, read before return.
+ * Errors: TR_ERR_INVALID_ARG (bad slot/duplicate/token out of range/empty prompt), TR_ERR_CAPACITY
+ * (prompt longer than max_seq). */
+int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *tokens_flat,
+               const int32_t *offsets, const tr_out *out);
+
+/* One decode step for n distinct slots: in_tokens[i] is appended to slot slots[i] (the caller supplies it
+ * every step, so a token generated by the large model can replace the small model's, Section 3.1), the
+ * model attends over the slot's cache, and the routing tail produces the outputs. Lengths grow by one;
+ * n_generated grows by one and n_routed by the flag.
+ * slots and in_tokens are HOST arrays, read before return.
+ * Errors: TR_ERR_STATE (slot never prefilled/loaded), TR_ERR_CAPACITY (slot full), TR_ERR_INVALID_ARG. */
+int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens,
+                   const tr_out *out);
+
+/* The routing tail alone on n rows of residual stream x (DEVICE, fp32 [n][d_model]): final RMSNorm, LM
+ * head, softmax confidence + argmax, router, flag. Touches no sequence state and no counters.
+ * n <= max_batch. */
+int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out);
+
+/* Threshold slider and mode switch of Section 3.1; they apply to calls made afterwards. */
+int tr_set_threshold(tr_ctx *ctx, float threshold);
+int tr_set_mode(tr_ctx *ctx, int32_t mode);
+
+/* Host-side sequence state. tr_seq_truncate rolls a slot back to its first new_len tokens. */
+int tr_seq_len(const tr_ctx *ctx, int32_t slot, int32_t *len);
+int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len);
+
+/* Overwrite a slot's cache with len tokens of given keys/values (DEVICE pointers in kv_dtype, layout
+ * [layer][kv_head][len][head_dim], keys already rotated) and set its length; counters are cleared. */
+int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, const void *k, const void *v);
+
+/* Device address of the per-slot counters, int64 [max_batch][2] = {n_generated, n_routed}
+ * (the routing history of Figure 5 as counts). They live in the workspace and are updated by the tail
+ * kernel; read them with a device-to-host copy after synchronising. */
+int tr_counters_ptr(const tr_ctx *ctx, const int64_t **dev_counters);
+
+/* Kernel timing for benchmarks: while enabled, the LM-head kernel of every tail launch is bracketed by
+ * HIP events on the launch stream. tr_profile_read synchronises those events and returns the summed
+ * duration in milliseconds and the number of launches since enabling. */
+int tr_profile_enable(tr_ctx *ctx, int32_t on);
+int tr_profile_read(tr_ctx *ctx, double *ms_total, int64_t *launches);
+
+const char *tr_last_error(const tr_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,539 @@
+// Streaming (GEMV-class) kernels of the decode step for gfx950: fp32 activations, fp32 or bf16 weights,
+// fp32 accumulation. One 64-lane wavefront owns a few output rows and strides over the reduction
+// dimension with 16-byte loads; reductions are wavefront shuffles in a fixed order, so results are
+// bit-identical from run to run.
+//
+// The step follows the decoder of the model family named in Section 4.2 of arxiv 2504.07878
+// (pre-norm, grouped-query attention, rotary embedding with half-split pairing, SwiGLU FFN);
+// the tail (final norm, LM head, confidence, router, flag) is in tail_kernels.hip.
+#include "tr_internal.h"
+
+namespace tr {
+
+// ------------------------------------------------------------------ small device helpers
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// nearest-even rounding of fp32 to bf16 (NaN kept quiet)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ void load8(const float *p, float (&w)[8])
+{
+    float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+}
+
+__device__ __forceinline__ void load8(const bf16_t *p, float (&w)[8])
+{
+    uint4 v = *reinterpret_cast<const uint4 *>(p);
+    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ float widen(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float widen(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+
+__device__ __forceinline__ void store_kv(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_kv(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Dot products of NR weight rows with MB activation rows over K (K % 8 == 0). With NORM the weights are
+// multiplied by the RMSNorm gain and the activations' sums of squares are accumulated alongside, so that
+// W.(g*x/rms) = (W*g).x / rms needs no separate normalisation pass. Results are valid in every lane.
+template <typename WT, int NR, int MB, bool NORM>
+__device__ __forceinline__ void wave_dots(const WT *const (&wrow)[NR], const WT *gain, const float *const (&xrow)[MB], int K,
+                                          float (&acc)[NR][MB], float (&ss)[MB])
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        ss[m] = 0.f;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) acc[r][m] = 0.f;
+    }
+    for (int k = lane * 8; k < K; k += 512) {
+        float w[NR][8];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) load8(wrow[r] + k, w[r]);
+        if (NORM) {
+            float g[8];
+            load8(gain + k, g);
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) w[r][i] *= g[i];
+        }
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            float xv[8];
+            load8(xrow[m] + k, xv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (NORM) ss[m] = fmaf(xv[i], xv[i], ss[m]);
+#pragma unroll
+                for (int r = 0; r < NR; ++r) acc[r][m] = fmaf(w[r][i], xv[i], acc[r][m]);
+            }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        if (NORM) ss[m] = wave_sum(ss[m]);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) acc[r][m] = wave_sum(acc[r][m]);
+    }
+}
+
+// ------------------------------------------------------------------ row metadata
+
+struct SetupArgs {
+    int n;
+    int slot[256], tok[256], pos[256];
+};
+
+__global__ void setup_rows_kernel(SetupArgs a, int *d_slot, int *d_tok, int *d_pos, int base)
+{
+    int i = threadIdx.x;
+    if (i < a.n) {
+        d_slot[base + i] = a.slot[i];
+        d_tok[base + i] = a.tok[i];
+        d_pos[base + i] = a.pos[i];
+    }
+}
+
+void launch_setup_rows(hipStream_t s, int n, const int *slots, const int *toks, const int *poss, int *d_slot, int *d_tok, int *d_pos)
+{
+    for (int base = 0; base < n; base += 256) {
+        SetupArgs a;
+        a.n = n - base < 256 ? n - base : 256;
+        for (int i = 0; i < a.n; ++i) {
+            a.slot[i] = slots[base + i];
+            a.tok[i] = toks[base + i];
+            a.pos[i] = poss[base + i];
+        }
+        hipLaunchKernelGGL(setup_rows_kernel, dim3(1), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base);
+    }
+}
+
+__global__ void iota_rows_kernel(int n, int slot, int *d_slot, int *d_pos)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        d_slot[i] = slot;
+        d_pos[i] = i;
+    }
+}
+
+void launch_iota_rows(hipStream_t s, int n, int slot, int *d_slot, int *d_pos)
+{
+    hipLaunchKernelGGL(iota_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, slot, d_slot, d_pos);
+}
+
+__global__ void reset_counters_kernel(long long *counters, int slot)
+{
+    counters[2 * slot + threadIdx.x] = 0;
+}
+
+void launch_reset_counters(hipStream_t s, long long *counters, int slot)
+{
+    hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(2), 0, s, counters, slot);
+}
+
+// ------------------------------------------------------------------ embedding lookup: x[r] = E[tok[r]]
+
+template <typename WT>
+__global__ void embed_kernel(const WT *E, const int *tok, int d, float *x)
+{
+    const int r = blockIdx.x;
+    const WT *e = E + (size_t)tok[r] * d;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) x[(size_t)r * d + j] = widen(e, j);
+}
+
+void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, int d, float *x)
+{
+    if (wdt == DT_F32) hipLaunchKernelGGL(embed_kernel<float>, dim3(R), dim3(256), 0, s, (const float *)E, tok, d, x);
+    else hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(R), dim3(256), 0, s, (const bf16_t *)E, tok, d, x);
+}
+
+// ------------------------------------------------------------------ attention input:
+// n = RMSNorm(x; ln1); [q|k|v] = W n + b; rotate q and k at the row's position; append k, v to the cache.
+// One wavefront computes the two output rows (j, j + dh/2) of one head that the rotation pairs up.
+
+template <typename WT, typename KT, int MB>
+__global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float *x, Rows rows, const float2 *rope, float *q, KT *kc,
+                                                  KT *vc)
+{
+    const int half = D.dh / 2;
+    const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (pair >= (D.Hq + 2 * D.Hkv) * half) return;
+    const int hh = pair / half, j = pair % half;
+    const WT *W, *bias;
+    int head;  // head index inside its own matrix
+    if (hh < D.Hq) { W = (const WT *)w.wq; bias = (const WT *)w.bq; head = hh; }
+    else if (hh < D.Hq + D.Hkv) { W = (const WT *)w.wk; bias = (const WT *)w.bk; head = hh - D.Hq; }
+    else { W = (const WT *)w.wv; bias = (const WT *)w.bv; head = hh - D.Hq - D.Hkv; }
+    const int n1 = head * D.dh + j, n2 = n1 + half;
+    const WT *const wrow[2] = {W + (size_t)n1 * D.d, W + (size_t)n2 * D.d};
+    const int r0 = blockIdx.y * MB;
+    const float *xrow[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) xrow[m] = x + (size_t)(r0 + m < rows.n ? r0 + m : r0) * D.d;
+    float acc[2][MB], ss[MB];
+    wave_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, xrow, D.d, acc, ss);
+    if ((threadIdx.x & 63) != 0) return;
+    const float b1 = bias ? widen(bias, n1) : 0.f, b2 = bias ? widen(bias, n2) : 0.f;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const int r = r0 + m;
+        if (r >= rows.n) break;
+        const float rstd = 1.0f / sqrtf(ss[m] / (float)D.d + D.eps);
+        float y1 = acc[0][m] * rstd + b1, y2 = acc[1][m] * rstd + b2;
+        const int pos = rows.pos[r];
+        if (hh < D.Hq + D.Hkv) {
+            const float2 cs = rope[(size_t)pos * half + j];
+            const float o1 = y1 * cs.x - y2 * cs.y, o2 = y2 * cs.x + y1 * cs.y;
+            y1 = o1; y2 = o2;
+        }
+        if (hh < D.Hq) {
+            q[(size_t)r * D.qw + n1] = y1;
+            q[(size_t)r * D.qw + n2] = y2;
+        } else {
+            KT *dst = (hh < D.Hq + D.Hkv ? kc : vc) + (((size_t)rows.slot[r] * D.Hkv + head) * D.max_seq + pos) * D.dh;
+            store_kv(dst + j, y1);
+            store_kv(dst + j + half, y2);
+        }
+    }
+}
+
+template <typename WT, typename KT>
+static void launch_qkv_t(hipStream_t s, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q, void *kc,
+                         void *vc)
+{
+    const int pairs = (D.Hq + 2 * D.Hkv) * (D.dh / 2);
+    if (rows.n == 1)
+        hipLaunchKernelGGL((qkv_kernel<WT, KT, 1>), dim3((pairs + 3) / 4, 1), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
+    else
+        hipLaunchKernelGGL((qkv_kernel<WT, KT, 4>), dim3((pairs + 3) / 4, (rows.n + 3) / 4), dim3(256), 0, s, D, w, x, rows, rope, q,
+                           (KT *)kc, (KT *)vc);
+}
+
+void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q,
+                void *kc, void *vc)
+{
+    if (wdt == DT_F32 && kdt == DT_F32) launch_qkv_t<float, float>(s, D, w, x, rows, rope, q, kc, vc);
+    else if (wdt == DT_F32) launch_qkv_t<float, bf16_t>(s, D, w, x, rows, rope, q, kc, vc);
+    else if (kdt == DT_F32) launch_qkv_t<bf16_t, float>(s, D, w, x, rows, rope, q, kc, vc);
+    else launch_qkv_t<bf16_t, bf16_t>(s, D, w, x, rows, rope, q, kc, vc);
+}
+
+// ------------------------------------------------------------------ grouped-query attention over the cache.
+// One workgroup (4 wavefronts) serves one query row, one kv head (all G query heads of its group share the
+// K/V loads) and one contiguous chunk of the context ("split"); partial (max, sum, weighted V) triples of
+// the splits are merged afterwards. Scores: one key per lane. Weighted sum of V: 8 dims per lane, 16-byte loads.
+
+constexpr int MAXG = 8;
+
+template <typename KT, int DH>
+__global__ __launch_bounds__(256) void attn_kernel(Dims D, const float *q, const KT *kc, const KT *vc, Rows rows, int chunk, int nsplit,
+                                                   float *part, float *att)
+{
+    constexpr int DG = DH / 8;    // lanes that cover one V row
+    constexpr int KG = 64 / DG;   // V rows covered by one wavefront load
+    __shared__ float q_s[MAXG][DH];
+    __shared__ float p_s[4][MAXG][64];
+    __shared__ float red_o[4][MAXG][DH];
+    __shared__ float red_m[4][MAXG], red_l[4][MAXG];
+
+    const int r = blockIdx.x, g = blockIdx.y, sp = blockIdx.z;
+    const int G = D.G, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int ctx = rows.pos[r] + 1;
+    const int j0 = sp * chunk, j1 = min(ctx, j0 + chunk);
+    const float scale = 1.0f / sqrtf((float)DH);
+    for (int i = threadIdx.x; i < G * DH; i += 256) q_s[i / DH][i % DH] = q[(size_t)r * D.qw + (size_t)g * G * DH + i] * scale;
+    __syncthreads();
+
+    const KT *Kb = kc + ((size_t)rows.slot[r] * D.Hkv + g) * (size_t)D.max_seq * DH;
+    const KT *Vb = vc + ((size_t)rows.slot[r] * D.Hkv + g) * (size_t)D.max_seq * DH;
+    const int dgrp = lane % DG, kgrp = lane / DG;
+
+    float m[MAXG], l[MAXG], o[MAXG][8];
+#pragma unroll
+    for (int h = 0; h < MAXG; ++h) {
+        m[h] = -INFINITY; l[h] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[h][i] = 0.f;
+    }
+
+    for (int t0 = j0; t0 < j1; t0 += 256) {
+        const int t = t0 + wave * 64;          // first key of this wavefront's tile
+        const bool tile_live = t < j1;         // wavefront-uniform
+        if (tile_live) {
+            const int j = t + lane;
+            const bool valid = j < j1;
+            float sc[MAXG];
+#pragma unroll
+            for (int h = 0; h < MAXG; ++h) sc[h] = 0.f;
+            if (valid) {
+                const KT *kr = Kb + (size_t)j * DH;
+#pragma unroll 2
+                for (int e = 0; e < DH; e += 8) {
+                    float kv[8];
+                    load8(kr + e, kv);
+#pragma unroll
+                    for (int h = 0; h < MAXG; ++h)
+                        if (h < G) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) sc[h] = fmaf(q_s[h][e + i], kv[i], sc[h]);
+                        }
+                }
+            }
+#pragma unroll
+            for (int h = 0; h < MAXG; ++h)
+                if (h < G) {
+                    const float s = valid ? sc[h] : -INFINITY;
+                    const float mn = fmaxf(m[h], wave_max(s));     // finite: lane 0 of a live tile is valid
+                    const float p = valid ? expf(s - mn) : 0.f;
+                    const float corr = expf(m[h] - mn);            // exp(-inf) = 0 on the first tile
+                    l[h] = l[h] * corr + wave_sum(p);
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) o[h][i] *= corr;
+                    m[h] = mn;
+                    p_s[wave][h][lane] = p;
+                }
+        }
+        __syncthreads();
+        if (tile_live) {
+#pragma unroll 2
+            for (int i = 0; i < 64 / KG; ++i) {
+                const int jj = i * KG + kgrp, j = t + jj;
+                if (j < j1) {
+                    float vv[8];
+                    load8(Vb + (size_t)j * DH + dgrp * 8, vv);
+#pragma unroll
+                    for (int h = 0; h < MAXG; ++h)
+                        if (h < G) {
+                            const float p = p_s[wave][h][jj];
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vv[e], o[h][e]);
+                        }
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // sum the per-key-group partial outputs inside the wavefront, then merge the 4 wavefronts
+#pragma unroll
+    for (int h = 0; h < MAXG; ++h)
+        if (h < G) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float v = o[h][e];
+#pragma unroll
+                for (int off = DG; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+                o[h][e] = v;
+            }
+            if (kgrp == 0) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) red_o[wave][h][dgrp * 8 + e] = o[h][e];
+            }
+            if (lane == 0) { red_m[wave][h] = m[h]; red_l[wave][h] = l[h]; }
+        }
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * DH; i += 256) {
+        const int h = i / DH, e = i % DH;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2) M = fmaxf(M, red_m[w2][h]);
+        float Lsum = 0.f, O = 0.f;
+        if (M > -INFINITY) {
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+                const float c = expf(red_m[w2][h] - M);
+                Lsum += red_l[w2][h] * c;
+                O += red_o[w2][h][e] * c;
+            }
+        }
+        const int head = g * G + h;
+        if (nsplit == 1) {
+            att[(size_t)r * D.qw + head * DH + e] = O / Lsum;
+        } else {
+            float *pp = part + (((size_t)r * D.Hq + head) * nsplit + sp) * (DH + 2);
+            pp[e] = O;
+            if (e == 0) { pp[DH] = M; pp[DH + 1] = Lsum; }
+        }
+    }
+}
+
+template <int DH>
+__global__ void attn_merge_kernel(Dims D, const float *part, int nsplit, float *att)
+{
+    const int r = blockIdx.x, head = blockIdx.y, e = threadIdx.x;
+    const float *pp = part + ((size_t)r * D.Hq + head) * nsplit * (DH + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, pp[s * (DH + 2) + DH]);
+    float Lsum = 0.f, O = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const float ms = pp[s * (DH + 2) + DH];
+        if (ms > -INFINITY) {
+            const float c = expf(ms - M);
+            Lsum += pp[s * (DH + 2) + DH + 1] * c;
+            O += pp[s * (DH + 2) + e] * c;
+        }
+    }
+    att[(size_t)r * D.qw + head * DH + e] = O / Lsum;
+}
+
+template <typename KT, int DH>
+static void launch_attention_t(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
+                               float *part, size_t part_floats, float *att)
+{
+    // enough splits to give the chip ~1024 workgroups, at least 256 keys each, bounded by the partials buffer
+    int nsplit = (1024 + rows.n * D.Hkv - 1) / (rows.n * D.Hkv);
+    const int by_ctx = (max_ctx + 255) / 256;
+    if (nsplit > by_ctx) nsplit = by_ctx;
+    const size_t per_split = (size_t)rows.n * D.Hq * (DH + 2);
+    if ((size_t)nsplit * per_split > part_floats) nsplit = (int)(part_floats / per_split);
+    if (nsplit < 1) nsplit = 1;
+    int chunk = (max_ctx + nsplit - 1) / nsplit;
+    chunk = (chunk + 255) / 256 * 256;
+    nsplit = (max_ctx + chunk - 1) / chunk;
+    hipLaunchKernelGGL((attn_kernel<KT, DH>), dim3(rows.n, D.Hkv, nsplit), dim3(256), 0, s, D, q, (const KT *)kc, (const KT *)vc, rows, chunk,
+                       nsplit, part, att);
+    if (nsplit > 1) hipLaunchKernelGGL((attn_merge_kernel<DH>), dim3(rows.n, D.Hq), dim3(DH), 0, s, D, part, nsplit, att);
+}
+
+void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
+                      float *part, size_t part_floats, float *att)
+{
+    if (D.dh == 64) {
+        if (kdt == DT_F32) launch_attention_t<float, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
+        else launch_attention_t<bf16_t, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
+    } else {
+        if (kdt == DT_F32) launch_attention_t<float, 128>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
+        else launch_attention_t<bf16_t, 128>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
+    }
+}
+
+// ------------------------------------------------------------------ attention output: x += Wo a
+
+template <typename WT, int MB>
+__global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, const float *in, int R, int N, int K, float *x)
+{
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const WT *const wrow[1] = {W + (size_t)n * K};
+    const int r0 = blockIdx.y * MB;
+    const float *xrow[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) xrow[m] = in + (size_t)(r0 + m < R ? r0 + m : r0) * K;
+    float acc[1][MB], ss[MB];
+    wave_dots<WT, 1, MB, false>(wrow, nullptr, xrow, K, acc, ss);
+    if ((threadIdx.x & 63) != 0) return;
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+        if (r0 + m < R) x[(size_t)(r0 + m) * N + n] += acc[0][m];
+}
+
+template <typename WT>
+static void launch_residual_gemv(hipStream_t s, const void *W, const float *in, int R, int N, int K, float *x)
+{
+    if (R == 1) hipLaunchKernelGGL((residual_gemv_kernel<WT, 1>), dim3((N + 3) / 4, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4>), dim3((N + 3) / 4, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+}
+
+void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, int R, float *x)
+{
+    if (wdt == DT_F32) launch_residual_gemv<float>(s, wo, att, R, D.d, D.qw, x);
+    else launch_residual_gemv<bf16_t>(s, wo, att, R, D.d, D.qw, x);
+}
+
+void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x)
+{
+    if (wdt == DT_F32) launch_residual_gemv<float>(s, wd, h, R, D.d, D.F, x);
+    else launch_residual_gemv<bf16_t>(s, wd, h, R, D.d, D.F, x);
+}
+
+// ------------------------------------------------------------------ FFN input: h = silu(Wg n) * (Wu n), n = RMSNorm(x; ln2)
+
+template <typename WT, int MB>
+__global__ __launch_bounds__(256) void gateup_kernel(Dims D, const WT *wg, const WT *wu, const WT *gain, const float *x, int R, float *h)
+{
+    const int f = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (f >= D.F) return;
+    const WT *const wrow[2] = {wg + (size_t)f * D.d, wu + (size_t)f * D.d};
+    const int r0 = blockIdx.y * MB;
+    const float *xrow[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) xrow[m] = x + (size_t)(r0 + m < R ? r0 + m : r0) * D.d;
+    float acc[2][MB], ss[MB];
+    wave_dots<WT, 2, MB, true>(wrow, gain, xrow, D.d, acc, ss);
+    if ((threadIdx.x & 63) != 0) return;
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+        if (r0 + m < R) {
+            const float rstd = 1.0f / sqrtf(ss[m] / (float)D.d + D.eps);
+            const float gt = acc[0][m] * rstd, up = acc[1][m] * rstd;
+            h[(size_t)(r0 + m) * D.F + f] = gt / (1.0f + expf(-gt)) * up;
+        }
+}
+
+void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h)
+{
+    const dim3 g1((D.F + 3) / 4, 1), g4((D.F + 3) / 4, (R + 3) / 4);
+    if (wdt == DT_F32) {
+        if (R == 1) hipLaunchKernelGGL((gateup_kernel<float, 1>), g1, dim3(256), 0, s, D, (const float *)w.wg, (const float *)w.wu, (const float *)w.ln2, x, R, h);
+        else hipLaunchKernelGGL((gateup_kernel<float, 4>), g4, dim3(256), 0, s, D, (const float *)w.wg, (const float *)w.wu, (const float *)w.ln2, x, R, h);
+    } else {
+        if (R == 1) hipLaunchKernelGGL((gateup_kernel<bf16_t, 1>), g1, dim3(256), 0, s, D, (const bf16_t *)w.wg, (const bf16_t *)w.wu, (const bf16_t *)w.ln2, x, R, h);
+        else hipLaunchKernelGGL((gateup_kernel<bf16_t, 4>), g4, dim3(256), 0, s, D, (const bf16_t *)w.wg, (const bf16_t *)w.wu, (const bf16_t *)w.ln2, x, R, h);
+    }
+}
+
+// ------------------------------------------------------------------ cache import: [layer][kv_head][len][dh] -> the slot's cache
+
+template <typename KT>
+__global__ void load_kv_kernel(Dims D, int slot, int len, const KT *k, const KT *v, KT *kc, KT *vc)
+{
+    const size_t per_layer_src = (size_t)D.Hkv * len * D.dh;
+    const size_t total = (size_t)D.L * per_layer_src;
+    const size_t layer_stride = (size_t)D.max_batch * D.Hkv * D.max_seq * D.dh;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t l = i / per_layer_src, rem = i % per_layer_src;
+        const size_t g = rem / ((size_t)len * D.dh), pe = rem % ((size_t)len * D.dh);
+        const size_t dst = l * layer_stride + ((size_t)slot * D.Hkv + g) * D.max_seq * D.dh + pe;
+        kc[dst] = k[i];
+        vc[dst] = v[i];
+    }
+}
+
+void launch_load_kv(hipStream_t s, int kdt, const Dims &D, int slot, int len, const void *k, const void *v, void *kc, void *vc)
+{
+    const size_t total = (size_t)D.L * D.Hkv * len * D.dh;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    if (kdt == DT_F32) hipLaunchKernelGGL(load_kv_kernel<float>, dim3(blocks), dim3(256), 0, s, D, slot, len, (const float *)k, (const float *)v, (float *)kc, (float *)vc);
+    else hipLaunchKernelGGL(load_kv_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, D, slot, len, (const bf16_t *)k, (const bf16_t *)v, (bf16_t *)kc, (bf16_t *)vc);
+}
+
+}  // namespace tr

@@ -1,0 +1,253 @@
+// Routing tail for gfx950: final RMSNorm -> LM head over the whole vocabulary -> softmax confidence and greedy
+// argmax -> MLP router on the exposed last-layer hidden state -> route flag -> per-slot counters.
+//
+// The rule (arxiv 2504.07878, Section 3.1): a token is routed to the large model when the router's score,
+// computed by an MLP classifier on the last-layer hidden state of the small model, falls below the threshold;
+// the small_only mode disables routing. The hidden state is an output of the model (Section 3.3, Figure 4).
+//
+// The logits are never written to memory unless a debug buffer is given: every workgroup streams one slice
+// of the head matrix, keeps a running (max, lowest argmax, sum of exponentials) per row, and the slices'
+// triples are merged in a fixed order, so results are bit-identical from run to run.
+#include "tr_internal.h"
+
+namespace tr {
+
+__device__ __forceinline__ float t_bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
+__device__ __forceinline__ float t_widen(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float t_widen(const bf16_t *p, size_t i) { return t_bf16_to_f32(p[i]); }
+
+__device__ __forceinline__ void t_load8(const float *p, float (&w)[8])
+{
+    float4 a = *reinterpret_cast<const float4 *>(p), b = *reinterpret_cast<const float4 *>(p + 4);
+    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+}
+
+__device__ __forceinline__ void t_load8(const bf16_t *p, float (&w)[8])
+{
+    uint4 v = *reinterpret_cast<const uint4 *>(p);
+    w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+    w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+    w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+    w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ float t_wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+constexpr int SLICE_ROWS = 128;  // vocabulary rows per workgroup (32 per wavefront)
+int tail_slice_rows() { return SLICE_ROWS; }
+
+// ------------------------------------------------------------------ final RMSNorm; exposes the hidden state
+
+template <typename WT>
+__global__ __launch_bounds__(256) void tail_norm_kernel(int d, float eps, const WT *gain, const float *x, const int *gather, float *hn,
+                                                        float *hidden, int hidden_tap)
+{
+    __shared__ float red[4];
+    const int i = blockIdx.x;
+    const float *xr = x + (size_t)(gather ? gather[i] : i) * d;
+    float ss = 0.f;
+    for (int j = threadIdx.x; j < d; j += 256) ss = fmaf(xr[j], xr[j], ss);
+    ss = t_wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float rstd = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+    for (int j = threadIdx.x; j < d; j += 256) {
+        const float v = xr[j] * rstd * t_widen(gain, j);
+        hn[(size_t)i * d + j] = v;
+        if (hidden) hidden[(size_t)i * d + j] = hidden_tap == 0 ? v : xr[j];
+    }
+}
+
+// ------------------------------------------------------------------ LM head slice: running softmax statistics
+
+// part[slice][row] = {max, argmax (as int bits), sum exp(z - max), unused}
+template <typename WT, int MB>
+__global__ __launch_bounds__(256) void lmhead_kernel(const WT *head, int V, int d, const float *hn, int n, float4 *part, float *logits)
+{
+    __shared__ float4 wpart[4][MB];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r0 = blockIdx.y * MB;
+    const float *xrow[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) xrow[m] = hn + (size_t)(r0 + m < n ? r0 + m : r0) * d;
+    float mx[MB], sum[MB];
+    int idx[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) { mx[m] = -INFINITY; sum[m] = 0.f; idx[m] = 0x7fffffff; }
+
+    const int v_begin = blockIdx.x * SLICE_ROWS + wave * (SLICE_ROWS / 4);
+    for (int v0 = v_begin; v0 < v_begin + SLICE_ROWS / 4 && v0 < V; v0 += 4) {
+        float acc[4][MB];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int m = 0; m < MB; ++m) acc[r][m] = 0.f;
+        for (int k = lane * 8; k < d; k += 512) {
+            float w[4][8];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) t_load8(head + (size_t)(v0 + r < V ? v0 + r : v0) * d + k, w[r]);
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                float xv[8];
+                t_load8(xrow[m] + k, xv);
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[r][m] = fmaf(w[r][i], xv[i], acc[r][m]);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int v = v0 + r;
+            if (v < V) {
+#pragma unroll
+                for (int m = 0; m < MB; ++m) {
+                    const float z = t_wave_sum(acc[r][m]);
+                    if (logits && lane == 0 && r0 + m < n) logits[(size_t)(r0 + m) * V + v] = z;
+                    if (z > mx[m]) {   // strict: the lowest index wins ties
+                        sum[m] = sum[m] * expf(mx[m] - z) + 1.0f;
+                        mx[m] = z; idx[m] = v;
+                    } else {
+                        sum[m] += expf(z - mx[m]);
+                    }
+                }
+            }
+        }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int m = 0; m < MB; ++m) wpart[wave][m] = make_float4(mx[m], __int_as_float(idx[m]), sum[m], 0.f);
+    }
+    __syncthreads();
+    if (threadIdx.x < MB && r0 + threadIdx.x < n) {
+        const int m = threadIdx.x;
+        float M = -INFINITY; int I = 0x7fffffff;
+        for (int w = 0; w < 4; ++w) {      // wavefronts hold increasing vocabulary ranges
+            const float4 p = wpart[w][m];
+            if (p.x > M) { M = p.x; I = __float_as_int(p.y); }
+        }
+        float S = 0.f;
+        for (int w = 0; w < 4; ++w) {
+            const float4 p = wpart[w][m];
+            if (p.x > -INFINITY) S += p.z * expf(p.x - M);
+        }
+        part[(size_t)blockIdx.x * n + r0 + m] = make_float4(M, __int_as_float(I), S, 0.f);
+    }
+}
+
+// ------------------------------------------------------------------ merge the slices, run the router, set the flag
+
+template <typename WT>
+__global__ __launch_bounds__(256) void tail_final_kernel(int d, int rh, TailArgs t)
+{
+    __shared__ float s_m[256];
+    __shared__ int s_i[256];
+    __shared__ float s_s[256];
+    __shared__ float s_h[1024];
+    const int i = blockIdx.x, tid = threadIdx.x, n = t.n;
+    const float4 *part = reinterpret_cast<const float4 *>(t.part);
+
+    // 1. global maximum and the lowest index that attains it
+    float M = -INFINITY; int I = 0x7fffffff;
+    for (int s = tid; s < t.nslices; s += 256) {
+        const float4 p = part[(size_t)s * n + i];
+        const int pi = __float_as_int(p.y);
+        if (p.x > M || (p.x == M && pi < I)) { M = p.x; I = pi; }
+    }
+    s_m[tid] = M; s_i[tid] = I;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) {
+            const float m2 = s_m[tid + o]; const int i2 = s_i[tid + o];
+            if (m2 > s_m[tid] || (m2 == s_m[tid] && i2 < s_i[tid])) { s_m[tid] = m2; s_i[tid] = i2; }
+        }
+        __syncthreads();
+    }
+    M = s_m[0]; I = s_i[0];
+    // 2. sum of exponentials relative to the global maximum (fixed summation tree)
+    float S = 0.f;
+    for (int s = tid; s < t.nslices; s += 256) {
+        const float4 p = part[(size_t)s * n + i];
+        if (p.x > -INFINITY) S += p.z * expf(p.x - M);
+    }
+    s_s[tid] = S;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) s_s[tid] += s_s[tid + o];
+        __syncthreads();
+    }
+    const float conf = 1.0f / s_s[0];
+
+    // 3. router: score = sigmoid(w2 . relu(W1 u + b1) + b2) on the tapped hidden state
+    float score = 1.0f;
+    int flag = 0;
+    if (rh > 0) {
+        const float *u = t.hidden_tap == 0 ? t.hn + (size_t)i * d : t.x + (size_t)(t.gather ? t.gather[i] : i) * d;
+        const WT *w1 = (const WT *)t.r_w1, *b1 = (const WT *)t.r_b1, *w2 = (const WT *)t.r_w2, *b2 = (const WT *)t.r_b2;
+        const int wave = tid >> 6, lane = tid & 63;
+        for (int j = wave; j < rh; j += 4) {
+            float acc = 0.f;
+            for (int k = lane * 8; k < d; k += 512) {
+                float w[8], xv[8];
+                t_load8(w1 + (size_t)j * d + k, w);
+                t_load8(u + k, xv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc = fmaf(w[e], xv[e], acc);
+            }
+            acc = t_wave_sum(acc);
+            if (lane == 0) {
+                const float h = acc + (b1 ? t_widen(b1, j) : 0.f);
+                s_h[j] = h > 0.f ? h : 0.f;
+            }
+        }
+        __syncthreads();
+        float a = 0.f;
+        for (int j = tid; j < rh; j += 256) a = fmaf(t_widen(w2, j), s_h[j], a);
+        s_s[tid] = a;
+        __syncthreads();
+        for (int o = 128; o > 0; o >>= 1) {
+            if (tid < o) s_s[tid] += s_s[tid + o];
+            __syncthreads();
+        }
+        const float pre = s_s[0] + (b2 ? t_widen(b2, 0) : 0.f);
+        score = 1.0f / (1.0f + expf(-pre));
+        if (t.mode == 0) flag = t.route_dir == 0 ? (score < t.threshold) : (score > t.threshold);
+    }
+    if (tid == 0) {
+        t.token[i] = I; t.conf[i] = conf; t.score[i] = score; t.flag[i] = flag;
+        if (t.counters && t.counter_mode) {
+            long long *c = t.counters + 2 * (size_t)t.slot[i];
+            if (t.counter_mode == 1) { c[0] += 1; c[1] += flag; }
+            else { c[0] = 1; c[1] = flag; }
+        }
+    }
+}
+
+template <typename WT>
+static void launch_tail_t(hipStream_t s, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1)
+{
+    hipLaunchKernelGGL(tail_norm_kernel<WT>, dim3(t.n), dim3(256), 0, s, D.d, D.eps, (const WT *)t.final_norm, t.x, t.gather, t.hn, t.hidden,
+                       t.hidden_tap);
+    if (ev0) (void)hipEventRecord(ev0, s);
+    if (t.n == 1)
+        hipLaunchKernelGGL((lmhead_kernel<WT, 1>), dim3(t.nslices, 1), dim3(256), 0, s, (const WT *)t.head, D.V, D.d, t.hn, t.n,
+                           (float4 *)t.part, t.logits);
+    else
+        hipLaunchKernelGGL((lmhead_kernel<WT, 4>), dim3(t.nslices, (t.n + 3) / 4), dim3(256), 0, s, (const WT *)t.head, D.V, D.d, t.hn, t.n,
+                           (float4 *)t.part, t.logits);
+    if (ev1) (void)hipEventRecord(ev1, s);
+    hipLaunchKernelGGL(tail_final_kernel<WT>, dim3(t.n), dim3(256), 0, s, D.d, D.rh, t);
+}
+
+void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1)
+{
+    if (wdt == DT_F32) launch_tail_t<float>(s, D, t, ev0, ev1);
+    else launch_tail_t<bf16_t>(s, D, t, ev0, ev1);
+}
+
+}  // namespace tr

@@ -1,0 +1,428 @@
+// Host side of libtokroute: the C ABI declared in include/tokroute.h. Validates arguments, keeps the per-slot
+// bookkeeping (sequence lengths on the host; n_generated / n_routed counters on the device, next to the
+// flags that feed them) and enqueues the fixed kernel sequence of a step on the caller's stream.
+#include "../../include/tokroute.h"
+#include "tr_internal.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace tr;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layout {
+    size_t kc, vc, rope, counters, slot, tok, pos, gather, x, q, att, h, hn, attn_part, tail_part, total;
+    size_t attn_part_floats;
+    int max_rows, nslices;
+};
+
+size_t elem_size(int dt) { return dt == TR_F32 ? 4 : 2; }
+
+int check_config(const tr_config *c)
+{
+    if (!c) return TR_ERR_INVALID_ARG;
+    if (c->n_layers < 1 || c->d_model < 8 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->d_ffn < 8 || c->vocab < 1 || c->max_batch < 1 ||
+        c->max_seq < 1)
+        return TR_ERR_SHAPE;
+    if (c->head_dim != 64 && c->head_dim != 128) return TR_ERR_SHAPE;           // attention kernels are built for these
+    if (c->n_q_heads % c->n_kv_heads || c->n_q_heads / c->n_kv_heads > 8) return TR_ERR_SHAPE;
+    if (c->d_model % 8 || c->d_ffn % 8) return TR_ERR_SHAPE;                    // 16-byte loads along the reduction dimension
+    if (c->router_hidden < 0 || c->router_hidden > 1024) return TR_ERR_SHAPE;
+    if ((c->dtype != TR_F32 && c->dtype != TR_BF16) || (c->kv_dtype != TR_F32 && c->kv_dtype != TR_BF16)) return TR_ERR_INVALID_ARG;
+    if (c->route_dir != TR_ROUTE_IF_BELOW && c->route_dir != TR_ROUTE_IF_ABOVE) return TR_ERR_INVALID_ARG;
+    if (c->hidden_tap != TR_POST_FINAL_NORM && c->hidden_tap != TR_PRE_FINAL_NORM) return TR_ERR_INVALID_ARG;
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return TR_ERR_INVALID_ARG;
+    if ((long long)c->max_batch * c->max_seq > (1ll << 31)) return TR_ERR_CAPACITY;
+    return TR_OK;
+}
+
+Layout make_layout(const tr_config *c)
+{
+    Layout L{};
+    const size_t kvw = (size_t)c->n_kv_heads * c->head_dim, qw = (size_t)c->n_q_heads * c->head_dim;
+    const size_t cache = (size_t)c->n_layers * c->max_batch * c->max_seq * kvw * elem_size(c->kv_dtype);
+    L.max_rows = c->max_batch > c->max_seq ? c->max_batch : c->max_seq;   // a decode batch or one whole prompt
+    L.nslices = (c->vocab + tail_slice_rows() - 1) / tail_slice_rows();
+    const size_t R = (size_t)L.max_rows;
+    // room for up to 32 context splits of a full decode batch
+    L.attn_part_floats = (size_t)c->max_batch * c->n_q_heads * 32 * (c->head_dim + 2);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    L.kc = take(cache); L.vc = take(cache);
+    L.rope = take((size_t)c->max_seq * (c->head_dim / 2) * sizeof(float2));
+    L.counters = take((size_t)c->max_batch * 2 * sizeof(long long));
+    L.slot = take(R * 4); L.tok = take(R * 4); L.pos = take(R * 4); L.gather = take((size_t)c->max_batch * 4);
+    L.x = take(R * c->d_model * 4); L.q = take(R * qw * 4); L.att = take(R * qw * 4); L.h = take(R * c->d_ffn * 4);
+    L.hn = take((size_t)c->max_batch * c->d_model * 4);
+    L.attn_part = take(L.attn_part_floats * 4);
+    L.tail_part = take((size_t)L.nslices * c->max_batch * sizeof(float4));
+    L.total = off;
+    return L;
+}
+
+}  // namespace
+
+struct tr_ctx {
+    tr_config c;
+    Dims D;
+    Layout lay;
+    char *ws;
+    std::vector<LayerW> layers;
+    const void *tok_emb, *head, *final_norm, *r_w1, *r_b1, *r_w2, *r_b2;
+    std::vector<int> len;   // -1 = never prefilled
+    float threshold;
+    int mode;
+    std::string err;
+    // kernel timing
+    bool profile = false;
+    std::vector<hipEvent_t> ev;   // pairs
+    size_t ev_used = 0;
+    double prof_ms = 0.0;
+    long long prof_launches = 0;
+
+    template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
+    void *kc_layer(int l) const { return ws + lay.kc + (size_t)l * c.max_batch * c.max_seq * D.kvw * elem_size(c.kv_dtype); }
+    void *vc_layer(int l) const { return ws + lay.vc + (size_t)l * c.max_batch * c.max_seq * D.kvw * elem_size(c.kv_dtype); }
+};
+
+namespace {
+
+int fail(tr_ctx *ctx, int code, const char *msg)
+{
+    if (ctx) ctx->err = msg;
+    return code;
+}
+
+int fail_hip(tr_ctx *ctx, hipError_t e, const char *what)
+{
+    if (ctx) ctx->err = std::string(what) + ": " + hipGetErrorString(e);
+    return TR_ERR_HIP;
+}
+
+bool check_out(const tr_out *o) { return o && o->token && o->conf && o->score && o->flag; }
+
+bool slots_ok(const tr_ctx *ctx, int n, const int32_t *slots)
+{
+    if (n < 1 || n > ctx->c.max_batch) return false;
+    std::vector<char> seen((size_t)ctx->c.max_batch, 0);
+    for (int i = 0; i < n; ++i) {
+        if (slots[i] < 0 || slots[i] >= ctx->c.max_batch || seen[(size_t)slots[i]]) return false;
+        seen[(size_t)slots[i]] = 1;
+    }
+    return true;
+}
+
+void drain_profile(tr_ctx *ctx)
+{
+    for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
+        float ms = 0.f;
+        if (hipEventSynchronize(ctx->ev[i + 1]) == hipSuccess && hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]) == hipSuccess) {
+            ctx->prof_ms += ms;
+            ctx->prof_launches += 1;
+        }
+    }
+    ctx->ev_used = 0;
+}
+
+void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1)
+{
+    *e0 = *e1 = nullptr;
+    if (!ctx->profile) return;
+    if (ctx->ev_used + 2 > ctx->ev.size()) drain_profile(ctx);
+    *e0 = ctx->ev[ctx->ev_used];
+    *e1 = ctx->ev[ctx->ev_used + 1];
+    ctx->ev_used += 2;
+}
+
+// All layers over the rows currently described by the device row arrays.
+void run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
+{
+    const Dims &D = ctx->D;
+    const Layout &L = ctx->lay;
+    Rows rows{ctx->at<int>(L.slot), ctx->at<int>(L.pos), ctx->at<int>(L.tok), R};
+    float *x = ctx->at<float>(L.x), *q = ctx->at<float>(L.q), *att = ctx->at<float>(L.att), *h = ctx->at<float>(L.h);
+    launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
+    for (int l = 0; l < D.L; ++l) {
+        const LayerW &w = ctx->layers[(size_t)l];
+        launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+        launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
+                         R <= ctx->c.max_batch ? L.attn_part_floats : 0, att);
+        launch_oproj(s, ctx->c.dtype, D, w.wo, att, R, x);
+        launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
+        launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
+    }
+}
+
+TailArgs tail_args(tr_ctx *ctx, const tr_out *out, int out_offset, int n)
+{
+    const Layout &L = ctx->lay;
+    TailArgs t{};
+    t.head = ctx->head; t.final_norm = ctx->final_norm;
+    t.r_w1 = ctx->r_w1; t.r_b1 = ctx->r_b1; t.r_w2 = ctx->r_w2; t.r_b2 = ctx->r_b2;
+    t.n = n;
+    t.hn = ctx->at<float>(L.hn);
+    t.part = ctx->at<float>(L.tail_part);
+    t.nslices = L.nslices; t.slice_rows = tail_slice_rows();
+    t.token = out->token + out_offset; t.conf = out->conf + out_offset; t.score = out->score + out_offset; t.flag = out->flag + out_offset;
+    t.hidden = out->hidden ? out->hidden + (size_t)out_offset * ctx->D.d : nullptr;
+    t.logits = out->logits ? out->logits + (size_t)out_offset * ctx->D.V : nullptr;
+    t.counters = ctx->at<long long>(L.counters);
+    t.threshold = ctx->threshold; t.route_dir = ctx->c.route_dir; t.mode = ctx->mode; t.hidden_tap = ctx->c.hidden_tap;
+    return t;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t tr_workspace_bytes(const tr_config *cfg)
+{
+    if (check_config(cfg) != TR_OK) return 0;
+    return make_layout(cfg).total;
+}
+
+int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t workspace_bytes, tr_ctx **out)
+{
+    if (!cfg || !w || !workspace || !out) return TR_ERR_INVALID_ARG;
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if ((uintptr_t)workspace % ALIGN) return TR_ERR_INVALID_ARG;
+    if (!w->tok_emb || !w->final_norm || (!cfg->tie_lm_head && !w->lm_head)) return TR_ERR_INVALID_ARG;
+    if (!w->ln1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->ln2 || !w->wg || !w->wu || !w->wd) return TR_ERR_INVALID_ARG;
+    if (cfg->router_hidden > 0 && (!w->r_w1 || !w->r_w2)) return TR_ERR_INVALID_ARG;
+    Layout lay = make_layout(cfg);
+    if (workspace_bytes < lay.total) return TR_ERR_CAPACITY;
+
+    tr_ctx *ctx = new tr_ctx();
+    ctx->c = *cfg;
+    ctx->lay = lay;
+    ctx->ws = static_cast<char *>(workspace);
+    Dims &D = ctx->D;
+    D.L = cfg->n_layers; D.d = cfg->d_model; D.Hq = cfg->n_q_heads; D.Hkv = cfg->n_kv_heads; D.dh = cfg->head_dim; D.F = cfg->d_ffn;
+    D.V = cfg->vocab; D.qw = D.Hq * D.dh; D.kvw = D.Hkv * D.dh; D.G = D.Hq / D.Hkv; D.rh = cfg->router_hidden;
+    D.max_batch = cfg->max_batch; D.max_seq = cfg->max_seq; D.eps = cfg->rms_eps;
+    bool aligned = true;
+    auto chk = [&](const void *p) { if (p && (uintptr_t)p % 16) aligned = false; return p; };
+    ctx->layers.resize((size_t)D.L);
+    for (int l = 0; l < D.L; ++l) {
+        LayerW &lw = ctx->layers[(size_t)l];
+        lw.ln1 = chk(w->ln1[l]); lw.wq = chk(w->wq[l]); lw.wk = chk(w->wk[l]); lw.wv = chk(w->wv[l]);
+        lw.bq = w->bq ? w->bq[l] : nullptr; lw.bk = w->bk ? w->bk[l] : nullptr; lw.bv = w->bv ? w->bv[l] : nullptr;
+        lw.wo = chk(w->wo[l]); lw.ln2 = chk(w->ln2[l]); lw.wg = chk(w->wg[l]); lw.wu = chk(w->wu[l]); lw.wd = chk(w->wd[l]);
+        if (!lw.ln1 || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.ln2 || !lw.wg || !lw.wu || !lw.wd) { delete ctx; return TR_ERR_INVALID_ARG; }
+    }
+    ctx->tok_emb = chk(w->tok_emb);
+    ctx->head = chk(cfg->tie_lm_head ? w->tok_emb : w->lm_head);
+    ctx->final_norm = chk(w->final_norm);
+    ctx->r_w1 = chk(w->r_w1); ctx->r_b1 = w->r_b1; ctx->r_w2 = w->r_w2; ctx->r_b2 = w->r_b2;
+    if (!aligned) { delete ctx; return TR_ERR_INVALID_ARG; }
+    ctx->len.assign((size_t)cfg->max_batch, -1);
+    ctx->threshold = cfg->threshold;
+    ctx->mode = TR_JOINT;
+
+    // rotary table: cos/sin of pos * theta^(-2j/dh), computed in double
+    const int half = D.dh / 2;
+    std::vector<float2> rope((size_t)cfg->max_seq * half);
+    for (int j = 0; j < half; ++j) {
+        const double inv = std::pow((double)cfg->rope_theta, -2.0 * j / (double)D.dh);
+        for (int p = 0; p < cfg->max_seq; ++p) {
+            const double a = (double)p * inv;
+            rope[(size_t)p * half + j] = make_float2((float)std::cos(a), (float)std::sin(a));
+        }
+    }
+    hipError_t e = hipMemcpy(ctx->ws + lay.rope, rope.data(), rope.size() * sizeof(float2), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemset(ctx->ws + lay.counters, 0, (size_t)cfg->max_batch * 2 * sizeof(long long));
+    if (e != hipSuccess) { delete ctx; return TR_ERR_HIP; }
+    *out = ctx;
+    return TR_OK;
+}
+
+void tr_destroy(tr_ctx *ctx)
+{
+    if (!ctx) return;
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+    delete ctx;
+}
+
+const char *tr_last_error(const tr_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int tr_set_threshold(tr_ctx *ctx, float t)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    ctx->threshold = t;
+    return TR_OK;
+}
+
+int tr_set_mode(tr_ctx *ctx, int32_t mode)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (mode != TR_JOINT && mode != TR_SMALL_ONLY) return fail(ctx, TR_ERR_INVALID_ARG, "tr_set_mode: unknown mode");
+    ctx->mode = mode;
+    return TR_OK;
+}
+
+int tr_seq_len(const tr_ctx *ctx, int32_t slot, int32_t *len)
+{
+    if (!ctx || !len || slot < 0 || slot >= ctx->c.max_batch) return TR_ERR_INVALID_ARG;
+    *len = ctx->len[(size_t)slot] < 0 ? 0 : ctx->len[(size_t)slot];
+    return TR_OK;
+}
+
+int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (slot < 0 || slot >= ctx->c.max_batch) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_truncate: slot out of range");
+    if (ctx->len[(size_t)slot] < 0) return fail(ctx, TR_ERR_STATE, "tr_seq_truncate: slot was never filled");
+    if (new_len < 0 || new_len > ctx->len[(size_t)slot]) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_truncate: new_len outside [0, len]");
+    ctx->len[(size_t)slot] = new_len;
+    return TR_OK;
+}
+
+int tr_counters_ptr(const tr_ctx *ctx, const int64_t **dev_counters)
+{
+    if (!ctx || !dev_counters) return TR_ERR_INVALID_ARG;
+    *dev_counters = reinterpret_cast<const int64_t *>(ctx->ws + ctx->lay.counters);
+    return TR_OK;
+}
+
+int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *tokens_flat, const int32_t *offsets,
+               const tr_out *out)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (!slots || !tokens_flat || !offsets || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: null argument");
+    if (!slots_ok(ctx, n, slots)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: bad slot list");
+    if (offsets[0] != 0) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: offsets[0] must be 0");
+    for (int i = 0; i < n; ++i) {
+        const long long T = (long long)offsets[i + 1] - offsets[i];
+        if (T < 1) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: empty prompt");
+        if (T > ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_prefill: prompt longer than max_seq");
+    }
+    for (int i = 0; i < offsets[n]; ++i)
+        if (tokens_flat[i] < 0 || tokens_flat[i] >= ctx->c.vocab) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: token out of range");
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const Layout &L = ctx->lay;
+    for (int i = 0; i < n; ++i) {
+        const int T = offsets[i + 1] - offsets[i], slot = slots[i];
+        // pageable source: the copy has left the caller's array when this returns
+        hipError_t e = hipMemcpyAsync(ctx->at<int>(L.tok), tokens_flat + offsets[i], (size_t)T * 4, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return fail_hip(ctx, e, "tr_prefill: token upload");
+        launch_iota_rows(s, T, slot, ctx->at<int>(L.slot), ctx->at<int>(L.pos));
+        run_layers(ctx, s, T, T);
+        TailArgs t = tail_args(ctx, out, i, 1);
+        t.x = ctx->at<float>(L.x) + (size_t)(T - 1) * ctx->D.d;
+        t.gather = nullptr;
+        t.slot = ctx->at<int>(L.slot);   // every row holds this slot
+        t.counter_mode = 2;
+        hipEvent_t e0, e1;
+        next_events(ctx, &e0, &e1);
+        launch_tail(s, ctx->c.dtype, ctx->D, t, e0, e1);
+        ctx->len[(size_t)slot] = T;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_prefill: launch");
+    return TR_OK;
+}
+
+int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens, const tr_out *out)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (!slots || !in_tokens || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: null argument");
+    if (!slots_ok(ctx, n, slots)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: bad slot list");
+    int max_ctx = 0;
+    std::vector<int> pos((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        if (in_tokens[i] < 0 || in_tokens[i] >= ctx->c.vocab) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: token out of range");
+        const int len = ctx->len[(size_t)slots[i]];
+        if (len < 0) return fail(ctx, TR_ERR_STATE, "tr_decode_step: slot was never prefilled");
+        if (len >= ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_decode_step: slot is full");
+        pos[(size_t)i] = len;
+        if (len + 1 > max_ctx) max_ctx = len + 1;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const Layout &L = ctx->lay;
+    launch_setup_rows(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos));
+    run_layers(ctx, s, n, max_ctx);
+    TailArgs t = tail_args(ctx, out, 0, n);
+    t.x = ctx->at<float>(L.x);
+    t.gather = nullptr;
+    t.slot = ctx->at<int>(L.slot);
+    t.counter_mode = 1;
+    hipEvent_t e0, e1;
+    next_events(ctx, &e0, &e1);
+    launch_tail(s, ctx->c.dtype, ctx->D, t, e0, e1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_decode_step: launch");
+    for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] += 1;
+    return TR_OK;
+}
+
+int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (!x || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_tail: null argument");
+    if (n < 1 || n > ctx->c.max_batch) return fail(ctx, TR_ERR_INVALID_ARG, "tr_tail: n outside [1, max_batch]");
+    if ((uintptr_t)x % 16) return fail(ctx, TR_ERR_INVALID_ARG, "tr_tail: x must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    TailArgs t = tail_args(ctx, out, 0, n);
+    t.x = x;
+    t.gather = nullptr;
+    t.slot = nullptr;
+    t.counters = nullptr;
+    t.counter_mode = 0;
+    hipEvent_t e0, e1;
+    next_events(ctx, &e0, &e1);
+    launch_tail(s, ctx->c.dtype, ctx->D, t, e0, e1);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_tail: launch");
+    return TR_OK;
+}
+
+int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, const void *k, const void *v)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (!k || !v) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_load_kv: null argument");
+    if (slot < 0 || slot >= ctx->c.max_batch) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_load_kv: slot out of range");
+    if (len < 1 || len > ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_seq_load_kv: len outside [1, max_seq]");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    launch_load_kv(s, ctx->c.kv_dtype, ctx->D, slot, len, k, v, ctx->ws + ctx->lay.kc, ctx->ws + ctx->lay.vc);
+    launch_reset_counters(s, ctx->at<long long>(ctx->lay.counters), slot);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_seq_load_kv: launch");
+    ctx->len[(size_t)slot] = len;
+    return TR_OK;
+}
+
+int tr_profile_enable(tr_ctx *ctx, int32_t on)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (on && ctx->ev.empty()) {
+        ctx->ev.resize(512);
+        for (auto &e : ctx->ev) {
+            hipError_t rc = hipEventCreate(&e);
+            if (rc != hipSuccess) { ctx->ev.clear(); return fail_hip(ctx, rc, "tr_profile_enable: hipEventCreate"); }
+        }
+    }
+    if (on && !ctx->profile) { ctx->prof_ms = 0.0; ctx->prof_launches = 0; ctx->ev_used = 0; }
+    if (!on && ctx->profile) drain_profile(ctx);
+    ctx->profile = on != 0;
+    return TR_OK;
+}
+
+int tr_profile_read(tr_ctx *ctx, double *ms_total, int64_t *launches)
+{
+    if (!ctx || !ms_total || !launches) return TR_ERR_INVALID_ARG;
+    drain_profile(ctx);
+    *ms_total = ctx->prof_ms;
+    *launches = ctx->prof_launches;
+    return TR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+"""The C-ABI library loads and exports every symbol include/tokroute.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "tokroute.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tr_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = declared_functions()
+    for must in ("tr_create", "tr_prefill", "tr_decode_step", "tr_tail", "tr_workspace_bytes", "tr_destroy"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2504_07878_amd import tokroute
+    lib = ctypes.CDLL(tokroute.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in tokroute.h but not exported"
+    assert sorted(tokroute.EXPORTS) == declared_functions()
+
+
+def test_workspace_sizing_and_config_validation_run_on_the_host():
+    from paper_2504_07878_amd import synth, tokroute
+    lib = tokroute.load_library()
+    s = synth.SLM_0P5B
+
+    def cfg(**kw):
+        d = s.asdict(); d.update(kw)
+        return tokroute.tr_config(d["n_layers"], d["d_model"], d["n_q_heads"], d["n_kv_heads"], d["head_dim"], d["d_ffn"], d["vocab"],
+                                  d["rms_eps"], d["rope_theta"], d["dtype"], d["kv_dtype"], d["tie_lm_head"], d["router_hidden"],
+                                  d["threshold"], 0, 0, d.get("max_batch", 64), d.get("max_seq", 1536))
+
+    n = lib.tr_workspace_bytes(ctypes.byref(cfg()))
+    cache = 2 * 24 * 64 * 1536 * 128 * 2
+    assert cache <= n < cache + (1 << 30)
+    assert lib.tr_workspace_bytes(ctypes.byref(cfg(max_batch=128))) > n
+    for bad in (dict(head_dim=48), dict(n_kv_heads=3), dict(d_model=900), dict(dtype=5), dict(max_seq=0), dict(router_hidden=5000)):
+        assert lib.tr_workspace_bytes(ctypes.byref(cfg(**bad))) == 0
+    assert lib.tr_workspace_bytes(None) == 0

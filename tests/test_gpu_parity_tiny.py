@@ -1,0 +1,186 @@
+"""GPU parity on the tiny fp32 model: the HIP path, called through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_07878_amd import synth
+from parity import compare_outputs, assert_rows_close
+
+pytestmark = pytest.mark.gpu
+SEED = 7878
+
+
+@pytest.fixture(scope="module")
+def tr():
+    from paper_2504_07878_amd import tokroute
+    tokroute.load_library()
+    return tokroute
+
+
+@pytest.fixture(scope="module")
+def tiny_weights():
+    return synth.make_weights(synth.TINY, SEED)
+
+
+def test_tiny_prefill_and_free_running_greedy_decode(tr, tro, tiny_weights):
+    """Workload 1: batch 1, 32-token uniform prompt, 16 greedy steps, free-running: tokens must equal the oracle's."""
+    s = synth.TINY
+    g = tr.Model(s.asdict(), tiny_weights, 1, 64)
+    o = tro.Model(s.asdict(), tiny_weights, 1, 64)
+    prompt = synth.prompt_tokens(SEED, "cfg1.prompt", 32, s.vocab)
+    go = g.prefill([0], [prompt], want_logits=True).cpu()
+    oo = o.prefill([0], [prompt], want_logits=True)
+    assert compare_outputs(go, oo, s.dtype, s.threshold, "prefill") == 0
+    gt, ot = int(go.token[0]), int(oo.token[0])
+    for step in range(16):
+        assert gt == ot, f"free-running tokens diverged at step {step}"
+        go = g.decode_step([0], [gt], want_logits=True).cpu()
+        oo = o.decode_step([0], [ot], want_logits=True)
+        assert compare_outputs(go, oo, s.dtype, s.threshold, f"step {step}") == 0
+        gt, ot = int(go.token[0]), int(oo.token[0])
+    assert g.seq_len(0) == o.seq_len(0) == 48
+    assert tuple(g.counters()[0]) == o.counters(0)
+
+
+def test_tiny_ragged_batch_with_biases_and_gains(tr, tro):
+    """Several slots, prompts of different lengths (1 .. several attention tiles), non-zero biases and non-unit gains."""
+    s = synth.TINY
+    w = synth.make_weights(s, SEED + 1, std=0.05, bias_std=0.05, gain_std=0.1)
+    B, max_seq = 7, 700
+    g = tr.Model(s.asdict(), w, B, max_seq)
+    o = tro.Model(s.asdict(), w, B, max_seq)
+    lens = [1, 2, 63, 64, 65, 300, 640]
+    prompts = [synth.prompt_tokens(SEED, f"rag{i}", n, s.vocab) for i, n in enumerate(lens)]
+    slots = [3, 0, 6, 1, 5, 2, 4]
+    go = g.prefill(slots, prompts, want_logits=True).cpu()
+    oo = o.prefill(slots, prompts, want_logits=True)
+    compare_outputs(go, oo, s.dtype, s.threshold, "ragged prefill")
+    for step in range(5):
+        toks = oo.token.copy()                      # teacher-forced with the oracle's tokens
+        order = np.roll(np.arange(B), step)         # the order of slots in a call is free
+        go = g.decode_step([slots[i] for i in order], toks[order], want_logits=True).cpu()
+        o2 = o.decode_step([slots[i] for i in order], toks[order], want_logits=True)
+        compare_outputs(go, o2, s.dtype, s.threshold, f"ragged step {step}")
+        inv = np.argsort(order)
+        oo = type("O", (), dict(token=o2.token[inv]))()
+    for i, slot in enumerate(slots):
+        assert g.seq_len(slot) == o.seq_len(slot) == lens[i] + 5
+    cnt = g.counters()
+    for slot in slots:
+        assert tuple(cnt[slot]) == o.counters(slot)
+
+
+def test_tiny_subset_of_slots_and_cache_contents(tr, tro, tiny_weights):
+    s = synth.TINY
+    g = tr.Model(s.asdict(), tiny_weights, 4, 128)
+    o = tro.Model(s.asdict(), tiny_weights, 4, 128)
+    prompts = [synth.prompt_tokens(SEED, f"sub{i}", 20 + 7 * i, s.vocab) for i in range(4)]
+    g.prefill([0, 1, 2, 3], prompts); o.prefill([0, 1, 2, 3], prompts)
+    # step only two of the four
+    go = g.decode_step([2, 0], [5, 9], want_logits=True).cpu(); oo = o.decode_step([2, 0], [5, 9], want_logits=True)
+    compare_outputs(go, oo, s.dtype, s.threshold, "subset step")
+    assert [g.seq_len(i) for i in range(4)] == [o.seq_len(i) for i in range(4)] == [21, 27, 35, 41]
+    # the other slots are untouched: stepping them now gives what the oracle gives
+    go = g.decode_step([1, 3], [7, 8], want_logits=True).cpu(); oo = o.decode_step([1, 3], [7, 8], want_logits=True)
+    compare_outputs(go, oo, s.dtype, s.threshold, "other slots")
+
+
+def test_tiny_error_paths_leave_state_unchanged(tr, tiny_weights):
+    s = synth.TINY
+    g = tr.Model(s.asdict(), tiny_weights, 2, 16)
+    g.prefill([0], [[1, 2, 3]])
+    before = (g.seq_len(0), g.seq_len(1), g.counters().copy())
+    cases = [(lambda: g.decode_step([1], [0]), tr.ERR_STATE),
+             (lambda: g.decode_step([0, 0], [1, 1]), tr.ERR_INVALID_ARG),
+             (lambda: g.decode_step([0], [s.vocab]), tr.ERR_INVALID_ARG),
+             (lambda: g.decode_step([0], [-1]), tr.ERR_INVALID_ARG),
+             (lambda: g.decode_step([2], [0]), tr.ERR_INVALID_ARG),
+             (lambda: g.prefill([1], [list(range(17))]), tr.ERR_CAPACITY),
+             (lambda: g.prefill([1], [[]]), tr.ERR_INVALID_ARG),
+             (lambda: g.seq_truncate(0, 4), tr.ERR_INVALID_ARG),
+             (lambda: g.seq_truncate(1, 0), tr.ERR_STATE),
+             (lambda: g.set_mode(7), tr.ERR_INVALID_ARG)]
+    for fn, code in cases:
+        with pytest.raises(tr.TokrouteError) as e:
+            fn()
+        assert e.value.code == code, (code, e.value)
+        assert (g.seq_len(0), g.seq_len(1)) == before[:2] and np.array_equal(g.counters(), before[2])
+    while g.seq_len(0) < 16:
+        g.decode_step([0], [1])
+    with pytest.raises(tr.TokrouteError) as e:
+        g.decode_step([0], [1])
+    assert e.value.code == tr.ERR_CAPACITY and g.seq_len(0) == 16
+
+
+def test_tiny_modes_threshold_and_options(tr, tro, tiny_weights):
+    s = synth.TINY
+    prompt = synth.prompt_tokens(SEED, "modes", 12, s.vocab)
+    g = tr.Model(s.asdict(), tiny_weights, 1, 64); o = tro.Model(s.asdict(), tiny_weights, 1, 64)
+    g.prefill([0], [prompt]); o.prefill([0], [prompt])
+    for thr, mode in ((0.0, tr.JOINT), (1.0, tr.JOINT), (1.0, tr.SMALL_ONLY), (0.5, tr.JOINT)):
+        g.set_threshold(thr); o.set_threshold(thr); g.set_mode(mode); o.set_mode(mode)
+        go = g.decode_step([0], [3], want_logits=True).cpu(); oo = o.decode_step([0], [3], want_logits=True)
+        compare_outputs(go, oo, s.dtype, thr, f"thr {thr} mode {mode}", joint=mode == tr.JOINT)
+        assert int(go.flag[0]) == (1 if (thr == 1.0 and mode == tr.JOINT) else 0 if thr != 0.5 else int(go.flag[0]))
+    assert tuple(g.counters()[0]) == o.counters(0)
+    # pre-norm hidden tap and the opposite routing direction
+    g2 = tr.Model(s.asdict(), tiny_weights, 1, 64, route_dir=tr.ROUTE_IF_ABOVE, hidden_tap=tr.PRE_FINAL_NORM)
+    o2 = tro.Model(s.asdict(), tiny_weights, 1, 64, route_dir=tro.ROUTE_IF_ABOVE, hidden_tap=tro.PRE_FINAL_NORM)
+    go = g2.prefill([0], [prompt], want_logits=True).cpu(); oo = o2.prefill([0], [prompt], want_logits=True)
+    compare_outputs(go, oo, s.dtype, s.threshold, "options", route_dir_below=False)
+
+
+def test_tiny_truncate_and_replace_token(tr, tro, tiny_weights):
+    """A token from the large model replaces the small model's next input; rolling back needs no recompute."""
+    s = synth.TINY
+    g = tr.Model(s.asdict(), tiny_weights, 1, 64); o = tro.Model(s.asdict(), tiny_weights, 1, 64)
+    prompt = synth.prompt_tokens(SEED, "trunc", 30, s.vocab)
+    g.prefill([0], [prompt]); o.prefill([0], [prompt])
+    a = g.decode_step([0], [11], want_logits=True).cpu()
+    g.decode_step([0], [12]); g.seq_truncate(0, 30)
+    b = g.decode_step([0], [11], want_logits=True).cpu()
+    assert np.array_equal(a.logits, b.logits) and a.token[0] == b.token[0]   # deterministic, bit for bit
+    o.decode_step([0], [11])
+    compare_outputs(g.decode_step([0], [99], want_logits=True).cpu(), o.decode_step([0], [99], want_logits=True), s.dtype, s.threshold, "after replace")
+
+
+def test_tiny_load_kv_and_no_router_untied_head(tr, tro):
+    s = synth.TINY.with_(router_hidden=0, tie_lm_head=0, kv_dtype=synth.BF16)
+    w = synth.make_weights(s, SEED + 2)
+    g = tr.Model(s.asdict(), w, 2, 300); o = tro.Model(s.asdict(), w, 2, 300)
+    k, v = synth.kv_fill(SEED, "kvfill", s, 257)
+    o.load_kv(1, synth.bf16_bits_to_f32(k), synth.bf16_bits_to_f32(v))
+    g.load_kv(1, tr.to_device(k, synth.BF16), tr.to_device(v, synth.BF16))
+    go = g.decode_step([1], [17], want_logits=True).cpu(); oo = o.decode_step([1], [17], want_logits=True)
+    assert_rows_close(go.logits, oo.logits, 1e-4, "loaded-cache logits")
+    assert go.token[0] == oo.token[0] and go.flag[0] == 0 and go.score[0] == 1.0 and g.seq_len(1) == 258
+
+
+def test_tiny_isolated_tail(tr, tro, tiny_weights):
+    s = synth.TINY
+    g = tr.Model(s.asdict(), tiny_weights, 9, 8)
+    x = synth.hidden_rows(SEED, "tailx", 9, s.d_model, False)
+    go = g.tail(torch.from_numpy(x).cuda(), want_logits=True).cpu()
+    w = tiny_weights
+    for i in range(9):
+        hn = tro.rmsnorm(x[i], w["final_norm"], s.dtype, s.rms_eps)
+        z = tro.linear(w["tok_emb"], None, s.dtype, hn)
+        tok, conf = tro.softmax_stats(z)
+        sc = tro.router_score(hn, w["r_w1"], w["r_b1"], w["r_w2"], w["r_b2"], s.dtype)
+        assert_rows_close(go.logits[i], z, 1e-4, "tail logits"); assert_rows_close(go.hidden[i], hn, 1e-4, "tail hidden")
+        assert go.token[i] == tok and go.conf[i] == pytest.approx(conf, rel=1e-4) and go.score[i] == pytest.approx(sc, abs=1e-5)
+        assert go.flag[i] == tro.route_flag(go.score[i], s.threshold)
+    assert not g.counters().any()
+
+
+def test_tiny_run_twice_is_bit_identical(tr, tiny_weights):
+    s = synth.TINY
+    prompts = [synth.prompt_tokens(SEED, f"det{i}", 40 + 100 * i, s.vocab) for i in range(3)]
+    res = []
+    for _ in range(2):
+        g = tr.Model(s.asdict(), tiny_weights, 3, 400)
+        a = g.prefill([0, 1, 2], prompts, want_logits=True).cpu()
+        b = g.decode_step([0, 1, 2], a.token, want_logits=True).cpu()
+        res.append((a, b))
+    for x, y in zip(res[0], res[1]):
+        assert np.array_equal(x.logits, y.logits) and np.array_equal(x.score, y.score) and np.array_equal(x.conf, y.conf)
