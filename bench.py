@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode + routing-tail path on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+One "step" is one pass of the whole hot path (embedding, all decoder layers over the KV cache, routing tail)
+over one batch. The headline workload is the 0.5B-class bf16 small model at 64 concurrent sequences with
+prompt lengths uniform on [128, 1024] and a contiguous per-sequence cache; the same run also reports the
+batch-1 decode and the isolated routing tail at 256 rows. Inputs are seeded and synthetic and are resident in
+HBM when the timed region starts. Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+SEED = 7878
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def kv_bytes_per_token(s):
+    return 2 * s.n_layers * s.n_kv_heads * s.head_dim * 2   # K and V, bf16
+
+
+def weight_bytes_per_step(s):
+    d, qw, kvw, F = s.d_model, s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim, s.d_ffn
+    per_layer = d * qw + 2 * d * kvw + qw * d + 3 * d * F
+    head = s.vocab * d
+    router = s.router_hidden * d + s.router_hidden if s.router_hidden else 0
+    return 2 * (s.n_layers * per_layer + head + router)
+
+
+def time_decode(model, slots, tokens_per_step, steps, warmup, out):
+    """Warm up, roll the sequences back, then time `steps` decode steps. Returns seconds."""
+    import torch
+    base = [model.seq_len(sl) for sl in slots]
+    for i in range(warmup):
+        model.decode_step(slots, tokens_per_step[i % len(tokens_per_step)], out)
+    torch.cuda.synchronize()
+    for sl, n in zip(slots, base):
+        model.seq_truncate(sl, n)
+    model.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        model.decode_step(slots, tokens_per_step[i % len(tokens_per_step)], out)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms, launches = model.profile_read()
+    model.profile_enable(False)
+    return dt, ms, launches, base
+
+
+def cpu_baseline(s, weights, seconds_budget=20.0):
+    """The oracle, as it stands, on the host cores: decode steps of a few sequences over a synthetic cache."""
+    from oracle import tro
+    from paper_2504_07878_amd import synth
+    n_seq, ctx = 2, 576
+    o = tro.Model(s.asdict(), weights, n_seq, ctx + 64)
+    for b in range(n_seq):
+        k, v = synth.kv_fill(SEED, f"cpu.kv{b}", s, ctx)
+        o.load_kv(b, synth.bf16_bits_to_f32(k), synth.bf16_bits_to_f32(v))
+    toks = synth.prompt_tokens(SEED, "cpu.toks", 64 * n_seq, s.vocab).reshape(64, n_seq)
+    done, t0 = 0, time.perf_counter()
+    while done < 64 and time.perf_counter() - t0 < seconds_budget:
+        o.decode_step(list(range(n_seq)), toks[done])
+        done += 1
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": n_seq * done / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{done} decode steps of {n_seq} sequences at context {ctx} on a synthetic cache (0.5B-class bf16 weights, fp32 oracle)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
+        sys.exit(2)
+
+    import torch
+    from paper_2504_07878_amd import synth, tokroute
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; there is no CPU path")
+        sys.exit(2)
+    tokroute.load_library()
+    s = synth.SLM_0P5B
+    t0 = time.perf_counter()
+    weights = synth.make_weights(s, SEED)
+    log(f"weights drawn in {time.perf_counter() - t0:.1f}s")
+
+    B, MAX_SEQ = 64, 1536
+    steps = max(1, min(args.steps, 512))
+    model = tokroute.Model(s.asdict(), weights, B, MAX_SEQ)
+    lens = synth.prompt_lengths(SEED, "cfg3.lens", B, 128, 1024)
+    prompts = [synth.prompt_tokens(SEED, f"cfg3.prompt{b}", int(n), s.vocab) for b, n in enumerate(lens)]
+    slots = list(range(B))
+    out = model.outputs(B)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    model.prefill(slots, prompts, out)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    log(f"prefill of {int(lens.sum())} tokens: {prefill_s:.3f}s")
+
+    toks = synth.prompt_tokens(SEED, "cfg3.steps", 512 * B, s.vocab).reshape(512, B)
+    dt, lm_ms, lm_n, base = time_decode(model, slots, toks, steps, args.warmup, out)
+    ms_per_step = dt / steps * 1e3
+    tok_s = B * steps / dt
+    # algorithmic bytes of the timed steps: weights once per step, each sequence's cache once, new K/V written
+    kvb = kv_bytes_per_token(s)
+    ctx_sum = sum(int(n) * steps + steps * (steps - 1) // 2 for n in base)      # sum over steps and sequences of cached tokens read
+    step_bytes = weight_bytes_per_step(s) + (ctx_sum + B * steps) * kvb / steps
+    roof_tok_s = B / (step_bytes / (HBM_PEAK_GBPS * 1e9))
+    lm_bytes = 2 * s.vocab * s.d_model
+    lm_avg_s = lm_ms / 1e3 / max(lm_n, 1)
+    result = {
+        "metric": "SLM decode tokens/s at B=64 (0.5B-class bf16, routing tail included)", "value": tok_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "0.5B-class bf16 decoder + router, 64 concurrent sequences, prompts U[128,1024], contiguous KV cache, "
+                               f"{steps} decode steps after prefill (BASELINE configs[2])",
+                   "batch": B, "max_seq": MAX_SEQ, "seed": SEED, "prefill_seconds": prefill_s,
+                   "algorithmic_bytes_per_step": step_bytes, "hbm_roofline_tokens_per_s": roof_tok_s,
+                   "fraction_of_hbm_roofline": tok_s / roof_tok_s},
+        "roofline": {"bound": "hbm", "kernel": "lmhead_kernel (LM head of the routing tail)", "achieved": lm_bytes / lm_avg_s / 1e9 if lm_n else None,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": (lm_bytes / lm_avg_s / 1e9 / HBM_PEAK_GBPS) if lm_n else None,
+                     "traffic": None, "launches": lm_n, "avg_us": lm_avg_s * 1e6, "algorithmic_bytes_per_launch": lm_bytes},
+    }
+
+    if not args.no_extras:
+        extras = {}
+        # batch 1: 256-token prompt, 256 steps
+        model.seq_truncate(0, 0)
+        p1 = synth.prompt_tokens(SEED, "cfg2.prompt", 256, s.vocab)
+        out1 = model.outputs(1)
+        model.prefill([0], [p1], out1)
+        n1 = min(steps, 256)
+        dt1, ms1, l1, _ = time_decode(model, [0], toks[:, :1], n1, args.warmup, out1)
+        b1_bytes = weight_bytes_per_step(s) + (256 + (n1 - 1) / 2 + 1) * kvb
+        extras["b1_decode"] = {"tokens_per_s": n1 / dt1, "ms_per_step": dt1 / n1 * 1e3, "steps": n1,
+                               "hbm_roofline_tokens_per_s": HBM_PEAK_GBPS * 1e9 / b1_bytes,
+                               "fraction_of_hbm_roofline": (n1 / dt1) / (HBM_PEAK_GBPS * 1e9 / b1_bytes),
+                               "lmhead_avg_us": ms1 / max(l1, 1) * 1e3}
+        # isolated routing tail, 256 rows
+        tail_model = tokroute.Model(s.asdict(), model.dev, 256, 8)
+        x = torch.from_numpy(synth.hidden_rows(SEED, "cfg4.x", 256, s.d_model, True)).cuda()
+        outt = tail_model.outputs(256)
+        for _ in range(3):
+            tail_model.tail(x, outt)
+        torch.cuda.synchronize()
+        reps = 20
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            tail_model.tail(x, outt)
+        torch.cuda.synchronize()
+        dtt = (time.perf_counter() - t0) / reps
+        tail_bytes = lm_bytes + 256 * s.d_model * 4 + 2 * (s.router_hidden * s.d_model + s.router_hidden) + 256 * 16
+        extras["tail_b256"] = {"GB_per_s": tail_bytes / dtt / 1e9, "us_per_call": dtt * 1e6, "algorithmic_bytes": tail_bytes,
+                               "fraction_of_hbm_roofline": tail_bytes / dtt / 1e9 / HBM_PEAK_GBPS}
+        result["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        del model
+        torch.cuda.empty_cache()
+        result["cpu_baseline"] = cpu_baseline(s, weights)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

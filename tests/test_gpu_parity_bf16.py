@@ -1,0 +1,130 @@
+"""GPU parity on the 0.5B-class bf16 model at the benchmark's shapes: batch 1, batch 64 (ragged prompts) and the
+isolated routing tail at 256 rows. Teacher-forced: both sides are fed the oracle's token, so one near-tie cannot
+change everything after it. Run with -s to see progress lines."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_07878_amd import synth
+from parity import compare_outputs, assert_rows_close, top2_gap
+
+pytestmark = pytest.mark.gpu
+SEED = 7878
+S = synth.SLM_0P5B
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(scope="module")
+def tr():
+    from paper_2504_07878_amd import tokroute
+    tokroute.load_library()
+    return tokroute
+
+
+@pytest.fixture(scope="module")
+def weights():
+    t = time.time()
+    w = synth.make_weights(S, SEED)
+    say(f"[weights drawn in {time.time() - t:.1f}s]")
+    return w
+
+
+@pytest.fixture(scope="module")
+def dev_weights(tr, weights):
+    return {k: tr.to_device(v, S.dtype) for k, v in weights.items()}
+
+
+def test_batch1_prompt256_then_256_teacher_forced_steps(tr, tro, weights, dev_weights):
+    """Workload 2 in full."""
+    g = tr.Model(S.asdict(), dev_weights, 1, 512)
+    o = tro.Model(S.asdict(), weights, 1, 512)
+    prompt = synth.prompt_tokens(SEED, "cfg2.prompt", 256, S.vocab)
+    go = g.prefill([0], [prompt], want_logits=True).cpu()
+    oo = o.prefill([0], [prompt], want_logits=True)
+    exempt = compare_outputs(go, oo, S.dtype, S.threshold, "prefill")
+    gout = g.outputs(1, want_logits=True)
+    free_running_divergence = None
+    for step in range(256):
+        if free_running_divergence is None and go.token[0] != oo.token[0]:
+            free_running_divergence = step
+        tok = [int(oo.token[0])]
+        go = g.decode_step([0], tok, gout).cpu()
+        oo = o.decode_step([0], tok, want_logits=True)
+        exempt += compare_outputs(go, oo, S.dtype, S.threshold, f"step {step}")
+        if step % 64 == 0:
+            say(f"[b1 step {step} ok; top-2 gap {top2_gap(oo.logits[0]):.4f} score {oo.score[0]:.4f}]")
+    assert g.seq_len(0) == o.seq_len(0) == 512
+    assert tuple(g.counters()[0]) == o.counters(0) or exempt > 0
+    say(f"[b1: {exempt} exempt near-ties; first token difference at step {free_running_divergence}]")
+    assert exempt <= 8
+
+
+def test_batch64_ragged_prompts_512_steps_sampled_against_oracle(tr, tro, weights, dev_weights):
+    """Workload 3: all 64 sequences run on the GPU; three of them (shortest, median, longest prompt) are followed by
+    the oracle and compared at the first 8 steps, every 64th step and the last one."""
+    B, MAX_SEQ, STEPS = 64, 1536, 512
+    g = tr.Model(S.asdict(), dev_weights, B, MAX_SEQ)
+    lens = synth.prompt_lengths(SEED, "cfg3.lens", B, 128, 1024)
+    prompts = [synth.prompt_tokens(SEED, f"cfg3.prompt{b}", int(n), S.vocab) for b, n in enumerate(lens)]
+    order = np.argsort(lens)
+    watch = [int(order[0]), int(order[B // 2]), int(order[-1])]
+    say(f"[b64: prompt lengths min {lens.min()} max {lens.max()} sum {lens.sum()}; oracle follows slots {watch}]")
+    o = tro.Model(S.asdict(), weights, len(watch), MAX_SEQ)
+    t = time.time()
+    oo = o.prefill(list(range(len(watch))), [prompts[b] for b in watch], want_logits=True)
+    say(f"[oracle prefill {time.time() - t:.1f}s]")
+    t = time.time()
+    gout = g.outputs(B, want_logits=True)
+    go = g.prefill(list(range(B)), prompts, gout).cpu()
+    say(f"[gpu prefill {time.time() - t:.1f}s]")
+    sub = lambda h: type("O", (), {k: (None if getattr(h, k) is None else getattr(h, k)[watch]) for k in ("token", "conf", "score", "flag", "hidden", "logits")})()
+    exempt = compare_outputs(sub(go), oo, S.dtype, S.threshold, "b64 prefill")
+    rand = synth.prompt_tokens(SEED, "cfg3.steps", STEPS * B, S.vocab).reshape(STEPS, B)
+    checked = 0
+    for step in range(STEPS):
+        toks = rand[step].copy()
+        toks[watch] = oo.token                       # the watched sequences continue with the oracle's tokens
+        check = step < 8 or step % 64 == 0 or step == STEPS - 1
+        g.decode_step(list(range(B)), toks, gout)
+        oo = o.decode_step(list(range(len(watch))), toks[watch], want_logits=check)
+        if check:
+            exempt += compare_outputs(sub(gout.cpu()), oo, S.dtype, S.threshold, f"b64 step {step}")
+            checked += 1
+            say(f"[b64 step {step} ok]")
+    assert checked >= 16 and exempt <= 4
+    cnt = g.counters()
+    for i, b in enumerate(watch):
+        assert g.seq_len(b) == o.seq_len(i) == lens[b] + STEPS
+        assert cnt[b][0] == o.counters(i)[0] == STEPS + 1
+        assert abs(int(cnt[b][1]) - o.counters(i)[1]) <= 25     # routed counts differ only through scores within 1e-3 of the threshold
+
+
+def test_isolated_tail_256_rows(tr, tro, weights, dev_weights):
+    """Workload 4 in full: logits, argmax, confidence, score and flag of every row."""
+    n = 256
+    g = tr.Model(S.asdict(), dev_weights, n, 8)
+    x = synth.hidden_rows(SEED, "cfg4.x", n, S.d_model, True)
+    go = g.tail(torch.from_numpy(x).cuda(), want_logits=True).cpu()
+    exempt = 0
+    for i in range(n):
+        hn = tro.rmsnorm(x[i], weights["final_norm"], S.dtype, S.rms_eps)
+        z = tro.linear(weights["tok_emb"], None, S.dtype, hn)
+        tok, conf = tro.softmax_stats(z)
+        sc = tro.router_score(hn, weights["r_w1"], weights["r_b1"], weights["r_w2"], weights["r_b2"], S.dtype)
+        assert_rows_close(go.logits[i], z, 2e-2, f"tail row {i} logits"); assert_rows_close(go.hidden[i], hn, 2e-2, f"tail row {i} hidden")
+        assert go.conf[i] == pytest.approx(conf, rel=2e-2) and go.score[i] == pytest.approx(sc, abs=2e-3)
+        if go.token[i] != tok:
+            assert top2_gap(z) < 1e-3; exempt += 1
+        if go.flag[i] != tro.route_flag(sc, S.threshold):
+            assert abs(sc - S.threshold) < 1e-3; exempt += 1
+        assert go.flag[i] == int(go.score[i] < np.float32(S.threshold))
+    say(f"[tail: {exempt} exempt near-ties of {2 * n} decisions]")
+    assert exempt <= 12
+    # without the debug logits buffer the decisions are the same, bit for bit
+    g2 = g.tail(torch.from_numpy(x).cuda(), want_logits=False).cpu()
+    assert np.array_equal(g2.token, go.token) and np.array_equal(g2.conf, go.conf) and np.array_equal(g2.score, go.score)
