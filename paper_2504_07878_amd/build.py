@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libtokroute.so")
-SOURCES = ["tokroute_api.hip", "decode_kernels.hip", "tail_kernels.hip"]
+SOURCES = ["tokroute_api.hip", "decode_kernels.hip", "tail_kernels.hip", "mfma_kernels.hip"]
 # packed fp32 instructions are kept off: the compiler would otherwise form them from ordinary float code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-result",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

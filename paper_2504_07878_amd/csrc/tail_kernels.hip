@@ -149,6 +149,7 @@ __global__ __launch_bounds__(256) void tail_final_kernel(int d, int rh, TailArgs
     __shared__ int s_i[256];
     __shared__ float s_s[256];
     __shared__ float s_h[1024];
+    __shared__ float s_u[4096];
     const int i = blockIdx.x, tid = threadIdx.x, n = t.n;
     const float4 *part = reinterpret_cast<const float4 *>(t.part);
 
@@ -189,21 +190,24 @@ __global__ __launch_bounds__(256) void tail_final_kernel(int d, int rh, TailArgs
     if (rh > 0) {
         const float *u = t.hidden_tap == 0 ? t.hn + (size_t)i * d : t.x + (size_t)(t.gather ? t.gather[i] : i) * d;
         const WT *w1 = (const WT *)t.r_w1, *b1 = (const WT *)t.r_b1, *w2 = (const WT *)t.r_w2, *b2 = (const WT *)t.r_b2;
-        const int wave = tid >> 6, lane = tid & 63;
-        for (int j = wave; j < rh; j += 4) {
-            float acc = 0.f;
-            for (int k = lane * 8; k < d; k += 512) {
-                float w[8], xv[8];
-                t_load8(w1 + (size_t)j * d + k, w);
-                t_load8(u + k, xv);
+        // one hidden unit per thread; the tapped row is staged in LDS and read as a broadcast
+        for (int k = tid; k < d; k += 256) s_u[k] = u[k];
+        __syncthreads();
+        for (int j = tid; j < rh; j += 256) {
+            const WT *wr = w1 + (size_t)j * d;
+            float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll 4
+            for (int k = 0; k < d; k += 8) {
+                float w[8];
+                t_load8(wr + k, w);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) acc = fmaf(w[e], xv[e], acc);
+                for (int e = 0; e < 8; e += 2) {
+                    acc0 = fmaf(w[e], s_u[k + e], acc0);
+                    acc1 = fmaf(w[e + 1], s_u[k + e + 1], acc1);
+                }
             }
-            acc = t_wave_sum(acc);
-            if (lane == 0) {
-                const float h = acc + (b1 ? t_widen(b1, j) : 0.f);
-                s_h[j] = h > 0.f ? h : 0.f;
-            }
+            const float h = acc0 + acc1 + (b1 ? t_widen(b1, j) : 0.f);
+            s_h[j] = h > 0.f ? h : 0.f;
         }
         __syncthreads();
         float a = 0.f;
@@ -229,25 +233,41 @@ __global__ __launch_bounds__(256) void tail_final_kernel(int d, int rh, TailArgs
 }
 
 template <typename WT>
-static void launch_tail_t(hipStream_t s, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1)
+static void launch_lmhead_gemv_t(hipStream_t s, const Dims &D, const TailArgs &t)
 {
-    hipLaunchKernelGGL(tail_norm_kernel<WT>, dim3(t.n), dim3(256), 0, s, D.d, D.eps, (const WT *)t.final_norm, t.x, t.gather, t.hn, t.hidden,
-                       t.hidden_tap);
-    if (ev0) (void)hipEventRecord(ev0, s);
     if (t.n == 1)
         hipLaunchKernelGGL((lmhead_kernel<WT, 1>), dim3(t.nslices, 1), dim3(256), 0, s, (const WT *)t.head, D.V, D.d, t.hn, t.n,
                            (float4 *)t.part, t.logits);
     else
         hipLaunchKernelGGL((lmhead_kernel<WT, 4>), dim3(t.nslices, (t.n + 3) / 4), dim3(256), 0, s, (const WT *)t.head, D.V, D.d, t.hn, t.n,
                            (float4 *)t.part, t.logits);
-    if (ev1) (void)hipEventRecord(ev1, s);
-    hipLaunchKernelGGL(tail_final_kernel<WT>, dim3(t.n), dim3(256), 0, s, D.d, D.rh, t);
 }
 
+void launch_lmhead_gemv(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
+{
+    if (wdt == DT_F32) launch_lmhead_gemv_t<float>(s, D, t);
+    else launch_lmhead_gemv_t<bf16_t>(s, D, t);
+}
+
+void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
+{
+    if (wdt == DT_F32) hipLaunchKernelGGL(tail_final_kernel<float>, dim3(t.n), dim3(256), 0, s, D.d, D.rh, t);
+    else hipLaunchKernelGGL(tail_final_kernel<bf16_t>, dim3(t.n), dim3(256), 0, s, D.d, D.rh, t);
+}
+
+// the all-streaming tail: norm, LM head slices, merge + router
 void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1)
 {
-    if (wdt == DT_F32) launch_tail_t<float>(s, D, t, ev0, ev1);
-    else launch_tail_t<bf16_t>(s, D, t, ev0, ev1);
+    if (wdt == DT_F32)
+        hipLaunchKernelGGL(tail_norm_kernel<float>, dim3(t.n), dim3(256), 0, s, D.d, D.eps, (const float *)t.final_norm, t.x, t.gather, t.hn,
+                           t.hidden, t.hidden_tap);
+    else
+        hipLaunchKernelGGL(tail_norm_kernel<bf16_t>, dim3(t.n), dim3(256), 0, s, D.d, D.eps, (const bf16_t *)t.final_norm, t.x, t.gather, t.hn,
+                           t.hidden, t.hidden_tap);
+    if (ev0) (void)hipEventRecord(ev0, s);
+    launch_lmhead_gemv(s, wdt, D, t);
+    if (ev1) (void)hipEventRecord(ev1, s);
+    launch_tail_final(s, wdt, D, t);
 }
 
 }  // namespace tr

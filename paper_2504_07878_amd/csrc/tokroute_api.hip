@@ -21,7 +21,21 @@ struct Layout {
     size_t kc, vc, rope, counters, slot, tok, pos, gather, x, q, att, h, hn, attn_part, tail_part, total;
     size_t attn_part_floats;
     int max_rows, nslices;
+    // matrix-core path: repacked weights, packed activations, split-K partials
+    bool mfma;
+    size_t wt_layers, wt_layer_stride, wt_qkv, wt_o, wt_gu, wt_d, wt_head, bias, bias_stride;
+    size_t pack_d, pack_a, pack_h, part;
 };
+
+constexpr int GEMV_MAX_ROWS = 8;   // up to this many rows the streaming GEMV kernels are used
+
+// The matrix-core kernels keep 896 columns of K per workgroup resident, and the layers with a non-linear
+// epilogue (rotary, SwiGLU, softmax statistics) cannot split K across workgroups.
+bool mfma_supported(const tr_config *c)
+{
+    return c->dtype == TR_BF16 && c->d_model % 16 == 0 && c->d_model <= 896 && c->d_ffn % 16 == 0 && (c->n_q_heads * c->head_dim) % 32 == 0 &&
+           (c->max_batch > GEMV_MAX_ROWS || c->max_seq > GEMV_MAX_ROWS);
+}
 
 size_t elem_size(int dt) { return dt == TR_F32 ? 4 : 2; }
 
@@ -34,7 +48,7 @@ int check_config(const tr_config *c)
     if (c->head_dim != 64 && c->head_dim != 128) return TR_ERR_SHAPE;           // attention kernels are built for these
     if (c->n_q_heads % c->n_kv_heads || c->n_q_heads / c->n_kv_heads > 8) return TR_ERR_SHAPE;
     if (c->d_model % 8 || c->d_ffn % 8) return TR_ERR_SHAPE;                    // 16-byte loads along the reduction dimension
-    if (c->router_hidden < 0 || c->router_hidden > 1024) return TR_ERR_SHAPE;
+    if (c->router_hidden < 0 || c->router_hidden > 1024 || (c->router_hidden > 0 && c->d_model > 4096)) return TR_ERR_SHAPE;
     if ((c->dtype != TR_F32 && c->dtype != TR_BF16) || (c->kv_dtype != TR_F32 && c->kv_dtype != TR_BF16)) return TR_ERR_INVALID_ARG;
     if (c->route_dir != TR_ROUTE_IF_BELOW && c->route_dir != TR_ROUTE_IF_ABOVE) return TR_ERR_INVALID_ARG;
     if (c->hidden_tap != TR_POST_FINAL_NORM && c->hidden_tap != TR_PRE_FINAL_NORM) return TR_ERR_INVALID_ARG;
@@ -62,7 +76,29 @@ Layout make_layout(const tr_config *c)
     L.x = take(R * c->d_model * 4); L.q = take(R * qw * 4); L.att = take(R * qw * 4); L.h = take(R * c->d_ffn * 4);
     L.hn = take((size_t)c->max_batch * c->d_model * 4);
     L.attn_part = take(L.attn_part_floats * 4);
-    L.tail_part = take((size_t)L.nslices * c->max_batch * sizeof(float4));
+    L.mfma = mfma_supported(c);
+    const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab) : 0;
+    L.tail_part = take((size_t)(L.nslices > head_wgs ? L.nslices : head_wgs) * c->max_batch * sizeof(float4));
+    if (L.mfma) {
+        const size_t d = (size_t)c->d_model, F = (size_t)c->d_ffn;
+        auto tiles = [](size_t n) { return (n + 31) / 32; };
+        const size_t tile_d = d / 16 * 1024, tile_q = qw / 16 * 1024, tile_f = F / 16 * 1024;   // bytes of one 32-row tile over K
+        size_t o2 = 0;
+        L.wt_qkv = o2; o2 += tiles(qw + 2 * kvw) * tile_d;
+        L.wt_o = o2;   o2 += tiles(d) * tile_q;
+        L.wt_gu = o2;  o2 += 2 * tiles(F) * tile_d;
+        L.wt_d = o2;   o2 += tiles(d) * tile_f;
+        L.wt_layer_stride = align_up(o2);
+        L.wt_layers = take(L.wt_layer_stride * c->n_layers);
+        L.wt_head = take(tiles((size_t)c->vocab) * tile_d);
+        L.bias_stride = align_up((qw + 2 * kvw) * 4);
+        L.bias = take(L.bias_stride * c->n_layers);
+        const size_t groups = (R + 63) / 64;
+        L.pack_d = take(groups * (d / 16) * 4 * 1024);
+        L.pack_a = take(groups * (qw / 16) * 4 * 1024);
+        L.pack_h = take(groups * (F / 16) * 4 * 1024);
+        L.part = take((size_t)MAX_SPLITS * R * d * 4);
+    }
     L.total = off;
     return L;
 }
@@ -90,6 +126,9 @@ struct tr_ctx {
     template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
     void *kc_layer(int l) const { return ws + lay.kc + (size_t)l * c.max_batch * c.max_seq * D.kvw * elem_size(c.kv_dtype); }
     void *vc_layer(int l) const { return ws + lay.vc + (size_t)l * c.max_batch * c.max_seq * D.kvw * elem_size(c.kv_dtype); }
+    char *wt(int l, size_t which) const { return ws + lay.wt_layers + (size_t)l * lay.wt_layer_stride + which; }
+    float *bias(int l) const { return reinterpret_cast<float *>(ws + lay.bias + (size_t)l * lay.bias_stride); }
+    bool use_mfma(int rows) const { return lay.mfma && rows > GEMV_MAX_ROWS; }
 };
 
 namespace {
@@ -141,23 +180,79 @@ void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1)
     ctx->ev_used += 2;
 }
 
-// All layers over the rows currently described by the device row arrays.
-void run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
+// All layers over the rows currently described by the device row arrays. Returns the number of split-K partial
+// buffers of the last down projection that still have to be added to the residual stream (matrix-core path).
+int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
 {
     const Dims &D = ctx->D;
     const Layout &L = ctx->lay;
     Rows rows{ctx->at<int>(L.slot), ctx->at<int>(L.pos), ctx->at<int>(L.tok), R};
     float *x = ctx->at<float>(L.x), *q = ctx->at<float>(L.q), *att = ctx->at<float>(L.att), *h = ctx->at<float>(L.h);
+    const size_t attn_part_floats = R <= ctx->c.max_batch ? L.attn_part_floats : 0;
     launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
+    if (!ctx->use_mfma(R)) {
+        for (int l = 0; l < D.L; ++l) {
+            const LayerW &w = ctx->layers[(size_t)l];
+            launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+            launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
+                             attn_part_floats, att);
+            launch_oproj(s, ctx->c.dtype, D, w.wo, att, R, x);
+            launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
+            launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
+        }
+        return 0;
+    }
+    const int ncb = mfma_ncb(R);
+    float *part = ctx->at<float>(L.part);
+    int pending = 0;
     for (int l = 0; l < D.L; ++l) {
         const LayerW &w = ctx->layers[(size_t)l];
-        launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+        PrepArgs p{};
+        p.x = x; p.row0 = 0; p.part = part; p.nsplit = pending; p.part_M = R; p.M = R; p.d = D.d; p.eps = D.eps;
+        p.gain = (const bf16_t *)w.ln1; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = ncb;
+        launch_prep(s, p);
+        launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
+                        ctx->kc_layer(l), ctx->vc_layer(l));
         launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
-                         R <= ctx->c.max_batch ? L.attn_part_floats : 0, att);
-        launch_oproj(s, ctx->c.dtype, D, w.wo, att, R, x);
-        launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
-        launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
+                         attn_part_floats, att);
+        launch_pack(s, att, R, D.qw, ctx->at<uint4>(L.pack_a), ncb);
+        launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
+        p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
+        launch_prep(s, p);
+        launch_gemm_swiglu(s, D, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), R, ctx->at<uint4>(L.pack_h));
+        launch_gemm_partial(s, ctx->wt(l, L.wt_d), ctx->at<uint4>(L.pack_h), D.F, D.d, R, part, &pending);
     }
+    return pending;
+}
+
+// The routing tail on n rows of the residual stream x starting at row0. `pending` split-K partials (rows indexed
+// like x, part_M rows per split) are added first.
+void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pending, int part_M)
+{
+    const Dims &D = ctx->D;
+    const Layout &L = ctx->lay;
+    hipEvent_t e0, e1;
+    next_events(ctx, &e0, &e1);
+    if (!ctx->lay.mfma || (pending == 0 && !ctx->use_mfma(t.n))) {
+        t.x = x + (size_t)row0 * D.d;
+        launch_tail(s, ctx->c.dtype, D, t, e0, e1);
+        return;
+    }
+    PrepArgs p{};
+    p.x = x; p.row0 = row0; p.part = ctx->at<float>(L.part); p.nsplit = pending; p.part_M = part_M; p.M = t.n; p.d = D.d; p.eps = D.eps;
+    p.gain = (const bf16_t *)ctx->final_norm; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = mfma_ncb(t.n);
+    p.hn = t.hn; p.hidden = t.hidden; p.hidden_tap = t.hidden_tap;
+    launch_prep(s, p);
+    t.x = x + (size_t)row0 * D.d;
+    if (e0) (void)hipEventRecord(e0, s);
+    if (ctx->use_mfma(t.n)) {
+        t.nslices = lmhead_mfma_wgs(D.V);
+        launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits);
+    } else {
+        launch_lmhead_gemv(s, ctx->c.dtype, D, t);
+    }
+    if (e1) (void)hipEventRecord(e1, s);
+    launch_tail_final(s, ctx->c.dtype, D, t);
 }
 
 TailArgs tail_args(tr_ctx *ctx, const tr_out *out, int out_offset, int n)
@@ -239,6 +334,26 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     }
     hipError_t e = hipMemcpy(ctx->ws + lay.rope, rope.data(), rope.size() * sizeof(float2), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.counters, 0, (size_t)cfg->max_batch * 2 * sizeof(long long));
+    if (e == hipSuccess && lay.mfma) {
+        // one-time repack of the bf16 matrices into matrix-core tiles; q|k|v are concatenated, gate/up interleaved
+        for (int l = 0; l < D.L; ++l) {
+            const LayerW &lw = ctx->layers[(size_t)l];
+            launch_repack(nullptr, lw.wq, D.qw, D.d, ctx->wt(l, lay.wt_qkv), 0, 1);
+            launch_repack(nullptr, lw.wk, D.kvw, D.d, ctx->wt(l, lay.wt_qkv), D.qw / 32, 1);
+            launch_repack(nullptr, lw.wv, D.kvw, D.d, ctx->wt(l, lay.wt_qkv), (D.qw + D.kvw) / 32, 1);
+            launch_repack(nullptr, lw.wo, D.d, D.qw, ctx->wt(l, lay.wt_o), 0, 1);
+            launch_repack(nullptr, lw.wg, D.F, D.d, ctx->wt(l, lay.wt_gu), 0, 2);
+            launch_repack(nullptr, lw.wu, D.F, D.d, ctx->wt(l, lay.wt_gu), 1, 2);
+            launch_repack(nullptr, lw.wd, D.d, D.F, ctx->wt(l, lay.wt_d), 0, 1);
+            launch_widen_bias(nullptr, lw.bq, D.qw, ctx->bias(l));
+            launch_widen_bias(nullptr, lw.bk, D.kvw, ctx->bias(l) + D.qw);
+            launch_widen_bias(nullptr, lw.bv, D.kvw, ctx->bias(l) + D.qw + D.kvw);
+        }
+        launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1);
+        e = hipMemset(ctx->ws + lay.pack_d, 0, lay.part - lay.pack_d);   // padding rows of the packed activations stay zero
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e == hipSuccess) e = hipGetLastError();
+    }
     if (e != hipSuccess) { delete ctx; return TR_ERR_HIP; }
     *out = ctx;
     return TR_OK;
@@ -315,15 +430,12 @@ int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, c
         hipError_t e = hipMemcpyAsync(ctx->at<int>(L.tok), tokens_flat + offsets[i], (size_t)T * 4, hipMemcpyHostToDevice, s);
         if (e != hipSuccess) return fail_hip(ctx, e, "tr_prefill: token upload");
         launch_iota_rows(s, T, slot, ctx->at<int>(L.slot), ctx->at<int>(L.pos));
-        run_layers(ctx, s, T, T);
+        const int pending = run_layers(ctx, s, T, T);
         TailArgs t = tail_args(ctx, out, i, 1);
-        t.x = ctx->at<float>(L.x) + (size_t)(T - 1) * ctx->D.d;
         t.gather = nullptr;
         t.slot = ctx->at<int>(L.slot);   // every row holds this slot
         t.counter_mode = 2;
-        hipEvent_t e0, e1;
-        next_events(ctx, &e0, &e1);
-        launch_tail(s, ctx->c.dtype, ctx->D, t, e0, e1);
+        run_tail(ctx, s, t, ctx->at<float>(L.x), T - 1, pending, T);
         ctx->len[(size_t)slot] = T;
     }
     hipError_t e = hipGetLastError();
@@ -349,15 +461,12 @@ int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slot
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const Layout &L = ctx->lay;
     launch_setup_rows(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos));
-    run_layers(ctx, s, n, max_ctx);
+    const int pending = run_layers(ctx, s, n, max_ctx);
     TailArgs t = tail_args(ctx, out, 0, n);
-    t.x = ctx->at<float>(L.x);
     t.gather = nullptr;
     t.slot = ctx->at<int>(L.slot);
     t.counter_mode = 1;
-    hipEvent_t e0, e1;
-    next_events(ctx, &e0, &e1);
-    launch_tail(s, ctx->c.dtype, ctx->D, t, e0, e1);
+    run_tail(ctx, s, t, ctx->at<float>(L.x), 0, pending, n);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_decode_step: launch");
     for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] += 1;
@@ -372,14 +481,11 @@ int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_o
     if ((uintptr_t)x % 16) return fail(ctx, TR_ERR_INVALID_ARG, "tr_tail: x must be 16-byte aligned");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     TailArgs t = tail_args(ctx, out, 0, n);
-    t.x = x;
     t.gather = nullptr;
     t.slot = nullptr;
     t.counters = nullptr;
     t.counter_mode = 0;
-    hipEvent_t e0, e1;
-    next_events(ctx, &e0, &e1);
-    launch_tail(s, ctx->c.dtype, ctx->D, t, e0, e1);
+    run_tail(ctx, s, t, const_cast<float *>(x), 0, 0, n);   // no partials pending: x is only read
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_tail: launch");
     return TR_OK;

@@ -26,6 +26,24 @@ struct Rows {
     int n;
 };
 
+constexpr int MAX_SPLITS = 16;   // most split-K partial buffers a linear layer may produce
+
+// residual update + RMSNorm + pack (see mfma_kernels.hip)
+struct PrepArgs {
+    float *x;                // residual stream, row of output m is row0 + m
+    int row0;
+    const float *part;       // [nsplit][part_M][d] split-K partials to add first (rows indexed like x)
+    int nsplit, part_M;
+    int M, d;
+    float eps;
+    const bf16_t *gain;
+    uint4 *pack;             // packed hi/lo activations out
+    int ncb;
+    float *hn;               // optional fp32 copy of the normalised rows [M][d]
+    float *hidden;           // optional exposed hidden state [M][d]
+    int hidden_tap;
+};
+
 struct TailArgs {
     const void *head, *final_norm, *r_w1, *r_b1, *r_w2, *r_b2;
     const float *x;          // [n][d] residual stream (rows picked through gather when given)
@@ -57,5 +75,20 @@ void launch_load_kv(hipStream_t s, int kdt, const Dims &D, int slot, int len, co
 void launch_reset_counters(hipStream_t s, long long *counters, int slot);
 
 int tail_slice_rows();
+void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);
+void launch_lmhead_gemv(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);
+
+// matrix-core path (bf16 weights, more than a few rows)
+void launch_repack(hipStream_t s, const void *W, int N, int K, void *Wt, int dst_tile0, int dst_tile_stride);
+void launch_widen_bias(hipStream_t s, const void *b, int n, float *out);
+void launch_prep(hipStream_t s, const PrepArgs &p);
+void launch_pack(hipStream_t s, const float *in, int M, int K, void *pack, int ncb);
+int mfma_ncb(int M);
+void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out);
+void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, const void *pack, const float *bias, Rows rows, const float2 *rope,
+                     float *q, void *kc, void *vc);
+void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack);
+int lmhead_mfma_wgs(int V);
+void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits);
 
 }  // namespace tr

@@ -39,7 +39,7 @@ def test_workspace_sizing_and_config_validation_run_on_the_host():
 
     n = lib.tr_workspace_bytes(ctypes.byref(cfg()))
     cache = 2 * 24 * 64 * 1536 * 128 * 2
-    assert cache <= n < cache + (1 << 30)
+    assert cache + 988_000_000 <= n < cache + (3 << 30)   # cache + repacked weights + scratch
     assert lib.tr_workspace_bytes(ctypes.byref(cfg(max_batch=128))) > n
     for bad in (dict(head_dim=48), dict(n_kv_heads=3), dict(d_model=900), dict(dtype=5), dict(max_seq=0), dict(router_hidden=5000)):
         assert lib.tr_workspace_bytes(ctypes.byref(cfg(**bad))) == 0

@@ -184,3 +184,27 @@ def test_tiny_run_twice_is_bit_identical(tr, tiny_weights):
         res.append((a, b))
     for x, y in zip(res[0], res[1]):
         assert np.array_equal(x.logits, y.logits) and np.array_equal(x.score, y.score) and np.array_equal(x.conf, y.conf)
+
+
+@pytest.mark.parametrize("B", [9, 33, 70])
+def test_small_bf16_model_on_the_matrix_core_path(tr, tro, B):
+    """bf16 weights and more than 8 rows take the MFMA kernels: batches of 9 (one column block), 33 (two) and 70 (two row
+    groups), ragged prompts up to several 64-row groups, non-zero biases, non-unit gains."""
+    s = synth.TINY.with_(dtype=synth.BF16, kv_dtype=synth.BF16)
+    w = synth.make_weights(s, SEED + 3, std=0.05, bias_std=0.05, gain_std=0.1)
+    max_seq = 200
+    g = tr.Model(s.asdict(), w, B, max_seq); o = tro.Model(s.asdict(), w, B, max_seq)
+    lens = synth.prompt_lengths(SEED, f"mfma.lens{B}", B, 1, 150)
+    lens[0], lens[1], lens[2] = 1, 9, 150
+    prompts = [synth.prompt_tokens(SEED, f"mfma{B}.{i}", int(n), s.vocab) for i, n in enumerate(lens)]
+    slots = list(np.random.default_rng(B).permutation(B))
+    go = g.prefill(slots, prompts, want_logits=True).cpu(); oo = o.prefill(slots, prompts, want_logits=True)
+    ex = compare_outputs(go, oo, s.dtype, s.threshold, f"mfma B={B} prefill")
+    for step in range(4):
+        toks = oo.token.copy()
+        go = g.decode_step(slots, toks, want_logits=True).cpu(); oo = o.decode_step(slots, toks, want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"mfma B={B} step {step}")
+    assert ex <= 2
+    cnt = g.counters()
+    for i, slot in enumerate(slots):
+        assert g.seq_len(slot) == lens[i] + 4 and cnt[slot][0] == 5
