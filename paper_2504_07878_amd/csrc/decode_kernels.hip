@@ -404,6 +404,156 @@ __global__ void attn_merge_kernel(Dims D, const float *part, int nsplit, float *
     att[(size_t)r * D.qw + head * DH + e] = O / Lsum;
 }
 
+// ---- decode variant: one wavefront per (query row, kv head, chunk of the context), no workgroup barrier in the
+// loop. Every chunk writes an unnormalised partial (weighted V sum, running max, sum of exponentials); the merge
+// kernel combines them in a fixed order. K and V of a tile are requested together, so a tile costs one memory
+// round trip; with one tile per wavefront the whole context of a batch is in flight at once.
+
+template <typename KT> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    uint4 v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void get(float (&w)[8]) const
+    {
+        w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+        w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+        w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+        w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+};
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float *p) { a = *reinterpret_cast<const float4 *>(p); b = *reinterpret_cast<const float4 *>(p + 4); }
+    __device__ __forceinline__ void get(float (&w)[8]) const { w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w; }
+};
+
+template <typename KT, int DH>
+__global__ __launch_bounds__(256) void attn_wave_kernel(Dims D, const float *q, const KT *kc, const KT *vc, Rows rows, int chunk, int nchunks,
+                                                        float *part)
+{
+    constexpr int DG = DH / 8, KG = 64 / DG, PS = DH + 4;   // PS: floats per partial (16-byte aligned rows)
+    __shared__ float q_s[MAXG][DH];
+    __shared__ float p_s[4][MAXG][64];
+    const int r = blockIdx.x, g = blockIdx.y;
+    const int G = D.G, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const float scale = 1.0f / sqrtf((float)DH);
+    for (int i = threadIdx.x; i < G * DH; i += 256) q_s[i / DH][i % DH] = q[(size_t)r * D.qw + (size_t)g * G * DH + i] * scale;
+    __syncthreads();   // the only workgroup barrier
+    const int c = blockIdx.z * 4 + wave;
+    if (c >= nchunks) return;
+    const int ctx = rows.pos[r] + 1;
+    const int j0 = c * chunk, j1 = min(ctx, j0 + chunk);
+    const KT *Kb = kc + ((size_t)rows.slot[r] * D.Hkv + g) * (size_t)D.max_seq * DH;
+    const KT *Vb = vc + ((size_t)rows.slot[r] * D.Hkv + g) * (size_t)D.max_seq * DH;
+    const int dgrp = lane % DG, kgrp = lane / DG;
+
+    float m[MAXG], l[MAXG], o[MAXG][8];
+#pragma unroll
+    for (int h = 0; h < MAXG; ++h) {
+        m[h] = -INFINITY; l[h] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[h][i] = 0.f;
+    }
+    for (int t = j0; t < j1; t += 64) {
+        // request K (one key per lane) and V (8 dims per lane, KG keys per load) of this tile together
+        const int jk = min(t + lane, j1 - 1);
+        Raw8<KT> kraw[DH / 8], vraw[64 / KG];
+#pragma unroll
+        for (int e = 0; e < DH / 8; ++e) kraw[e].load(Kb + (size_t)jk * DH + e * 8);
+#pragma unroll
+        for (int i = 0; i < 64 / KG; ++i) vraw[i].load(Vb + (size_t)min(t + i * KG + kgrp, j1 - 1) * DH + dgrp * 8);
+        const bool valid = t + lane < j1;
+        float sc[MAXG];
+#pragma unroll
+        for (int h = 0; h < MAXG; ++h) sc[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < DH / 8; ++e) {
+            float kv[8];
+            kraw[e].get(kv);
+#pragma unroll
+            for (int h = 0; h < MAXG; ++h)
+                if (h < G) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) sc[h] = fmaf(q_s[h][e * 8 + i], kv[i], sc[h]);
+                }
+        }
+        // tile maximum and sum of exponentials per head; the G butterflies are interleaved so that their
+        // cross-lane exchanges overlap
+        float tm[MAXG], ts[MAXG], pv[MAXG];
+#pragma unroll
+        for (int h = 0; h < MAXG; ++h) tm[h] = (valid && h < G) ? sc[h] : -INFINITY;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            float other[MAXG];
+#pragma unroll
+            for (int h = 0; h < MAXG; ++h) if (h < G) other[h] = __shfl_xor(tm[h], off, 64);
+#pragma unroll
+            for (int h = 0; h < MAXG; ++h) if (h < G) tm[h] = fmaxf(tm[h], other[h]);
+        }
+#pragma unroll
+        for (int h = 0; h < MAXG; ++h) {
+            pv[h] = 0.f; ts[h] = 0.f;
+            if (h < G) {
+                tm[h] = fmaxf(m[h], tm[h]);                          // finite: lane 0 of a tile is always valid
+                pv[h] = valid ? __expf(sc[h] - tm[h]) : 0.f;
+                ts[h] = pv[h];
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            float other[MAXG];
+#pragma unroll
+            for (int h = 0; h < MAXG; ++h) if (h < G) other[h] = __shfl_xor(ts[h], off, 64);
+#pragma unroll
+            for (int h = 0; h < MAXG; ++h) if (h < G) ts[h] += other[h];
+        }
+#pragma unroll
+        for (int h = 0; h < MAXG; ++h)
+            if (h < G) {
+                const float corr = __expf(m[h] - tm[h]);             // 0 on the first tile
+                l[h] = l[h] * corr + ts[h];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o[h][i] *= corr;
+                m[h] = tm[h];
+                p_s[wave][h][lane] = pv[h];                          // read back by other lanes of this wavefront only
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 64 / KG; ++i) {
+            const int jj = i * KG + kgrp;
+            if (t + jj < j1) {
+                float vv[8];
+                vraw[i].get(vv);
+#pragma unroll
+                for (int h = 0; h < MAXG; ++h)
+                    if (h < G) {
+                        const float p = p_s[wave][h][jj];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o[h][e] = fmaf(p, vv[e], o[h][e]);
+                    }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+#pragma unroll
+    for (int h = 0; h < MAXG; ++h)
+        if (h < G) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float v = o[h][e];
+#pragma unroll
+                for (int off = DG; off < 64; off <<= 1) v += __shfl_xor(v, off, 64);
+                o[h][e] = v;
+            }
+            float *pp = part + (((size_t)r * D.Hq + g * G + h) * nchunks + c) * PS;
+            if (kgrp == 0) {
+                *reinterpret_cast<float4 *>(pp + dgrp * 8) = make_float4(o[h][0], o[h][1], o[h][2], o[h][3]);
+                *reinterpret_cast<float4 *>(pp + dgrp * 8 + 4) = make_float4(o[h][4], o[h][5], o[h][6], o[h][7]);
+            }
+            if (lane == 0) { pp[DH] = m[h]; pp[DH + 1] = l[h]; }
+        }
+}
+
 template <typename KT, int DH>
 static void launch_attention_t(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
                                float *part, size_t part_floats, float *att)
@@ -423,16 +573,38 @@ static void launch_attention_t(hipStream_t s, const Dims &D, const float *q, con
     if (nsplit > 1) hipLaunchKernelGGL((attn_merge_kernel<DH>), dim3(rows.n, D.Hq), dim3(DH), 0, s, D, part, nsplit, att);
 }
 
-void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
-                      float *part, size_t part_floats, float *att)
+template <typename KT, int DH>
+static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
+                                  float *part, size_t part_floats, float *att, void *pack, int ncb)
 {
+    int chunk = 64 * ((max_ctx + 64 * 32 - 1) / (64 * 32));   // at most 32 chunks per row
+    const int nchunks = (max_ctx + chunk - 1) / chunk;
+    if ((size_t)rows.n * D.Hq * nchunks * (DH + 4) > part_floats) return false;
+    hipLaunchKernelGGL((attn_wave_kernel<KT, DH>), dim3(rows.n, D.Hkv, (nchunks + 3) / 4), dim3(256), 0, s, D, q, (const KT *)kc, (const KT *)vc,
+                       rows, chunk, nchunks, part);
+    launch_attn_merge(s, D, part, nchunks, rows, chunk, att, pack, ncb);
+    return true;
+}
+
+// att (fp32 [R][qw]) and/or pack (packed hi/lo activations of the output projection) receive the result.
+void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
+                      float *part, size_t part_floats, float *att, void *pack, int ncb)
+{
+    bool done = false;
+    if (D.dh == 64) done = kdt == DT_F32 ? launch_attention_wave<float, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb)
+                                         : launch_attention_wave<bf16_t, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb);
+    else done = kdt == DT_F32 ? launch_attention_wave<float, 128>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb)
+                              : launch_attention_wave<bf16_t, 128>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb);
+    if (done) return;
+    // many rows (a prompt): one workgroup per row and kv head over the whole context
     if (D.dh == 64) {
-        if (kdt == DT_F32) launch_attention_t<float, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
-        else launch_attention_t<bf16_t, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
+        if (kdt == DT_F32) launch_attention_t<float, 64>(s, D, q, kc, vc, rows, max_ctx, part, 0, att);
+        else launch_attention_t<bf16_t, 64>(s, D, q, kc, vc, rows, max_ctx, part, 0, att);
     } else {
-        if (kdt == DT_F32) launch_attention_t<float, 128>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
-        else launch_attention_t<bf16_t, 128>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att);
+        if (kdt == DT_F32) launch_attention_t<float, 128>(s, D, q, kc, vc, rows, max_ctx, part, 0, att);
+        else launch_attention_t<bf16_t, 128>(s, D, q, kc, vc, rows, max_ctx, part, 0, att);
     }
+    if (pack) launch_pack(s, att, rows.n, D.qw, pack, ncb);
 }
 
 // ------------------------------------------------------------------ attention output: x += Wo a

@@ -21,6 +21,7 @@ namespace tr {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+constexpr int NWAVES = 4;  // wavefronts per workgroup (one per SIMD, 512 registers each); they split K
 constexpr int MAXKW = 14;  // k-steps a wavefront keeps resident (4 wavefronts x 14 x 16 = 896 columns of K per workgroup)
 
 __device__ __forceinline__ bf16_t m_f32_to_bf16(float f)
@@ -178,6 +179,60 @@ void launch_pack(hipStream_t s, const float *in, int M, int K, void *pack, int n
     hipLaunchKernelGGL(pack_kernel, dim3(M), dim3(128), 0, s, in, M, K, (uint4 *)pack, ncb);
 }
 
+// Merge of the per-chunk attention partials of one row (fixed order over chunks), written as fp32 rows and/or as
+// packed hi/lo activations for the output projection. One thread per 8 consecutive dims of a head.
+__global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos, int chunk, float *att, uint4 *pack, int ncb)
+{
+    const int r = blockIdx.x, ps = dh + 4;
+    const int live = min(nchunks, (pos[r] + chunk) / chunk);   // chunks that hold at least one key of this row
+    for (int k8 = threadIdx.x; k8 < qw / 8; k8 += blockDim.x) {
+        const int head = (k8 * 8) / dh, d0 = (k8 * 8) % dh;
+        const float *pp = part + ((size_t)r * Hq + head) * nchunks * ps;
+        // chunks are taken four at a time with their loads issued together (indices clamped, weight 0 past the end)
+        float M = -INFINITY;
+        for (int c0 = 0; c0 < live; c0 += 4) {
+            float mc[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) mc[u] = pp[min(c0 + u, live - 1) * ps + dh];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) M = fmaxf(M, mc[u]);
+        }
+        float L = 0.f, o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+        for (int c0 = 0; c0 < live; c0 += 4) {
+            float mc[4], lc[4];
+            float4 a[4], b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float *pc = pp + min(c0 + u, live - 1) * ps;
+                mc[u] = pc[dh]; lc[u] = pc[dh + 1];
+                a[u] = *reinterpret_cast<const float4 *>(pc + d0); b[u] = *reinterpret_cast<const float4 *>(pc + d0 + 4);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float w = c0 + u < live ? __expf(mc[u] - M) : 0.f;
+                L = fmaf(lc[u], w, L);
+                o[0] = fmaf(a[u].x, w, o[0]); o[1] = fmaf(a[u].y, w, o[1]); o[2] = fmaf(a[u].z, w, o[2]); o[3] = fmaf(a[u].w, w, o[3]);
+                o[4] = fmaf(b[u].x, w, o[4]); o[5] = fmaf(b[u].y, w, o[5]); o[6] = fmaf(b[u].z, w, o[6]); o[7] = fmaf(b[u].w, w, o[7]);
+            }
+        }
+        const float inv = 1.0f / L;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= inv;
+        if (att) {
+            *reinterpret_cast<float4 *>(att + (size_t)r * qw + k8 * 8) = make_float4(o[0], o[1], o[2], o[3]);
+            *reinterpret_cast<float4 *>(att + (size_t)r * qw + k8 * 8 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+        }
+        if (pack) store_packed(pack + (size_t)(r >> 6) * (qw / 16) * ncb * 64, ncb, r & 63, k8, o);
+    }
+}
+
+void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb)
+{
+    hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(128), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, chunk, att, (uint4 *)pack, ncb);
+}
+
 // ------------------------------------------------------------------ the GEMM
 
 struct GemmArgs {
@@ -307,16 +362,26 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     {
         if (m >= M) return;
         const int n0 = t * 32 + i0;
+        if (logits) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int n = n0 + e;
-            if (n < V) {
-                const float z = v[e];
-                if (logits) logits[(size_t)m * V + n] = z;
-                if (z > mx) { sum = sum * expf(mx - z) + 1.0f; mx = z; idx = n; }
-                else sum += expf(z - mx);
-            }
+            for (int e = 0; e < 8; ++e)
+                if (n0 + e < V) logits[(size_t)m * V + n0 + e] = v[e];
         }
+        float lm = -INFINITY;
+        int li = 0;
+#pragma unroll
+        for (int e = 7; e >= 0; --e)
+            if (n0 + e < V && v[e] >= lm) { lm = v[e]; li = e; }   // descending scan: the lowest index wins ties
+        if (lm > mx) {                                              // strict: earlier tiles win ties
+            sum *= __expf(mx - lm);
+            mx = lm;
+            idx = n0 + li;
+        }
+        float add = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (n0 + e < V) add += __expf(v[e] - mx);
+        sum += add;
     }
     // the four threads that share a batch row (one per 8-row band) merge through LDS
     __device__ void end(float *lds)
@@ -344,85 +409,116 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     }
 };
 
-template <int NCB, class Epi>
+// 256 threads = 4 wavefronts, each owning KW consecutive k-steps (compile time, so that every load of the steady
+// state is unconditional and the hardware wait counters can be exact). The weight tiles of a wavefront alternate
+// between two register sets: while tile t is multiplied, the loads of tile t+1 are in flight
+// (14 KiB per wavefront, 56 KiB per compute unit at KW = 14).
+template <int NCB, int KW, class Epi>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmArgs a, Epi epi_in)
 {
-    Epi epi = epi_in;   // per-thread epilogue state lives in registers
     constexpr int NCO = NCB / 2;
-    __shared__ float red[4][32][65];
+    __shared__ __attribute__((aligned(16))) float red[NWAVES][64][36];   // [wavefront][batch column][feature row], padded
+    Epi epi = epi_in;   // per-thread epilogue state lives in registers
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ks0 = blockIdx.y * a.ksw, ks1 = min(a.KS, ks0 + a.ksw);
-    const int per = (ks1 - ks0 + 3) >> 2;
+    const int per = (ks1 - ks0 + NWAVES - 1) / NWAVES;   // <= KW
     const int wk0 = ks0 + wave * per;
     const int nk = max(0, min(ks1, wk0 + per) - wk0);
     const int group = blockIdx.z;
 
-    // resident activations of this wavefront's k-steps
-    bf16x8 b[MAXKW][NCB];
-    {
-        const uint4 *pk = a.pack + ((size_t)group * a.KS + wk0) * NCB * 64 + lane;
+    // resident activations of this wavefront's k-steps (zero beyond its share, so the extra products vanish)
+    bf16x8 b[KW][NCB];
+    int koff[KW];   // k-step of each resident slot, clamped into the matrix
 #pragma unroll
-        for (int kk = 0; kk < MAXKW; ++kk)
+    for (int kk = 0; kk < KW; ++kk) {
+        koff[kk] = min(wk0 + kk, a.KS - 1);
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb) {
-                uint4 u = make_uint4(0, 0, 0, 0);
-                if (kk < nk) u = pk[((size_t)kk * NCB + cb) * 64];
-                b[kk][cb] = __builtin_bit_cast(bf16x8, u);
-            }
+        for (int cb = 0; cb < NCB; ++cb) {
+            uint4 u = make_uint4(0, 0, 0, 0);
+            if (kk < nk) u = a.pack[(((size_t)group * a.KS + wk0 + kk) * NCB + cb) * 64 + lane];
+            b[kk][cb] = __builtin_bit_cast(bf16x8, u);
+        }
     }
 
     const int t0 = blockIdx.x * a.tiles_per_wg, t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
-    uint4 wc[MAXKW], wn[MAXKW];
+    const size_t tile_stride = (size_t)a.KS * 64;
+    uint4 w0[KW], w1[KW];
+
+    auto load_tile = [&](int t, uint4 (&w)[KW]) {   // unconditional: t must be a valid tile
+        const uint4 *wp = a.Wt + (size_t)t * tile_stride + lane;
 #pragma unroll
-    for (int kk = 0; kk < MAXKW; ++kk) { wc[kk] = make_uint4(0, 0, 0, 0); wn[kk] = make_uint4(0, 0, 0, 0); }
-    if (t0 < t1) {
-        const uint4 *wp = a.Wt + ((size_t)t0 * a.KS + wk0) * 64 + lane;
-#pragma unroll
-        for (int kk = 0; kk < MAXKW; ++kk)
-            if (kk < nk) wc[kk] = wp[(size_t)kk * 64];
-    }
-    epi.begin();
+        for (int kk = 0; kk < KW; ++kk) w[kk] = wp[(size_t)koff[kk] * 64];
+    };
     const int j = threadIdx.x & 63, i0 = (threadIdx.x >> 6) * 8;
-    for (int t = t0; t < t1; ++t) {
-        if (t + 1 < t1) {
-            const uint4 *wp = a.Wt + ((size_t)(t + 1) * a.KS + wk0) * 64 + lane;
-#pragma unroll
-            for (int kk = 0; kk < MAXKW; ++kk)
-                if (kk < nk) wn[kk] = wp[(size_t)kk * 64];
-        }
-        f32x16 acc[NCO];
+    f32x16 acc[NCO];
+    auto mfma_tile = [&](const uint4 (&w)[KW]) {
 #pragma unroll
         for (int co = 0; co < NCO; ++co)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[co][r] = 0.f;
 #pragma unroll
-        for (int kk = 0; kk < MAXKW; ++kk)
-            if (kk < nk) {
-                const bf16x8 w = __builtin_bit_cast(bf16x8, wc[kk]);
+        for (int kk = 0; kk < KW; ++kk) {
+            const bf16x8 wv = __builtin_bit_cast(bf16x8, w[kk]);
 #pragma unroll
-                for (int co = 0; co < NCO; ++co) {
-                    acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, b[kk][co], acc[co], 0, 0, 0);
-                    acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, b[kk][NCO + co], acc[co], 0, 0, 0);
-                }
+            for (int co = 0; co < NCO; ++co) {
+                acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][co], acc[co], 0, 0, 0);
+                acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][NCO + co], acc[co], 0, 0, 0);
             }
+        }
+    };
+    auto post_tile = [&](int t) {
         __syncthreads();   // the previous tile has been read
 #pragma unroll
         for (int co = 0; co < NCO; ++co)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) red[wave][(r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)][co * 32 + (lane & 31)] = acc[co][r];
+            for (int qd = 0; qd < 4; ++qd)   // registers 4qd..4qd+3 are 4 consecutive feature rows of one batch column
+                *reinterpret_cast<float4 *>(&red[wave][co * 32 + (lane & 31)][qd * 8 + (lane >> 5) * 4]) =
+                    make_float4(acc[co][4 * qd], acc[co][4 * qd + 1], acc[co][4 * qd + 2], acc[co][4 * qd + 3]);
         __syncthreads();
         float v[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) v[r] = 0.f;
         if (j < 32 * NCO) {
 #pragma unroll
-            for (int r = 0; r < 8; ++r) v[r] = (red[0][i0 + r][j] + red[1][i0 + r][j]) + (red[2][i0 + r][j] + red[3][i0 + r][j]);
+            for (int ww = 0; ww < NWAVES; ++ww) {
+                const float4 lo4 = *reinterpret_cast<const float4 *>(&red[ww][j][i0]);
+                const float4 hi4 = *reinterpret_cast<const float4 *>(&red[ww][j][i0 + 4]);
+                v[0] += lo4.x; v[1] += lo4.y; v[2] += lo4.z; v[3] += lo4.w;
+                v[4] += hi4.x; v[5] += hi4.y; v[6] += hi4.z; v[7] += hi4.w;
+            }
         }
         epi.tile(t, group * 64 + j, i0, v);
-#pragma unroll
-        for (int kk = 0; kk < MAXKW; ++kk) wc[kk] = wn[kk];
+    };
+
+    epi.begin();
+    int t = t0;
+    if (t < t1) load_tile(t, w0);
+    if (t + 1 < t1) load_tile(t + 1, w1);
+    // steady state: two tiles per trip, every load unconditional. A register set is refilled as soon as its MFMAs have
+    // been issued, so the loads of the tile after next fly while this tile is reduced and the next one is multiplied.
+    for (; t + 3 < t1; t += 2) {
+        mfma_tile(w0);
+        load_tile(t + 2, w0);
+        post_tile(t);
+        mfma_tile(w1);
+        load_tile(t + 3, w1);
+        post_tile(t + 1);
     }
+    const int rest = t1 - t;   // 0..3 tiles left; w0 holds tile t, w1 tile t+1
+    if (rest >= 1) { mfma_tile(w0); if (rest >= 3) load_tile(t + 2, w0); post_tile(t); }
+    if (rest >= 2) { mfma_tile(w1); post_tile(t + 1); }
+    if (rest >= 3) { mfma_tile(w0); post_tile(t + 2); }
     epi.end(&red[0][0][0]);
+}
+
+template <int NCB, class Epi>
+static void launch_gemm_kw(hipStream_t s, const GemmArgs &a, dim3 grid, const Epi &epi)
+{
+    const int per = (a.ksw + NWAVES - 1) / NWAVES;
+    if (per <= 2) hipLaunchKernelGGL((gemm_kernel<NCB, 2, Epi>), grid, dim3(256), 0, s, a, epi);
+    else if (per <= 4) hipLaunchKernelGGL((gemm_kernel<NCB, 4, Epi>), grid, dim3(256), 0, s, a, epi);
+    else if (per <= 8) hipLaunchKernelGGL((gemm_kernel<NCB, 8, Epi>), grid, dim3(256), 0, s, a, epi);
+    else hipLaunchKernelGGL((gemm_kernel<NCB, 14, Epi>), grid, dim3(256), 0, s, a, epi);
 }
 
 template <class Epi>
@@ -430,8 +526,8 @@ static void launch_gemm(hipStream_t s, const GemmArgs &a, int nsplit, const Epi 
 {
     const int groups = (a.M + 63) / 64;
     const dim3 grid((a.n_tiles + a.tiles_per_wg - 1) / a.tiles_per_wg, nsplit, groups);
-    if (a.M <= 32) hipLaunchKernelGGL((gemm_kernel<2, Epi>), grid, dim3(256), 0, s, a, epi);
-    else hipLaunchKernelGGL((gemm_kernel<4, Epi>), grid, dim3(256), 0, s, a, epi);
+    if (a.M <= 32) launch_gemm_kw<2>(s, a, grid, epi);
+    else launch_gemm_kw<4>(s, a, grid, epi);
 }
 
 int mfma_ncb(int M) { return M <= 32 ? 2 : 4; }
@@ -439,7 +535,7 @@ int mfma_ncb(int M) { return M <= 32 ? 2 : 4; }
 // split-K plan for the linear layers whose epilogue is a plain sum
 void plan_partial(int KS, int n_tiles, int *nsplit, int *ksw, int *tiles_per_wg)
 {
-    int S = (KS + 4 * MAXKW - 1) / (4 * MAXKW);
+    int S = (KS + NWAVES * MAXKW - 1) / (NWAVES * MAXKW);
     const int want = 256 / (n_tiles > 0 ? n_tiles : 1);
     if (want > S) S = want;
     if (S > MAX_SPLITS) S = MAX_SPLITS;

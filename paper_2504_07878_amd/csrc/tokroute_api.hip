@@ -66,7 +66,7 @@ Layout make_layout(const tr_config *c)
     L.nslices = (c->vocab + tail_slice_rows() - 1) / tail_slice_rows();
     const size_t R = (size_t)L.max_rows;
     // room for up to 32 context splits of a full decode batch
-    L.attn_part_floats = (size_t)c->max_batch * c->n_q_heads * 32 * (c->head_dim + 2);
+    L.attn_part_floats = (size_t)c->max_batch * c->n_q_heads * 32 * (c->head_dim + 4);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     L.kc = take(cache); L.vc = take(cache);
@@ -195,7 +195,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
             const LayerW &w = ctx->layers[(size_t)l];
             launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
             launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
-                             attn_part_floats, att);
+                             attn_part_floats, att, nullptr, 0);
             launch_oproj(s, ctx->c.dtype, D, w.wo, att, R, x);
             launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
             launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
@@ -214,8 +214,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
         launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
                         ctx->kc_layer(l), ctx->vc_layer(l));
         launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
-                         attn_part_floats, att);
-        launch_pack(s, att, R, D.qw, ctx->at<uint4>(L.pack_a), ncb);
+                         attn_part_floats, attn_part_floats ? nullptr : att, ctx->at<uint4>(L.pack_a), ncb);
         launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
         p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
         launch_prep(s, p);

@@ -66,7 +66,8 @@ void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, 
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope,
                 float *q, void *kc, void *vc);
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
-                      float *part, size_t part_floats, float *att);
+                      float *part, size_t part_floats, float *att, void *pack, int ncb);
+void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb);
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, int R, float *x);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x);

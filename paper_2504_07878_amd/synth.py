@@ -99,18 +99,21 @@ def const(shape, value: float, dtype: int) -> np.ndarray:
 
 
 def make_weights(s: ModelShape, base_seed: int, std: float = 0.02, bias_std: float = 0.0, gain_std: float = 0.0,
-                 qkv_bias: bool = True) -> dict:
+                 qkv_bias: bool = True, workers: int = 1) -> dict:
     """All weight tensors of a model, by name.
 
     Matrices ~ N(0, std^2) in [out][in] layout; RMSNorm gains = 1 (+ N(0, gain_std^2) when asked); biases = 0
-    (N(0, bias_std^2) when asked). Per-layer tensors are named ``l{i}.wq`` etc.
+    (N(0, bias_std^2) when asked). Per-layer tensors are named ``l{i}.wq`` etc. Every tensor has its own stream, so
+    drawing the matrices on several threads (``workers``) gives the same values as drawing them one by one.
     """
     d, qw, kvw, F, V = s.d_model, s.n_q_heads * s.head_dim, s.n_kv_heads * s.head_dim, s.d_ffn, s.vocab
     dt = s.dtype
     w = {}
+    todo = []
 
     def mat(name, shape):
-        w[name] = normal(base_seed, name, shape, std, dt)
+        w[name] = None          # keeps the insertion order
+        todo.append((name, shape))
 
     def gain(name, n):
         w[name] = normal(base_seed, name, (n,), gain_std, dt, mean=1.0) if gain_std else const((n,), 1.0, dt)
@@ -134,6 +137,14 @@ def make_weights(s: ModelShape, base_seed: int, std: float = 0.02, bias_std: flo
     if s.router_hidden:
         mat("r_w1", (s.router_hidden, d)); bias("r_b1", s.router_hidden)
         mat("r_w2", (s.router_hidden,)); bias("r_b2", 1)
+    if workers > 1:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(workers) as pool:
+            for (name, _), a in zip(todo, pool.map(lambda t: normal(base_seed, t[0], t[1], std, dt), todo)):
+                w[name] = a
+    else:
+        for name, shape in todo:
+            w[name] = normal(base_seed, name, shape, std, dt)
     return w
 
 
