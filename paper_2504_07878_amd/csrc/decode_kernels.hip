@@ -58,13 +58,67 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
+template <typename KT> struct Raw8;
+template <> struct Raw8<bf16_t> {
+    uint4 v;
+    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
+    __device__ __forceinline__ void get(float (&w)[8]) const
+    {
+        w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
+        w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
+        w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
+        w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+};
+template <> struct Raw8<float> {
+    float4 a, b;
+    __device__ __forceinline__ void load(const float *p) { a = *reinterpret_cast<const float4 *>(p); b = *reinterpret_cast<const float4 *>(p + 4); }
+    __device__ __forceinline__ void get(float (&w)[8]) const { w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w; }
+};
+
 // Dot products of NR weight rows with MB activation rows over K (K % 8 == 0). With NORM the weights are
 // multiplied by the RMSNorm gain and the activations' sums of squares are accumulated alongside, so that
 // W.(g*x/rms) = (W*g).x / rms needs no separate normalisation pass. Results are valid in every lane.
+// The weight stream is requested four 512-column steps at a time (4*NR 16-byte loads in flight per lane).
 template <typename WT, int NR, int MB, bool NORM>
-__device__ __forceinline__ void wave_dots(const WT *const (&wrow)[NR], const WT *gain, const float *const (&xrow)[MB], int K,
+__device__ __forceinline__ void dots_step(const Raw8<WT> (&rw)[NR], const Raw8<WT> &rg, const float *const (&xrow)[MB], int k,
                                           float (&acc)[NR][MB], float (&ss)[MB])
 {
+    float w[NR][8];
+#pragma unroll
+    for (int r = 0; r < NR; ++r) rw[r].get(w[r]);
+    if (NORM) {
+        float g[8];
+        rg.get(g);
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) w[r][i] *= g[i];
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        float xv[8];
+        load8(xrow[m] + k, xv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (NORM) ss[m] = fmaf(xv[i], xv[i], ss[m]);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) acc[r][m] = fmaf(w[r][i], xv[i], acc[r][m]);
+        }
+    }
+}
+
+constexpr int KC = 2048;   // activation columns staged in LDS at a time
+
+// Workgroup-wide GEMV step: the 4 wavefronts of a workgroup each own NR weight rows; the MB activation rows are
+// staged through LDS in chunks of KC columns (read once from memory per workgroup, then broadcast from LDS, which keeps
+// the vector-memory pipe free for the weight stream). Every wavefront of the workgroup must call this (barriers inside).
+// xs: LDS buffer of MB*KC floats. Rows m >= mvalid are read as zeros. Results are valid in every lane.
+template <typename WT, int NR, int MB, bool NORM>
+__device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *gain, const float *x, size_t xstride, int mvalid, int K, float *xs,
+                                        float (&acc)[NR][MB], float (&ss)[MB])
+{
+    constexpr int U = 4;
     const int lane = threadIdx.x & 63;
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
@@ -72,28 +126,40 @@ __device__ __forceinline__ void wave_dots(const WT *const (&wrow)[NR], const WT 
 #pragma unroll
         for (int r = 0; r < NR; ++r) acc[r][m] = 0.f;
     }
-    for (int k = lane * 8; k < K; k += 512) {
-        float w[NR][8];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) load8(wrow[r] + k, w[r]);
-        if (NORM) {
-            float g[8];
-            load8(gain + k, g);
-#pragma unroll
-            for (int r = 0; r < NR; ++r)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) w[r][i] *= g[i];
+    for (int kc0 = 0; kc0 < K; kc0 += KC) {
+        const int kc = min(KC, K - kc0);
+        __syncthreads();
+        for (int idx = threadIdx.x; idx < MB * (kc / 4); idx += 256) {
+            const int m = idx / (kc / 4), c4 = idx % (kc / 4);
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (m < mvalid) v = *reinterpret_cast<const float4 *>(x + (size_t)m * xstride + kc0 + c4 * 4);
+            *reinterpret_cast<float4 *>(xs + m * KC + c4 * 4) = v;
         }
+        __syncthreads();
+        const float *xr[MB];
 #pragma unroll
-        for (int m = 0; m < MB; ++m) {
-            float xv[8];
-            load8(xrow[m] + k, xv);
+        for (int m = 0; m < MB; ++m) xr[m] = xs + m * KC;
+        const WT *wr[NR];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (NORM) ss[m] = fmaf(xv[i], xv[i], ss[m]);
+        for (int r = 0; r < NR; ++r) wr[r] = wrow[r] + kc0;
+        int k = lane * 8;
+        for (; k + (U - 1) * 512 < kc; k += U * 512) {
+            Raw8<WT> rw[U][NR], rg[U];
 #pragma unroll
-                for (int r = 0; r < NR; ++r) acc[r][m] = fmaf(w[r][i], xv[i], acc[r][m]);
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int r = 0; r < NR; ++r) rw[u][r].load(wr[r] + k + u * 512);
+                if (NORM) rg[u].load(gain + kc0 + k + u * 512);
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u) dots_step<WT, NR, MB, NORM>(rw[u], rg[u], xr, k + u * 512, acc, ss);
+        }
+        for (; k < kc; k += 512) {
+            Raw8<WT> rw[NR], rg;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rw[r].load(wr[r] + k);
+            if (NORM) rg.load(gain + kc0 + k);
+            dots_step<WT, NR, MB, NORM>(rw, rg, xr, k, acc, ss);
         }
     }
 #pragma unroll
@@ -183,9 +249,11 @@ template <typename WT, typename KT, int MB>
 __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float *x, Rows rows, const float2 *rope, float *q, KT *kc,
                                                   KT *vc)
 {
+    __shared__ __attribute__((aligned(16))) float xs[MB * KC];
     const int half = D.dh / 2;
-    const int pair = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (pair >= (D.Hq + 2 * D.Hkv) * half) return;
+    const int npairs = (D.Hq + 2 * D.Hkv) * half;
+    const int pair_raw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int pair = pair_raw < npairs ? pair_raw : npairs - 1;   // surplus wavefronts redo the last pair and drop it
     const int hh = pair / half, j = pair % half;
     const WT *W, *bias;
     int head;  // head index inside its own matrix
@@ -195,12 +263,9 @@ __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float 
     const int n1 = head * D.dh + j, n2 = n1 + half;
     const WT *const wrow[2] = {W + (size_t)n1 * D.d, W + (size_t)n2 * D.d};
     const int r0 = blockIdx.y * MB;
-    const float *xrow[MB];
-#pragma unroll
-    for (int m = 0; m < MB; ++m) xrow[m] = x + (size_t)(r0 + m < rows.n ? r0 + m : r0) * D.d;
     float acc[2][MB], ss[MB];
-    wave_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, xrow, D.d, acc, ss);
-    if ((threadIdx.x & 63) != 0) return;
+    wg_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, x + (size_t)r0 * D.d, D.d, rows.n - r0, D.d, xs, acc, ss);
+    if ((threadIdx.x & 63) != 0 || pair_raw >= npairs) return;
     const float b1 = bias ? widen(bias, n1) : 0.f, b2 = bias ? widen(bias, n2) : 0.f;
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
@@ -218,9 +283,14 @@ __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float 
             q[(size_t)r * D.qw + n1] = y1;
             q[(size_t)r * D.qw + n2] = y2;
         } else {
-            KT *dst = (hh < D.Hq + D.Hkv ? kc : vc) + (((size_t)rows.slot[r] * D.Hkv + head) * D.max_seq + pos) * D.dh;
-            store_kv(dst + j, y1);
-            store_kv(dst + j + half, y2);
+            if (hh < D.Hq + D.Hkv) {
+                KT *dst = kc + (((size_t)rows.slot[r] * D.Hkv + head) * D.max_seq + pos) * D.dh;
+                store_kv(dst + j, y1);
+                store_kv(dst + j + half, y2);
+            } else {
+                store_kv(vc + v_offset(D, rows.slot[r], head, pos, j), y1);
+                store_kv(vc + v_offset(D, rows.slot[r], head, pos, j + half), y2);
+            }
         }
     }
 }
@@ -232,6 +302,8 @@ static void launch_qkv_t(hipStream_t s, const Dims &D, const LayerW &w, const fl
     const int pairs = (D.Hq + 2 * D.Hkv) * (D.dh / 2);
     if (rows.n == 1)
         hipLaunchKernelGGL((qkv_kernel<WT, KT, 1>), dim3((pairs + 3) / 4, 1), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
+    else if (rows.n == 2)
+        hipLaunchKernelGGL((qkv_kernel<WT, KT, 2>), dim3((pairs + 3) / 4, 1), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
     else
         hipLaunchKernelGGL((qkv_kernel<WT, KT, 4>), dim3((pairs + 3) / 4, (rows.n + 3) / 4), dim3(256), 0, s, D, w, x, rows, rope, q,
                            (KT *)kc, (KT *)vc);
@@ -409,24 +481,6 @@ __global__ void attn_merge_kernel(Dims D, const float *part, int nsplit, float *
 // kernel combines them in a fixed order. K and V of a tile are requested together, so a tile costs one memory
 // round trip; with one tile per wavefront the whole context of a batch is in flight at once.
 
-template <typename KT> struct Raw8;
-template <> struct Raw8<bf16_t> {
-    uint4 v;
-    __device__ __forceinline__ void load(const bf16_t *p) { v = *reinterpret_cast<const uint4 *>(p); }
-    __device__ __forceinline__ void get(float (&w)[8]) const
-    {
-        w[0] = __uint_as_float(v.x << 16); w[1] = __uint_as_float(v.x & 0xffff0000u);
-        w[2] = __uint_as_float(v.y << 16); w[3] = __uint_as_float(v.y & 0xffff0000u);
-        w[4] = __uint_as_float(v.z << 16); w[5] = __uint_as_float(v.z & 0xffff0000u);
-        w[6] = __uint_as_float(v.w << 16); w[7] = __uint_as_float(v.w & 0xffff0000u);
-    }
-};
-template <> struct Raw8<float> {
-    float4 a, b;
-    __device__ __forceinline__ void load(const float *p) { a = *reinterpret_cast<const float4 *>(p); b = *reinterpret_cast<const float4 *>(p + 4); }
-    __device__ __forceinline__ void get(float (&w)[8]) const { w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w; }
-};
-
 template <typename KT, int DH>
 __global__ __launch_bounds__(256) void attn_wave_kernel(Dims D, const float *q, const KT *kc, const KT *vc, Rows rows, int chunk, int nchunks,
                                                         float *part)
@@ -582,7 +636,7 @@ static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, 
     if ((size_t)rows.n * D.Hq * nchunks * (DH + 4) > part_floats) return false;
     hipLaunchKernelGGL((attn_wave_kernel<KT, DH>), dim3(rows.n, D.Hkv, (nchunks + 3) / 4), dim3(256), 0, s, D, q, (const KT *)kc, (const KT *)vc,
                        rows, chunk, nchunks, part);
-    launch_attn_merge(s, D, part, nchunks, rows, chunk, att, pack, ncb);
+    launch_attn_merge(s, D, part, nchunks, rows, chunk, pack ? nullptr : att, pack, ncb);
     return true;
 }
 
@@ -590,6 +644,10 @@ static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, 
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
                       float *part, size_t part_floats, float *att, void *pack, int ncb)
 {
+    if (kdt == DT_BF16) {   // bf16 cache: V is stored transposed and attention runs on the matrix cores
+        launch_attention_mfma(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb);
+        return;
+    }
     bool done = false;
     if (D.dh == 64) done = kdt == DT_F32 ? launch_attention_wave<float, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb)
                                          : launch_attention_wave<bf16_t, 64>(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb);
@@ -612,26 +670,29 @@ void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, con
 template <typename WT, int MB>
 __global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, const float *in, int R, int N, int K, float *x)
 {
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (n >= N) return;
-    const WT *const wrow[1] = {W + (size_t)n * K};
+    __shared__ __attribute__((aligned(16))) float xs[MB * KC];
+    const int n_raw = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 2;     // two consecutive output rows per wavefront
+    const int n = n_raw < N ? n_raw : 0, n2 = n_raw + 1 < N ? n_raw + 1 : n;
+    const WT *const wrow[2] = {W + (size_t)n * K, W + (size_t)n2 * K};
     const int r0 = blockIdx.y * MB;
-    const float *xrow[MB];
-#pragma unroll
-    for (int m = 0; m < MB; ++m) xrow[m] = in + (size_t)(r0 + m < R ? r0 + m : r0) * K;
-    float acc[1][MB], ss[MB];
-    wave_dots<WT, 1, MB, false>(wrow, nullptr, xrow, K, acc, ss);
-    if ((threadIdx.x & 63) != 0) return;
+    float acc[2][MB], ss[MB];
+    wg_dots<WT, 2, MB, false>(wrow, nullptr, in + (size_t)r0 * K, K, R - r0, K, xs, acc, ss);
+    if ((threadIdx.x & 63) != 0 || n_raw >= N) return;
 #pragma unroll
     for (int m = 0; m < MB; ++m)
-        if (r0 + m < R) x[(size_t)(r0 + m) * N + n] += acc[0][m];
+        if (r0 + m < R) {
+            x[(size_t)(r0 + m) * N + n_raw] += acc[0][m];
+            if (n_raw + 1 < N) x[(size_t)(r0 + m) * N + n_raw + 1] += acc[1][m];
+        }
 }
 
 template <typename WT>
 static void launch_residual_gemv(hipStream_t s, const void *W, const float *in, int R, int N, int K, float *x)
 {
-    if (R == 1) hipLaunchKernelGGL((residual_gemv_kernel<WT, 1>), dim3((N + 3) / 4, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
-    else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4>), dim3((N + 3) / 4, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    const int gx = (N + 7) / 8;
+    if (R == 1) hipLaunchKernelGGL((residual_gemv_kernel<WT, 1>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    else if (R == 2) hipLaunchKernelGGL((residual_gemv_kernel<WT, 2>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
 }
 
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, int R, float *x)
@@ -651,16 +712,14 @@ void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const fl
 template <typename WT, int MB>
 __global__ __launch_bounds__(256) void gateup_kernel(Dims D, const WT *wg, const WT *wu, const WT *gain, const float *x, int R, float *h)
 {
-    const int f = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (f >= D.F) return;
+    __shared__ __attribute__((aligned(16))) float xs[MB * KC];
+    const int f_raw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int f = f_raw < D.F ? f_raw : D.F - 1;
     const WT *const wrow[2] = {wg + (size_t)f * D.d, wu + (size_t)f * D.d};
     const int r0 = blockIdx.y * MB;
-    const float *xrow[MB];
-#pragma unroll
-    for (int m = 0; m < MB; ++m) xrow[m] = x + (size_t)(r0 + m < R ? r0 + m : r0) * D.d;
     float acc[2][MB], ss[MB];
-    wave_dots<WT, 2, MB, true>(wrow, gain, xrow, D.d, acc, ss);
-    if ((threadIdx.x & 63) != 0) return;
+    wg_dots<WT, 2, MB, true>(wrow, gain, x + (size_t)r0 * D.d, D.d, R - r0, D.d, xs, acc, ss);
+    if ((threadIdx.x & 63) != 0 || f_raw >= D.F) return;
 #pragma unroll
     for (int m = 0; m < MB; ++m)
         if (r0 + m < R) {
@@ -675,9 +734,11 @@ void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const
     const dim3 g1((D.F + 3) / 4, 1), g4((D.F + 3) / 4, (R + 3) / 4);
     if (wdt == DT_F32) {
         if (R == 1) hipLaunchKernelGGL((gateup_kernel<float, 1>), g1, dim3(256), 0, s, D, (const float *)w.wg, (const float *)w.wu, (const float *)w.ln2, x, R, h);
+        else if (R == 2) hipLaunchKernelGGL((gateup_kernel<float, 2>), g1, dim3(256), 0, s, D, (const float *)w.wg, (const float *)w.wu, (const float *)w.ln2, x, R, h);
         else hipLaunchKernelGGL((gateup_kernel<float, 4>), g4, dim3(256), 0, s, D, (const float *)w.wg, (const float *)w.wu, (const float *)w.ln2, x, R, h);
     } else {
         if (R == 1) hipLaunchKernelGGL((gateup_kernel<bf16_t, 1>), g1, dim3(256), 0, s, D, (const bf16_t *)w.wg, (const bf16_t *)w.wu, (const bf16_t *)w.ln2, x, R, h);
+        else if (R == 2) hipLaunchKernelGGL((gateup_kernel<bf16_t, 2>), g1, dim3(256), 0, s, D, (const bf16_t *)w.wg, (const bf16_t *)w.wu, (const bf16_t *)w.ln2, x, R, h);
         else hipLaunchKernelGGL((gateup_kernel<bf16_t, 4>), g4, dim3(256), 0, s, D, (const bf16_t *)w.wg, (const bf16_t *)w.wu, (const bf16_t *)w.ln2, x, R, h);
     }
 }
@@ -690,12 +751,13 @@ __global__ void load_kv_kernel(Dims D, int slot, int len, const KT *k, const KT 
     const size_t per_layer_src = (size_t)D.Hkv * len * D.dh;
     const size_t total = (size_t)D.L * per_layer_src;
     const size_t layer_stride = (size_t)D.max_batch * D.Hkv * D.max_seq * D.dh;
+    const size_t v_layer_stride = (size_t)D.max_batch * D.Hkv * D.dh * (D.vts ? D.vts : D.max_seq);
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const size_t l = i / per_layer_src, rem = i % per_layer_src;
         const size_t g = rem / ((size_t)len * D.dh), pe = rem % ((size_t)len * D.dh);
         const size_t dst = l * layer_stride + ((size_t)slot * D.Hkv + g) * D.max_seq * D.dh + pe;
         kc[dst] = k[i];
-        vc[dst] = v[i];
+        vc[l * v_layer_stride + v_offset(D, slot, (int)g, (int)(pe / D.dh), (int)(pe % D.dh))] = v[i];
     }
 }
 

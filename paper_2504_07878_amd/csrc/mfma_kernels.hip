@@ -230,7 +230,172 @@ __global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, in
 
 void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb)
 {
-    hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(128), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, chunk, att, (uint4 *)pack, ncb);
+    const int threads = D.qw / 8 >= 512 ? 512 : (D.qw / 8 + 63) / 64 * 64;
+    hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(threads), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, chunk, att, (uint4 *)pack, ncb);
+}
+
+// ------------------------------------------------------------------ grouped-query attention on the matrix cores
+// (bf16 cache, V stored transposed). One wavefront owns one (query row, kv head, chunk of the context) and walks its
+// chunk in blocks of 32 keys:
+//   S[key][head]  = K[key][:] . q[head][:]   v_mfma 32x32x16, A = K rows straight from the cache, B = q as hi+lo bf16
+//   O[dim][head] += V^T[dim][key] . P[head][key]          A = V^T rows straight from the cache, B = P as hi+lo bf16
+// The 32 accumulator columns are the query heads of the group (7 of 32 used). In the accumulator layout a lane holds
+// one head column, so the softmax of a block is in-register arithmetic plus one exchange between lanes l and l^32,
+// and the probabilities already sit where the second product wants its B operand: K rows are fetched in the order
+// "bits 2 and 3 of the row index swapped", which makes the 8 accumulator registers of one k-step hold 8 consecutive keys.
+
+__device__ __forceinline__ void to_hi_lo(const float (&v)[8], bf16x8 &hi, bf16x8 &lo)
+{
+    uint4 h, l;
+    split_hi_lo(v, h, l);
+    hi = __builtin_bit_cast(bf16x8, h);
+    lo = __builtin_bit_cast(bf16x8, l);
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, int chunk, int nchunks,
+                                                        float *part, float *att)
+{
+    constexpr int KSQ = DH / 16, DB = DH / 32, PS = DH + 4;
+    const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= rows.n * nchunks) return;
+    const int r = item / nchunks, c = item % nchunks, g = blockIdx.y;
+    const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
+    const int ctx = rows.pos[r] + 1;
+    const int j0 = c * chunk, j1 = min(ctx, j0 + chunk);
+    const int slot = rows.slot[r];
+
+    bf16x8 qh[KSQ], ql[KSQ];
+    {
+        const float scale = 1.0f / sqrtf((float)DH);
+        const float *qp = q + (size_t)r * D.qw + (size_t)(g * G + (j < G ? j : 0)) * DH + hf * 8;
+#pragma unroll
+        for (int ks = 0; ks < KSQ; ++ks) {
+            float v[8];
+            const float4 a = *reinterpret_cast<const float4 *>(qp + ks * 16), b = *reinterpret_cast<const float4 *>(qp + ks * 16 + 4);
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = j < G ? v[e] * scale : 0.f;
+            to_hi_lo(v, qh[ks], ql[ks]);
+        }
+    }
+    const bf16_t *Kb = kc + ((size_t)slot * D.Hkv + g) * (size_t)D.max_seq * DH;
+    const bf16_t *Vb = vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * D.vts;
+    const int krow = (j & 0x13) | ((j & 4) << 1) | ((j & 8) >> 1);   // row j of the A operand holds key krow (bits 2,3 swapped)
+
+    float m = -INFINITY, l = 0.f;
+    f32x16 o[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr) o[db][rr] = 0.f;
+
+    // NB blocks of 32 keys are requested together (all loads of 64 keys in flight at once for 64-wide heads)
+    constexpr int NB = DH == 64 ? 2 : 1;
+    for (int t0 = j0; t0 < j1; t0 += 32 * NB) {
+        uint4 ka[NB][KSQ], va[NB][2][DB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int t = t0 + 32 * nb;   // may start past j1 in the last trip: rows are clamped, V^T rows are padded to 32
+            const bf16_t *kp = Kb + (size_t)min(t + krow, j1 - 1) * DH + hf * 8;
+#pragma unroll
+            for (int ks = 0; ks < KSQ; ++ks) ka[nb][ks] = *reinterpret_cast<const uint4 *>(kp + ks * 16);
+            const int tv = min(t, D.vts - 32);
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+                    va[nb][kk][db] = *reinterpret_cast<const uint4 *>(Vb + (size_t)(db * 32 + j) * D.vts + tv + 16 * kk + 8 * hf);
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int t = t0 + 32 * nb;
+            if (t >= j1) break;   // uniform over the wavefront
+            f32x16 sacc;
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) sacc[rr] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KSQ; ++ks) {
+                const bf16x8 kv = __builtin_bit_cast(bf16x8, ka[nb][ks]);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qh[ks], sacc, 0, 0, 0);
+                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, ql[ks], sacc, 0, 0, 0);
+            }
+            // register rr of this lane is key t + 16*(rr/8) + 8*hf + rr%8 of head j
+            float bm = -INFINITY;
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) {
+                if (t + 16 * (rr >> 3) + 8 * hf + (rr & 7) >= j1) sacc[rr] = -INFINITY;
+                bm = fmaxf(bm, sacc[rr]);
+            }
+            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));      // key t is valid, so the pair maximum is finite
+            const float mn = fmaxf(m, bm);
+            const float corr = __expf(m - mn);           // 0 on the first block
+            float p[16], ps = 0.f;
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) { p[rr] = __expf(sacc[rr] - mn); ps += p[rr]; }
+            l = l * corr + ps;
+            m = mn;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) o[db][rr] *= corr;
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const float pk[8] = {p[8 * kk], p[8 * kk + 1], p[8 * kk + 2], p[8 * kk + 3], p[8 * kk + 4], p[8 * kk + 5], p[8 * kk + 6], p[8 * kk + 7]};
+                bf16x8 ph, pl;
+                to_hi_lo(pk, ph, pl);
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const bf16x8 vv = __builtin_bit_cast(bf16x8, va[nb][kk][db]);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, ph, o[db], 0, 0, 0);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pl, o[db], 0, 0, 0);
+                }
+            }
+        }
+    }
+    const float lt = l + __shfl_xor(l, 32, 64);      // both lanes of a head used the same running maximum
+    if (j >= G) return;
+    const int head = g * G + j;
+    // accumulator register rr of block db is dim db*32 + 8*(rr/4) + 4*hf + rr%4
+    if (nchunks == 1) {
+        const float inv = 1.0f / lt;
+        float *dst = att + (size_t)r * D.qw + (size_t)head * DH;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                *reinterpret_cast<float4 *>(dst + db * 32 + qd * 8 + hf * 4) =
+                    make_float4(o[db][4 * qd] * inv, o[db][4 * qd + 1] * inv, o[db][4 * qd + 2] * inv, o[db][4 * qd + 3] * inv);
+    } else {
+        float *pp = part + (((size_t)r * D.Hq + head) * nchunks + c) * PS;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                *reinterpret_cast<float4 *>(pp + db * 32 + qd * 8 + hf * 4) = make_float4(o[db][4 * qd], o[db][4 * qd + 1], o[db][4 * qd + 2], o[db][4 * qd + 3]);
+        if (hf == 0) { pp[DH] = m; pp[DH + 1] = lt; }
+    }
+}
+
+void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
+                           size_t part_floats, float *att, void *pack, int ncb)
+{
+    // decode: up to 32 chunks of the context per row, merged afterwards; prompts: one wavefront walks the whole context of a row
+    size_t room = part_floats / ((size_t)rows.n * D.Hq * (D.dh + 4));   // chunks per row that fit the partials buffer
+    if (room > 64) room = 64;
+    int chunk = (max_ctx + 63) / 64 * 64, nchunks = 1;
+    if (room >= 2) {
+        chunk = 64 * (int)((max_ctx + 64 * room - 1) / (64 * room));
+        nchunks = (max_ctx + chunk - 1) / chunk;
+    }
+    const dim3 grid((rows.n * nchunks + 3) / 4, D.Hkv);
+    float *direct = nchunks == 1 ? att : nullptr;
+    if (D.dh == 64)
+        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
+    else
+        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
+    if (nchunks > 1) launch_attn_merge(s, D, part, nchunks, rows, chunk, pack ? nullptr : att, pack, ncb);
+    else if (pack) launch_pack(s, att, rows.n, D.qw, pack, ncb);
 }
 
 // ------------------------------------------------------------------ the GEMM
@@ -270,7 +435,7 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
     const int *slot, *pos;
     float *q;
     KT *kc, *vc;
-    int M, Hq, Hkv, dh, max_seq, qw;
+    int M, Hq, Hkv, dh, max_seq, qw, vts;
     float hold[2][8];
     __device__ void begin() {}
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
@@ -309,11 +474,19 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
             *reinterpret_cast<float4 *>(dst + half + 4) = make_float4(hi[4], hi[5], hi[6], hi[7]);
         } else {
             const int head = hh < Hq + Hkv ? hh - Hq : hh - Hq - Hkv;
-            KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)slot[m] * Hkv + head) * max_seq + p) * dh + e0;
-            store8(dst, lo);
-            store8(dst + half, hi);
+            if (hh < Hq + Hkv || vts == 0) {
+                KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)slot[m] * Hkv + head) * max_seq + p) * dh + e0;
+                store8(dst, lo);
+                store8(dst + half, hi);
+            } else {   // transposed V: one position of 16 dim rows
+                KT *dst = vc + (((size_t)slot[m] * Hkv + head) * dh + e0) * vts + p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { store1(dst + (size_t)e * vts, lo[e]); store1(dst + (size_t)(half + e) * vts, hi[e]); }
+            }
         }
     }
+    __device__ static void store1(float *dst, float v) { *dst = v; }
+    __device__ static void store1(bf16_t *dst, float v) { *dst = m_f32_to_bf16(v); }
     __device__ static void store8(float *dst, const float (&v)[8])
     {
         *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -567,10 +740,10 @@ void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, cons
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.qw + 2 * D.kvw) / 32; a.M = rows.n;
     a.tiles_per_wg = D.dh / 32;   // one head per workgroup
     if (kdt == DT_F32) {
-        EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, {}};
+        EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, {}};
         launch_gemm(s, a, 1, e);
     } else {
-        EpiQkv<bf16_t> e{bias, rope, rows.slot, rows.pos, q, (bf16_t *)kc, (bf16_t *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, {}};
+        EpiQkv<bf16_t> e{bias, rope, rows.slot, rows.pos, q, (bf16_t *)kc, (bf16_t *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, {}};
         launch_gemm(s, a, 1, e);
     }
 }

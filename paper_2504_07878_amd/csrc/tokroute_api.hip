@@ -18,6 +18,7 @@ constexpr size_t ALIGN = 256;
 size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
+    size_t k_layer_bytes, v_layer_bytes;
     size_t kc, vc, rope, counters, slot, tok, pos, gather, x, q, att, h, hn, attn_part, tail_part, total;
     size_t attn_part_floats;
     int max_rows, nslices;
@@ -61,7 +62,9 @@ Layout make_layout(const tr_config *c)
 {
     Layout L{};
     const size_t kvw = (size_t)c->n_kv_heads * c->head_dim, qw = (size_t)c->n_q_heads * c->head_dim;
-    const size_t cache = (size_t)c->n_layers * c->max_batch * c->max_seq * kvw * elem_size(c->kv_dtype);
+    const int vts = c->kv_dtype == TR_BF16 ? (c->max_seq + 31) / 32 * 32 : 0;   // bf16 cache: V transposed, rows padded to 32 positions
+    L.k_layer_bytes = (size_t)c->max_batch * c->max_seq * kvw * elem_size(c->kv_dtype);
+    L.v_layer_bytes = (size_t)c->max_batch * (vts ? vts : c->max_seq) * kvw * elem_size(c->kv_dtype);
     L.max_rows = c->max_batch > c->max_seq ? c->max_batch : c->max_seq;   // a decode batch or one whole prompt
     L.nslices = (c->vocab + tail_slice_rows() - 1) / tail_slice_rows();
     const size_t R = (size_t)L.max_rows;
@@ -69,7 +72,7 @@ Layout make_layout(const tr_config *c)
     L.attn_part_floats = (size_t)c->max_batch * c->n_q_heads * 32 * (c->head_dim + 4);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
-    L.kc = take(cache); L.vc = take(cache);
+    L.kc = take(L.k_layer_bytes * c->n_layers); L.vc = take(L.v_layer_bytes * c->n_layers);
     L.rope = take((size_t)c->max_seq * (c->head_dim / 2) * sizeof(float2));
     L.counters = take((size_t)c->max_batch * 2 * sizeof(long long));
     L.slot = take(R * 4); L.tok = take(R * 4); L.pos = take(R * 4); L.gather = take((size_t)c->max_batch * 4);
@@ -124,8 +127,8 @@ struct tr_ctx {
     long long prof_launches = 0;
 
     template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
-    void *kc_layer(int l) const { return ws + lay.kc + (size_t)l * c.max_batch * c.max_seq * D.kvw * elem_size(c.kv_dtype); }
-    void *vc_layer(int l) const { return ws + lay.vc + (size_t)l * c.max_batch * c.max_seq * D.kvw * elem_size(c.kv_dtype); }
+    void *kc_layer(int l) const { return ws + lay.kc + (size_t)l * lay.k_layer_bytes; }
+    void *vc_layer(int l) const { return ws + lay.vc + (size_t)l * lay.v_layer_bytes; }
     char *wt(int l, size_t which) const { return ws + lay.wt_layers + (size_t)l * lay.wt_layer_stride + which; }
     float *bias(int l) const { return reinterpret_cast<float *>(ws + lay.bias + (size_t)l * lay.bias_stride); }
     bool use_mfma(int rows) const { return lay.mfma && rows > GEMV_MAX_ROWS; }
@@ -214,7 +217,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
         launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
                         ctx->kc_layer(l), ctx->vc_layer(l));
         launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
-                         attn_part_floats, attn_part_floats ? nullptr : att, ctx->at<uint4>(L.pack_a), ncb);
+                         attn_part_floats, att, ctx->at<uint4>(L.pack_a), ncb);
         launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
         p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
         launch_prep(s, p);
@@ -302,6 +305,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     D.L = cfg->n_layers; D.d = cfg->d_model; D.Hq = cfg->n_q_heads; D.Hkv = cfg->n_kv_heads; D.dh = cfg->head_dim; D.F = cfg->d_ffn;
     D.V = cfg->vocab; D.qw = D.Hq * D.dh; D.kvw = D.Hkv * D.dh; D.G = D.Hq / D.Hkv; D.rh = cfg->router_hidden;
     D.max_batch = cfg->max_batch; D.max_seq = cfg->max_seq; D.eps = cfg->rms_eps;
+    D.vts = cfg->kv_dtype == TR_BF16 ? (cfg->max_seq + 31) / 32 * 32 : 0;
     bool aligned = true;
     auto chk = [&](const void *p) { if (p && (uintptr_t)p % 16) aligned = false; return p; };
     ctx->layers.resize((size_t)D.L);
@@ -333,6 +337,8 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     }
     hipError_t e = hipMemcpy(ctx->ws + lay.rope, rope.data(), rope.size() * sizeof(float2), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.counters, 0, (size_t)cfg->max_batch * 2 * sizeof(long long));
+    // the attention kernels read whole 32-key blocks and mask afterwards: cache positions never written must hold finite values
+    if (e == hipSuccess) e = hipMemset(ctx->ws + lay.kc, 0, lay.rope - lay.kc);
     if (e == hipSuccess && lay.mfma) {
         // one-time repack of the bf16 matrices into matrix-core tiles; q|k|v are concatenated, gate/up interleaved
         for (int l = 0; l < D.L; ++l) {

@@ -12,8 +12,16 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 
 struct Dims {
     int L, d, Hq, Hkv, dh, F, V, qw, kvw, G, rh, max_batch, max_seq;
+    int vts;   // bf16 cache: V is stored transposed, [slot][kv head][dim][vts positions] (vts = max_seq rounded up to 32);
+               // 0: V is stored like K, [slot][kv head][position][dim] (fp32 cache)
     float eps;
 };
+
+// element offset of V[slot][head][pos][dim] inside one layer's V cache
+__host__ __device__ inline size_t v_offset(const Dims &D, int slot, int head, int pos, int dim)
+{
+    return D.vts ? (((size_t)slot * D.Hkv + head) * D.dh + dim) * D.vts + pos : (((size_t)slot * D.Hkv + head) * D.max_seq + pos) * D.dh + dim;
+}
 
 // Weights of one decoder layer (device pointers in the model's storage type).
 struct LayerW {
@@ -67,6 +75,8 @@ void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w,
                 float *q, void *kc, void *vc);
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
                       float *part, size_t part_floats, float *att, void *pack, int ncb);
+void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
+                           size_t part_floats, float *att, void *pack, int ncb);
 void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb);
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, int R, float *x);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
