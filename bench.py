@@ -83,11 +83,48 @@ def cpu_baseline(s, weights, seconds_budget=20.0):
             "sample": f"{done} decode steps of {n_seq} sequences at context {ctx} on a synthetic cache (0.5B-class bf16 weights, fp32 oracle)"}
 
 
+def counters_workload(s):
+    """A plain copy kernel of known size, then the routing tail at 64 rows: the two things a --pmc pass compares."""
+    import torch
+    from paper_2504_07878_amd import synth, tokroute
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)                       # 1 GiB read + 1 GiB written
+    torch.cuda.synchronize()
+    one = s.with_(n_layers=1)
+    w = synth.make_weights(one, SEED, workers=8)
+    m = tokroute.Model(one.asdict(), w, 64, 8)
+    x = torch.from_numpy(synth.hidden_rows(SEED, "counters.x", 64, s.d_model, False)).cuda()
+    out = m.outputs(64)
+    for _ in range(5):
+        m.tail(x, out)
+    torch.cuda.synchronize()
+    log("counters workload done: 1 copy of 1 GiB, 5 tail calls at 64 rows")
+
+
+def measured_traffic():
+    """HBM traffic of the LM-head kernel from hardware counters, valid only for the kernel source it was taken on."""
+    import hashlib
+    src = os.path.join(ROOT, "paper_2504_07878_amd", "csrc", "mfma_kernels.hip")
+    if not os.path.exists(src) or LMHEAD_TRAFFIC["source_sha256"] != hashlib.sha256(open(src, "rb").read()).hexdigest():
+        return None
+    return LMHEAD_TRAFFIC["fetch_bytes"] + LMHEAD_TRAFFIC["write_bytes"]
+
+
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
+# run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
+LMHEAD_TRAFFIC = {"source_sha256": "", "fetch_bytes": 0, "write_bytes": 0}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="b64", choices=["b64", "counters"],
+                    help="b64: the benchmark; counters: one 1 GiB device copy (calibration) and a few routing-tail calls at 64 rows, "
+                         "short enough for a hardware-counter pass of rocprofv3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -103,8 +140,11 @@ def main():
         sys.exit(2)
     tokroute.load_library()
     s = synth.SLM_0P5B
+    if args.workload == "counters":
+        counters_workload(s)
+        return
     t0 = time.perf_counter()
-    weights = synth.make_weights(s, SEED)
+    weights = synth.make_weights(s, SEED, workers=8)
     log(f"weights drawn in {time.perf_counter() - t0:.1f}s")
 
     B, MAX_SEQ = 64, 1536
@@ -141,9 +181,9 @@ def main():
                    "batch": B, "max_seq": MAX_SEQ, "seed": SEED, "prefill_seconds": prefill_s,
                    "algorithmic_bytes_per_step": step_bytes, "hbm_roofline_tokens_per_s": roof_tok_s,
                    "fraction_of_hbm_roofline": tok_s / roof_tok_s},
-        "roofline": {"bound": "hbm", "kernel": "lmhead_kernel (LM head of the routing tail)", "achieved": lm_bytes / lm_avg_s / 1e9 if lm_n else None,
+        "roofline": {"bound": "hbm", "kernel": "gemm_kernel<4,14,EpiLmHead> (LM head of the routing tail, 64 rows)", "achieved": lm_bytes / lm_avg_s / 1e9 if lm_n else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": (lm_bytes / lm_avg_s / 1e9 / HBM_PEAK_GBPS) if lm_n else None,
-                     "traffic": None, "launches": lm_n, "avg_us": lm_avg_s * 1e6, "algorithmic_bytes_per_launch": lm_bytes},
+                     "traffic": measured_traffic(), "launches": lm_n, "avg_us": lm_avg_s * 1e6, "algorithmic_bytes_per_launch": lm_bytes},
     }
 
     if not args.no_extras:

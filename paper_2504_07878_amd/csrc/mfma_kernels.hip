@@ -524,6 +524,8 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
     __device__ void end(float *) {}
 };
 
+// DUMP = false keeps every vector-memory store out of the tile loop, so that the wait counters of the weight stream stay exact
+template <bool DUMP>
 struct EpiLmHead {    // running softmax statistics per batch row; logits optionally dumped
     float4 *part;     // [gridDim.x][M]
     float *logits;
@@ -535,7 +537,7 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     {
         if (m >= M) return;
         const int n0 = t * 32 + i0;
-        if (logits) {
+        if (DUMP) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 if (n0 + e < V) logits[(size_t)m * V + n0 + e] = v[e];
@@ -584,13 +586,17 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
 
 // 256 threads = 4 wavefronts, each owning KW consecutive k-steps (compile time, so that every load of the steady
 // state is unconditional and the hardware wait counters can be exact). The weight tiles of a wavefront alternate
-// between two register sets: while tile t is multiplied, the loads of tile t+1 are in flight
-// (14 KiB per wavefront, 56 KiB per compute unit at KW = 14).
+// between two register sets; a set is refilled (tile t + 2) right after the MFMAs that read it have been issued.
+// (Two dependent MFMAs on one accumulator run at half rate; the hi and lo products of the two column blocks are
+// interleaved so that consecutive MFMAs never share an accumulator.)
+constexpr int RED_FLOATS = NWAVES * 64 * 36;   // [wavefront][batch column][feature row padded to 36]
+
 template <int NCB, int KW, class Epi>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmArgs a, Epi epi_in)
 {
     constexpr int NCO = NCB / 2;
-    __shared__ __attribute__((aligned(16))) float red[NWAVES][64][36];   // [wavefront][batch column][feature row], padded
+    constexpr int P0 = KW >= 8 ? 1 : 0, P1 = KW >= 8 ? 5 : (KW > 1 ? 1 : 0), P2 = KW >= 8 ? 8 : KW - 1;   // k-steps after which the slices go
+    __shared__ __attribute__((aligned(16))) float red[RED_FLOATS];
     Epi epi = epi_in;   // per-thread epilogue state lives in registers
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ks0 = blockIdx.y * a.ksw, ks1 = min(a.KS, ks0 + a.ksw);
@@ -615,83 +621,106 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     const int t0 = blockIdx.x * a.tiles_per_wg, t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
     const size_t tile_stride = (size_t)a.KS * 64;
-    uint4 w0[KW], w1[KW];
+    uint4 w[2][KW];
+    f32x16 acc[NCO];
+    const int j = threadIdx.x & 63, i0 = (threadIdx.x >> 6) * 8;
 
-    auto load_tile = [&](int t, uint4 (&w)[KW]) {   // unconditional: t must be a valid tile
+    auto load_tile = [&](int t, uint4 (&ws)[KW]) {   // unconditional: t must be a valid tile
         const uint4 *wp = a.Wt + (size_t)t * tile_stride + lane;
 #pragma unroll
-        for (int kk = 0; kk < KW; ++kk) w[kk] = wp[(size_t)koff[kk] * 64];
+        for (int kk = 0; kk < KW; ++kk) ws[kk] = wp[(size_t)koff[kk] * 64];
     };
-    const int j = threadIdx.x & 63, i0 = (threadIdx.x >> 6) * 8;
-    f32x16 acc[NCO];
-    auto mfma_tile = [&](const uint4 (&w)[KW]) {
+    auto mfma_step = [&](const uint4 &wk, int kk) {
+        const bf16x8 wv = __builtin_bit_cast(bf16x8, wk);
 #pragma unroll
-        for (int co = 0; co < NCO; ++co)
+        for (int hl = 0; hl < 2; ++hl)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[co][r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KW; ++kk) {
-            const bf16x8 wv = __builtin_bit_cast(bf16x8, w[kk]);
-#pragma unroll
-            for (int co = 0; co < NCO; ++co) {
-                acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][co], acc[co], 0, 0, 0);
-                acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][NCO + co], acc[co], 0, 0, 0);
-            }
-        }
+            for (int co = 0; co < NCO; ++co) acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][hl * NCO + co], acc[co], 0, 0, 0);
     };
-    auto post_tile = [&](int t) {
+    // the three slices of a tile's reduction + epilogue
+    auto put = [&]() {
         __syncthreads();   // the previous tile has been read
 #pragma unroll
         for (int co = 0; co < NCO; ++co)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)   // registers 4qd..4qd+3 are 4 consecutive feature rows of one batch column
-                *reinterpret_cast<float4 *>(&red[wave][co * 32 + (lane & 31)][qd * 8 + (lane >> 5) * 4]) =
+                *reinterpret_cast<float4 *>(&red[(wave * 64 + co * 32 + (lane & 31)) * 36 + qd * 8 + (lane >> 5) * 4]) =
                     make_float4(acc[co][4 * qd], acc[co][4 * qd + 1], acc[co][4 * qd + 2], acc[co][4 * qd + 3]);
+    };
+    auto get = [&](float (&v)[8]) {
         __syncthreads();
-        float v[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) v[r] = 0.f;
         if (j < 32 * NCO) {
 #pragma unroll
             for (int ww = 0; ww < NWAVES; ++ww) {
-                const float4 lo4 = *reinterpret_cast<const float4 *>(&red[ww][j][i0]);
-                const float4 hi4 = *reinterpret_cast<const float4 *>(&red[ww][j][i0 + 4]);
+                const float4 lo4 = *reinterpret_cast<const float4 *>(&red[(ww * 64 + j) * 36 + i0]);
+                const float4 hi4 = *reinterpret_cast<const float4 *>(&red[(ww * 64 + j) * 36 + i0 + 4]);
                 v[0] += lo4.x; v[1] += lo4.y; v[2] += lo4.z; v[3] += lo4.w;
                 v[4] += hi4.x; v[5] += hi4.y; v[6] += hi4.z; v[7] += hi4.w;
             }
         }
+    };
+    auto post_tile = [&](int t) {
+        float v[8];
+        put();
+        get(v);
         epi.tile(t, group * 64 + j, i0, v);
+    };
+    auto mfma_tile = [&](const uint4 (&ws)[KW]) {
+#pragma unroll
+        for (int co = 0; co < NCO; ++co)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[co][r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KW; ++kk) mfma_step(ws[kk], kk);
     };
 
     epi.begin();
     int t = t0;
-    if (t < t1) load_tile(t, w0);
-    if (t + 1 < t1) load_tile(t + 1, w1);
-    // steady state: two tiles per trip, every load unconditional. A register set is refilled as soon as its MFMAs have
-    // been issued, so the loads of the tile after next fly while this tile is reduced and the next one is multiplied.
-    for (; t + 3 < t1; t += 2) {
-        mfma_tile(w0);
-        load_tile(t + 2, w0);
-        post_tile(t);
-        mfma_tile(w1);
-        load_tile(t + 3, w1);
-        post_tile(t + 1);
+    if (t1 - t0 >= 4) {
+        // long tile ranges: nothing conditional between the first load and the end of the steady state, so the
+        // compiler can wait for exactly the registers it needs and leave the younger loads in flight
+        load_tile(t0, w[0]);
+        load_tile(t0 + 1, w[1]);
+        for (; t + 3 < t1; t += 2) {
+            mfma_tile(w[0]);
+            load_tile(t + 2, w[0]);
+            post_tile(t);
+            mfma_tile(w[1]);
+            load_tile(t + 3, w[1]);
+            post_tile(t + 1);
+        }
+    } else {
+        if (t < t1) load_tile(t, w[0]);
+        if (t + 1 < t1) load_tile(t + 1, w[1]);
     }
-    const int rest = t1 - t;   // 0..3 tiles left; w0 holds tile t, w1 tile t+1
-    if (rest >= 1) { mfma_tile(w0); if (rest >= 3) load_tile(t + 2, w0); post_tile(t); }
-    if (rest >= 2) { mfma_tile(w1); post_tile(t + 1); }
-    if (rest >= 3) { mfma_tile(w0); post_tile(t + 2); }
-    epi.end(&red[0][0][0]);
+    // up to three tiles are left; w[0] holds tile t, w[1] tile t + 1
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        if (t + i < t1) {
+            mfma_tile(w[i & 1]);
+            if (i == 0 && t + 2 < t1) load_tile(t + 2, w[0]);
+            post_tile(t + i);
+        }
+    }
+    epi.end(red);
+}
+
+template <int NCB, int KW, class Epi>
+static void launch_gemm_one(hipStream_t s, const GemmArgs &a, dim3 grid, const Epi &epi)
+{
+    hipLaunchKernelGGL((gemm_kernel<NCB, KW, Epi>), grid, dim3(256), 0, s, a, epi);
 }
 
 template <int NCB, class Epi>
 static void launch_gemm_kw(hipStream_t s, const GemmArgs &a, dim3 grid, const Epi &epi)
 {
     const int per = (a.ksw + NWAVES - 1) / NWAVES;
-    if (per <= 2) hipLaunchKernelGGL((gemm_kernel<NCB, 2, Epi>), grid, dim3(256), 0, s, a, epi);
-    else if (per <= 4) hipLaunchKernelGGL((gemm_kernel<NCB, 4, Epi>), grid, dim3(256), 0, s, a, epi);
-    else if (per <= 8) hipLaunchKernelGGL((gemm_kernel<NCB, 8, Epi>), grid, dim3(256), 0, s, a, epi);
-    else hipLaunchKernelGGL((gemm_kernel<NCB, 14, Epi>), grid, dim3(256), 0, s, a, epi);
+    if (per <= 2) launch_gemm_one<NCB, 2>(s, a, grid, epi);
+    else if (per <= 4) launch_gemm_one<NCB, 4>(s, a, grid, epi);
+    else if (per <= 8) launch_gemm_one<NCB, 8>(s, a, grid, epi);
+    else launch_gemm_one<NCB, 14>(s, a, grid, epi);
 }
 
 template <class Epi>
@@ -769,8 +798,13 @@ void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.V + 31) / 32; a.M = M;
     a.tiles_per_wg = (a.n_tiles + 255) / 256;
-    EpiLmHead e{(float4 *)part, logits, M, D.V, 0.f, 0.f, 0};
-    launch_gemm(s, a, 1, e);
+    if (logits) {
+        EpiLmHead<true> e{(float4 *)part, logits, M, D.V, 0.f, 0.f, 0};
+        launch_gemm(s, a, 1, e);
+    } else {
+        EpiLmHead<false> e{(float4 *)part, nullptr, M, D.V, 0.f, 0.f, 0};
+        launch_gemm(s, a, 1, e);
+    }
 }
 
 }  // namespace tr
