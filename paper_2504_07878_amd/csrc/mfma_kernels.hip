@@ -408,6 +408,7 @@ struct GemmArgs {
     int n_tiles;
     int tiles_per_wg;
     int M;              // rows in total (groups of 64 along gridDim.z)
+    int remap_groups;   // > 0: 1-D grid; the row groups of one tile range are placed on the same XCD, next to each other in time
 };
 
 // Epilogues receive, per thread, 8 consecutive output features (rows i0..i0+7 of tile t) of one batch row.
@@ -415,6 +416,7 @@ struct GemmArgs {
 struct EpiPartial {   // split-K partial sums: part[split][m][n]
     float *part;
     int N, M;
+    __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
@@ -437,6 +439,7 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
     KT *kc, *vc;
     int M, Hq, Hkv, dh, max_seq, qw, vts;
     float hold[2][8];
+    __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
@@ -506,6 +509,7 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
     uint4 *hpack;     // [group][F/16][NCB][64]
     int M, F, ncb;
     float hold[8];
+    __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
@@ -531,7 +535,8 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     float *logits;
     int M, V;
     float mx, sum;
-    int idx;
+    int idx, bx, grp, nwg;   // nwg: workgroups that own tiles (the grid may be padded)
+    __device__ void block(int b, int g) { bx = b; grp = g; }
     __device__ void begin() { mx = -INFINITY; sum = 0.f; idx = 0x7fffffff; }
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
@@ -566,8 +571,8 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
         s[threadIdx.x] = make_float4(mx, __int_as_float(idx), sum, 0.f);
         __syncthreads();
         const int j = threadIdx.x;
-        const int m = blockIdx.z * 64 + j;
-        if (j < 64 && m < M) {
+        const int m = grp * 64 + j;
+        if (j < 64 && m < M && bx < nwg) {
             float Mx = -INFINITY; int I = 0x7fffffff;
             for (int b = 0; b < 4; ++b) {
                 const float4 p = s[b * 64 + j];
@@ -579,7 +584,7 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
                 const float4 p = s[b * 64 + j];
                 if (p.x > -INFINITY) S += p.z * expf(p.x - Mx);
             }
-            part[(size_t)blockIdx.x * M + m] = make_float4(Mx, __int_as_float(I), S, 0.f);
+            part[(size_t)bx * M + m] = make_float4(Mx, __int_as_float(I), S, 0.f);
         }
     }
 };
@@ -603,7 +608,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int per = (ks1 - ks0 + NWAVES - 1) / NWAVES;   // <= KW
     const int wk0 = ks0 + wave * per;
     const int nk = max(0, min(ks1, wk0 + per) - wk0);
-    const int group = blockIdx.z;
+    int bx = blockIdx.x, group = blockIdx.z;
+    if (a.remap_groups > 0) {   // workgroups are dealt to the 8 XCDs round-robin: keep the groups of a tile range on one XCD
+        const int xcd = bx & 7, slot = bx >> 3;
+        group = slot % a.remap_groups;
+        bx = (slot / a.remap_groups) * 8 + xcd;
+    }
+    epi.block(bx, group);
 
     // resident activations of this wavefront's k-steps (zero beyond its share, so the extra products vanish)
     bf16x8 b[KW][NCB];
@@ -619,7 +630,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     }
 
-    const int t0 = blockIdx.x * a.tiles_per_wg, t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
+    const int t0 = min(bx * a.tiles_per_wg, a.n_tiles), t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
     const size_t tile_stride = (size_t)a.KS * 64;
     uint4 w[2][KW];
     f32x16 acc[NCO];
@@ -727,7 +738,8 @@ template <class Epi>
 static void launch_gemm(hipStream_t s, const GemmArgs &a, int nsplit, const Epi &epi)
 {
     const int groups = (a.M + 63) / 64;
-    const dim3 grid((a.n_tiles + a.tiles_per_wg - 1) / a.tiles_per_wg, nsplit, groups);
+    dim3 grid((a.n_tiles + a.tiles_per_wg - 1) / a.tiles_per_wg, nsplit, groups);
+    if (a.remap_groups > 0) grid = dim3((grid.x + 7) / 8 * 8 * groups, 1, 1);
     if (a.M <= 32) launch_gemm_kw<2>(s, a, grid, epi);
     else launch_gemm_kw<4>(s, a, grid, epi);
 }
@@ -798,11 +810,12 @@ void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.V + 31) / 32; a.M = M;
     a.tiles_per_wg = (a.n_tiles + 255) / 256;
+    a.remap_groups = M > 64 ? (M + 63) / 64 : 0;
     if (logits) {
-        EpiLmHead<true> e{(float4 *)part, logits, M, D.V, 0.f, 0.f, 0};
+        EpiLmHead<true> e{(float4 *)part, logits, M, D.V, 0.f, 0.f, 0, 0, 0, lmhead_mfma_wgs(D.V)};
         launch_gemm(s, a, 1, e);
     } else {
-        EpiLmHead<false> e{(float4 *)part, nullptr, M, D.V, 0.f, 0.f, 0};
+        EpiLmHead<false> e{(float4 *)part, nullptr, M, D.V, 0.f, 0.f, 0, 0, 0, lmhead_mfma_wgs(D.V)};
         launch_gemm(s, a, 1, e);
     }
 }
