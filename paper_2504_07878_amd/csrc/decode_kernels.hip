@@ -110,12 +110,44 @@ __device__ __forceinline__ void dots_step(const Raw8<WT> (&rw)[NR], const Raw8<W
 
 constexpr int KC = 2048;   // activation columns staged in LDS at a time
 
+// Where the staged activations come from: plain fp32 rows ...
+struct StageRows {
+    const float *x;
+    size_t stride;
+    __device__ __forceinline__ float4 load(int m, int k) const { return *reinterpret_cast<const float4 *>(x + (size_t)m * stride + k); }
+    __device__ __forceinline__ void advance(int rows) { x += (size_t)rows * stride; }
+};
+// ... or attention partials merged on the fly (fixed order over the chunks)
+struct StageAttn {
+    AttnPending a;
+    int Hq, dh, r0;
+    __device__ __forceinline__ float4 load(int m, int k) const
+    {
+        const int r = r0 + m, head = k / dh, d0 = k % dh, ps = dh + 4;
+        const int live = min(a.nchunks, (a.pos[r] + a.chunk) / a.chunk);
+        const float *pp = a.part + ((size_t)r * Hq + head) * a.nchunks * ps;
+        float M = -INFINITY;
+        for (int c = 0; c < live; ++c) M = fmaxf(M, pp[c * ps + dh]);
+        float L = 0.f;
+        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int c = 0; c < live; ++c) {
+            const float w = __expf(pp[c * ps + dh] - M);
+            const float4 v = *reinterpret_cast<const float4 *>(pp + c * ps + d0);
+            L = fmaf(pp[c * ps + dh + 1], w, L);
+            o.x = fmaf(v.x, w, o.x); o.y = fmaf(v.y, w, o.y); o.z = fmaf(v.z, w, o.z); o.w = fmaf(v.w, w, o.w);
+        }
+        const float inv = 1.0f / L;
+        return make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+    }
+    __device__ __forceinline__ void advance(int rows) { r0 += rows; }
+};
+
 // Workgroup-wide GEMV step: the 4 wavefronts of a workgroup each own NR weight rows; the MB activation rows are
 // staged through LDS in chunks of KC columns (read once from memory per workgroup, then broadcast from LDS, which keeps
 // the vector-memory pipe free for the weight stream). Every wavefront of the workgroup must call this (barriers inside).
 // xs: LDS buffer of MB*KC floats. Rows m >= mvalid are read as zeros. Results are valid in every lane.
-template <typename WT, int NR, int MB, bool NORM>
-__device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *gain, const float *x, size_t xstride, int mvalid, int K, float *xs,
+template <typename WT, int NR, int MB, bool NORM, class Stage>
+__device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *gain, const Stage &src, int mvalid, int K, float *xs,
                                         float (&acc)[NR][MB], float (&ss)[MB])
 {
     constexpr int U = 4;
@@ -132,7 +164,7 @@ __device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *g
         for (int idx = threadIdx.x; idx < MB * (kc / 4); idx += 256) {
             const int m = idx / (kc / 4), c4 = idx % (kc / 4);
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (m < mvalid) v = *reinterpret_cast<const float4 *>(x + (size_t)m * xstride + kc0 + c4 * 4);
+            if (m < mvalid) v = src.load(m, kc0 + c4 * 4);
             *reinterpret_cast<float4 *>(xs + m * KC + c4 * 4) = v;
         }
         __syncthreads();
@@ -264,7 +296,7 @@ __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float 
     const WT *const wrow[2] = {W + (size_t)n1 * D.d, W + (size_t)n2 * D.d};
     const int r0 = blockIdx.y * MB;
     float acc[2][MB], ss[MB];
-    wg_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, x + (size_t)r0 * D.d, D.d, rows.n - r0, D.d, xs, acc, ss);
+    wg_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, rows.n - r0, D.d, xs, acc, ss);
     if ((threadIdx.x & 63) != 0 || pair_raw >= npairs) return;
     const float b1 = bias ? widen(bias, n1) : 0.f, b2 = bias ? widen(bias, n2) : 0.f;
 #pragma unroll
@@ -642,10 +674,11 @@ static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, 
 
 // att (fp32 [R][qw]) and/or pack (packed hi/lo activations of the output projection) receive the result.
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
-                      float *part, size_t part_floats, float *att, void *pack, int ncb)
+                      float *part, size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
 {
+    if (defer) defer->nchunks = 0;
     if (kdt == DT_BF16) {   // bf16 cache: V is stored transposed and attention runs on the matrix cores
-        launch_attention_mfma(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb);
+        launch_attention_mfma(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb, defer);
         return;
     }
     bool done = false;
@@ -667,8 +700,8 @@ void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, con
 
 // ------------------------------------------------------------------ attention output: x += Wo a
 
-template <typename WT, int MB>
-__global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, const float *in, int R, int N, int K, float *x)
+template <typename WT, int MB, class Stage>
+__global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, Stage in, int R, int N, int K, float *x)
 {
     __shared__ __attribute__((aligned(16))) float xs[MB * KC];
     const int n_raw = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 2;     // two consecutive output rows per wavefront
@@ -676,7 +709,9 @@ __global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, const f
     const WT *const wrow[2] = {W + (size_t)n * K, W + (size_t)n2 * K};
     const int r0 = blockIdx.y * MB;
     float acc[2][MB], ss[MB];
-    wg_dots<WT, 2, MB, false>(wrow, nullptr, in + (size_t)r0 * K, K, R - r0, K, xs, acc, ss);
+    Stage src = in;
+    src.advance(r0);
+    wg_dots<WT, 2, MB, false>(wrow, nullptr, src, R - r0, K, xs, acc, ss);
     if ((threadIdx.x & 63) != 0 || n_raw >= N) return;
 #pragma unroll
     for (int m = 0; m < MB; ++m)
@@ -686,25 +721,33 @@ __global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, const f
         }
 }
 
-template <typename WT>
-static void launch_residual_gemv(hipStream_t s, const void *W, const float *in, int R, int N, int K, float *x)
+template <typename WT, class Stage>
+static void launch_residual_gemv(hipStream_t s, const void *W, const Stage &in, int R, int N, int K, float *x)
 {
     const int gx = (N + 7) / 8;
-    if (R == 1) hipLaunchKernelGGL((residual_gemv_kernel<WT, 1>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
-    else if (R == 2) hipLaunchKernelGGL((residual_gemv_kernel<WT, 2>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
-    else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    if (R == 1) hipLaunchKernelGGL((residual_gemv_kernel<WT, 1, Stage>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    else if (R == 2) hipLaunchKernelGGL((residual_gemv_kernel<WT, 2, Stage>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4, Stage>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
 }
 
-void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, int R, float *x)
+void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x)
 {
-    if (wdt == DT_F32) launch_residual_gemv<float>(s, wo, att, R, D.d, D.qw, x);
-    else launch_residual_gemv<bf16_t>(s, wo, att, R, D.d, D.qw, x);
+    if (pend.nchunks > 0) {
+        const StageAttn st{pend, D.Hq, D.dh, 0};
+        if (wdt == DT_F32) launch_residual_gemv<float>(s, wo, st, R, D.d, D.qw, x);
+        else launch_residual_gemv<bf16_t>(s, wo, st, R, D.d, D.qw, x);
+        return;
+    }
+    const StageRows st{att, (size_t)D.qw};
+    if (wdt == DT_F32) launch_residual_gemv<float>(s, wo, st, R, D.d, D.qw, x);
+    else launch_residual_gemv<bf16_t>(s, wo, st, R, D.d, D.qw, x);
 }
 
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x)
 {
-    if (wdt == DT_F32) launch_residual_gemv<float>(s, wd, h, R, D.d, D.F, x);
-    else launch_residual_gemv<bf16_t>(s, wd, h, R, D.d, D.F, x);
+    const StageRows st{h, (size_t)D.F};
+    if (wdt == DT_F32) launch_residual_gemv<float>(s, wd, st, R, D.d, D.F, x);
+    else launch_residual_gemv<bf16_t>(s, wd, st, R, D.d, D.F, x);
 }
 
 // ------------------------------------------------------------------ FFN input: h = silu(Wg n) * (Wu n), n = RMSNorm(x; ln2)
@@ -718,7 +761,7 @@ __global__ __launch_bounds__(256) void gateup_kernel(Dims D, const WT *wg, const
     const WT *const wrow[2] = {wg + (size_t)f * D.d, wu + (size_t)f * D.d};
     const int r0 = blockIdx.y * MB;
     float acc[2][MB], ss[MB];
-    wg_dots<WT, 2, MB, true>(wrow, gain, x + (size_t)r0 * D.d, D.d, R - r0, D.d, xs, acc, ss);
+    wg_dots<WT, 2, MB, true>(wrow, gain, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, R - r0, D.d, xs, acc, ss);
     if ((threadIdx.x & 63) != 0 || f_raw >= D.F) return;
 #pragma unroll
     for (int m = 0; m < MB; ++m)

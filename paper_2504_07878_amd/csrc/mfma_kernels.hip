@@ -378,8 +378,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
 }
 
 void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
-                           size_t part_floats, float *att, void *pack, int ncb)
+                           size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
 {
+    if (defer) defer->nchunks = 0;
     // decode: up to 32 chunks of the context per row, merged afterwards; prompts: one wavefront walks the whole context of a row
     size_t room = part_floats / ((size_t)rows.n * D.Hq * (D.dh + 4));   // chunks per row that fit the partials buffer
     if (room > 64) room = 64;
@@ -394,6 +395,10 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
         hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
     else
         hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
+    if (nchunks > 1 && defer && !pack && rows.n <= 4 && nchunks <= 16) {   // the consumer merges
+        defer->part = part; defer->pos = rows.pos; defer->nchunks = nchunks; defer->chunk = chunk;
+        return;
+    }
     if (nchunks > 1) launch_attn_merge(s, D, part, nchunks, rows, chunk, pack ? nullptr : att, pack, ncb);
     else if (pack) launch_pack(s, att, rows.n, D.qw, pack, ncb);
 }
@@ -408,6 +413,7 @@ struct GemmArgs {
     int n_tiles;
     int tiles_per_wg;
     int M;              // rows in total (groups of 64 along gridDim.z)
+    int half;           // 1: every 64-row group is served by two workgroups of 32 rows each (more workgroups for short tile ranges)
     int remap_groups;   // > 0: 1-D grid; the row groups of one tile range are placed on the same XCD, next to each other in time
 };
 
@@ -615,6 +621,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         bx = (slot / a.remap_groups) * 8 + xcd;
     }
     epi.block(bx, group);
+    // half mode: the packed activations hold 4 column blocks per 64-row group; this workgroup takes {h, 2 + h}
+    const int pgroup = a.half ? group >> 1 : group, hsel = a.half ? group & 1 : 0, pncb = a.half ? 4 : NCB;
+    const int row0 = pgroup * 64 + hsel * 32;
 
     // resident activations of this wavefront's k-steps (zero beyond its share, so the extra products vanish)
     bf16x8 b[KW][NCB];
@@ -625,7 +634,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) {
             uint4 u = make_uint4(0, 0, 0, 0);
-            if (kk < nk) u = a.pack[(((size_t)group * a.KS + wk0 + kk) * NCB + cb) * 64 + lane];
+            if (kk < nk) u = a.pack[(((size_t)pgroup * a.KS + wk0 + kk) * pncb + (a.half ? cb * 2 + hsel : cb)) * 64 + lane];
             b[kk][cb] = __builtin_bit_cast(bf16x8, u);
         }
     }
@@ -676,7 +685,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         float v[8];
         put();
         get(v);
-        epi.tile(t, group * 64 + j, i0, v);
+        if (j < 32 * NCO) epi.tile(t, row0 + j, i0, v);   // lanes past the column blocks of this workgroup hold nothing
     };
     auto mfma_tile = [&](const uint4 (&ws)[KW]) {
 #pragma unroll
@@ -740,8 +749,11 @@ static void launch_gemm(hipStream_t s, const GemmArgs &a, int nsplit, const Epi 
     const int groups = (a.M + 63) / 64;
     dim3 grid((a.n_tiles + a.tiles_per_wg - 1) / a.tiles_per_wg, nsplit, groups);
     if (a.remap_groups > 0) grid = dim3((grid.x + 7) / 8 * 8 * groups, 1, 1);
-    if (a.M <= 32) launch_gemm_kw<2>(s, a, grid, epi);
-    else launch_gemm_kw<4>(s, a, grid, epi);
+    if (a.half && a.M > 32) { grid.z = 2 * groups; launch_gemm_kw<2>(s, a, grid, epi); return; }
+    GemmArgs b = a;
+    b.half = 0;
+    if (a.M <= 32) launch_gemm_kw<2>(s, b, grid, epi);
+    else launch_gemm_kw<4>(s, b, grid, epi);
 }
 
 int mfma_ncb(int M) { return M <= 32 ? 2 : 4; }
@@ -780,6 +792,7 @@ void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, cons
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.qw + 2 * D.kvw) / 32; a.M = rows.n;
     a.tiles_per_wg = D.dh / 32;   // one head per workgroup
+    a.half = 1;
     if (kdt == DT_F32) {
         EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, {}};
         launch_gemm(s, a, 1, e);

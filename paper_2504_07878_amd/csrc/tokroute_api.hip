@@ -194,12 +194,13 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
     const size_t attn_part_floats = R <= ctx->c.max_batch ? L.attn_part_floats : 0;
     launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
     if (!ctx->use_mfma(R)) {
+        AttnPending pend{};
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
             launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
             launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
-                             attn_part_floats, att, nullptr, 0);
-            launch_oproj(s, ctx->c.dtype, D, w.wo, att, R, x);
+                             attn_part_floats, att, nullptr, 0, &pend);
+            launch_oproj(s, ctx->c.dtype, D, w.wo, att, pend, R, x);
             launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
             launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
         }
@@ -217,7 +218,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
         launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
                         ctx->kc_layer(l), ctx->vc_layer(l));
         launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
-                         attn_part_floats, att, ctx->at<uint4>(L.pack_a), ncb);
+                         attn_part_floats, att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
         launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
         p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
         launch_prep(s, p);
@@ -235,7 +236,7 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     const Layout &L = ctx->lay;
     hipEvent_t e0, e1;
     next_events(ctx, &e0, &e1);
-    if (!ctx->lay.mfma || (pending == 0 && !ctx->use_mfma(t.n))) {
+    if (!ctx->lay.mfma) {
         t.x = x + (size_t)row0 * D.d;
         launch_tail(s, ctx->c.dtype, D, t, e0, e1);
         return;
@@ -247,12 +248,9 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     launch_prep(s, p);
     t.x = x + (size_t)row0 * D.d;
     if (e0) (void)hipEventRecord(e0, s);
-    if (ctx->use_mfma(t.n)) {
-        t.nslices = lmhead_mfma_wgs(D.V);
-        launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits);
-    } else {
-        launch_lmhead_gemv(s, ctx->c.dtype, D, t);
-    }
+    // the head is streamed by the matrix-core kernel for any row count: one row costs the same bytes as 32
+    t.nslices = lmhead_mfma_wgs(D.V);
+    launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits);
     if (e1) (void)hipEventRecord(e1, s);
     launch_tail_final(s, ctx->c.dtype, D, t);
 }

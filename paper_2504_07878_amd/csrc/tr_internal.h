@@ -34,6 +34,14 @@ struct Rows {
     int n;
 };
 
+// Attention partials that have not been merged yet: the consumer (the output projection of the GEMV path) merges them
+// while it stages its activations, which saves a kernel when only a few rows are in flight.
+struct AttnPending {
+    const float *part;   // [row][head][nchunks][dh + 4]: unnormalised weighted V sums, then running max and sum of exponentials
+    const int *pos;
+    int nchunks, chunk;  // nchunks == 0: nothing pending, the merged rows are in the fp32 buffer
+};
+
 constexpr int MAX_SPLITS = 16;   // most split-K partial buffers a linear layer may produce
 
 // residual update + RMSNorm + pack (see mfma_kernels.hip)
@@ -74,11 +82,11 @@ void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, 
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope,
                 float *q, void *kc, void *vc);
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
-                      float *part, size_t part_floats, float *att, void *pack, int ncb);
+                      float *part, size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer);
 void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
-                           size_t part_floats, float *att, void *pack, int ncb);
+                           size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer);
 void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb);
-void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, int R, float *x);
+void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x);
 void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1);
