@@ -668,17 +668,18 @@ static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, 
     if ((size_t)rows.n * D.Hq * nchunks * (DH + 4) > part_floats) return false;
     hipLaunchKernelGGL((attn_wave_kernel<KT, DH>), dim3(rows.n, D.Hkv, (nchunks + 3) / 4), dim3(256), 0, s, D, q, (const KT *)kc, (const KT *)vc,
                        rows, chunk, nchunks, part);
-    launch_attn_merge(s, D, part, nchunks, rows, chunk, pack ? nullptr : att, pack, ncb);
+    RowsInline none{};
+    launch_attn_merge(s, D, part, nchunks, rows, none, chunk, pack ? nullptr : att, pack, ncb);
     return true;
 }
 
 // att (fp32 [R][qw]) and/or pack (packed hi/lo activations of the output projection) receive the result.
-void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
-                      float *part, size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
+void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, const RowsInline &ri,
+                      int max_ctx, float *part, size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
     if (kdt == DT_BF16) {   // bf16 cache: V is stored transposed and attention runs on the matrix cores
-        launch_attention_mfma(s, D, q, kc, vc, rows, max_ctx, part, part_floats, att, pack, ncb, defer);
+        launch_attention_mfma(s, D, q, kc, vc, rows, ri, max_ctx, part, part_floats, att, pack, ncb, defer);
         return;
     }
     bool done = false;

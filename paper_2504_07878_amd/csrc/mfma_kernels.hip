@@ -181,10 +181,11 @@ void launch_pack(hipStream_t s, const float *in, int M, int K, void *pack, int n
 
 // Merge of the per-chunk attention partials of one row (fixed order over chunks), written as fp32 rows and/or as
 // packed hi/lo activations for the output projection. One thread per 8 consecutive dims of a head.
-__global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos, int chunk, float *att, uint4 *pack, int ncb)
+__global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos, RowsInline ri, int chunk, float *att, uint4 *pack, int ncb)
 {
     const int r = blockIdx.x, ps = dh + 4;
-    const int live = min(nchunks, (pos[r] + chunk) / chunk);   // chunks that hold at least one key of this row
+    const int p = ri.n ? ri.pos[r] : pos[r];
+    const int live = min(nchunks, (p + chunk) / chunk);   // chunks that hold at least one key of this row
     for (int k8 = threadIdx.x; k8 < qw / 8; k8 += blockDim.x) {
         const int head = (k8 * 8) / dh, d0 = (k8 * 8) % dh;
         const float *pp = part + ((size_t)r * Hq + head) * nchunks * ps;
@@ -228,10 +229,10 @@ __global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, in
     }
 }
 
-void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb)
+void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, const RowsInline &ri, int chunk, float *att, void *pack, int ncb)
 {
     const int threads = D.qw / 8 >= 512 ? 512 : (D.qw / 8 + 63) / 64 * 64;
-    hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(threads), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, chunk, att, (uint4 *)pack, ncb);
+    hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(threads), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, ri, chunk, att, (uint4 *)pack, ncb);
 }
 
 // ------------------------------------------------------------------ grouped-query attention on the matrix cores
@@ -253,17 +254,17 @@ __device__ __forceinline__ void to_hi_lo(const float (&v)[8], bf16x8 &hi, bf16x8
 }
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, int chunk, int nchunks,
-                                                        float *part, float *att)
+__global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, RowsInline ri, int chunk,
+                                                        int nchunks, float *part, float *att)
 {
     constexpr int KSQ = DH / 16, DB = DH / 32, PS = DH + 4;
     const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (item >= rows.n * nchunks) return;
-    const int r = item / nchunks, c = item % nchunks, g = blockIdx.y;
+    const int r = __builtin_amdgcn_readfirstlane(item / nchunks), c = item % nchunks, g = blockIdx.y;   // one row per wavefront
     const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
-    const int ctx = rows.pos[r] + 1;
+    const int ctx = (ri.n ? ri.pos[r] : rows.pos[r]) + 1;
     const int j0 = c * chunk, j1 = min(ctx, j0 + chunk);
-    const int slot = rows.slot[r];
+    const int slot = ri.n ? ri.slot[r] : rows.slot[r];
 
     bf16x8 qh[KSQ], ql[KSQ];
     {
@@ -377,7 +378,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     }
 }
 
-void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
+void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, const RowsInline &ri, int max_ctx, float *part,
                            size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
@@ -392,14 +393,14 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
     const dim3 grid((rows.n * nchunks + 3) / 4, D.Hkv);
     float *direct = nchunks == 1 ? att : nullptr;
     if (D.dh == 64)
-        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
+        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, chunk, nchunks, part, direct);
     else
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
+        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, chunk, nchunks, part, direct);
     if (nchunks > 1 && defer && !pack && rows.n <= 4 && nchunks <= 16) {   // the consumer merges
         defer->part = part; defer->pos = rows.pos; defer->nchunks = nchunks; defer->chunk = chunk;
         return;
     }
-    if (nchunks > 1) launch_attn_merge(s, D, part, nchunks, rows, chunk, pack ? nullptr : att, pack, ncb);
+    if (nchunks > 1) launch_attn_merge(s, D, part, nchunks, rows, ri, chunk, pack ? nullptr : att, pack, ncb);
     else if (pack) launch_pack(s, att, rows.n, D.qw, pack, ncb);
 }
 
