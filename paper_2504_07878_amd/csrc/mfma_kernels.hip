@@ -229,8 +229,72 @@ __global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, in
     }
 }
 
+// The same merge for a few rows with many chunks: one workgroup per (row, head), the chunks spread over 16 thread
+// groups whose results are combined through LDS in a fixed order, so that no thread walks more than
+// ceil(nchunks / 16) chunks one after the other. Up to 64 chunks, dh <= 128.
+__global__ __launch_bounds__(256) void attn_merge_wide_kernel(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos, RowsInline ri,
+                                                              int chunk, float *att, uint4 *pack, int ncb)
+{
+    __shared__ float s_m[64];
+    __shared__ float s_l[16];
+    __shared__ __attribute__((aligned(16))) float s_o[16][128];
+    const int r = blockIdx.x, head = blockIdx.y, ps = dh + 4, tid = threadIdx.x;
+    const int p = ri.n ? ri.pos[r] : pos[r];
+    const int live = min(nchunks, (p + chunk) / chunk);
+    const float *pp = part + ((size_t)r * Hq + head) * nchunks * ps;
+    if (tid < 64) s_m[tid] = tid < live ? pp[tid * ps + dh] : -INFINITY;
+    __syncthreads();
+    float M = -INFINITY;
+    for (int c = 0; c < live; ++c) M = fmaxf(M, s_m[c]);
+    const int d8 = dh / 8, cl = tid / d8, k8 = tid % d8;      // 16 chunk lanes x dh/8 thread columns (cl < 16 when tid < 2*dh)
+    if (cl < 16) {
+        float L = 0.f, o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = cl + 16 * u;
+            const float *pc = pp + min(c, live - 1) * ps;
+            const float w = c < live ? __expf(s_m[min(c, 63)] - M) : 0.f;
+            const float lc = pc[dh + 1];
+            const float4 a = *reinterpret_cast<const float4 *>(pc + k8 * 8), b = *reinterpret_cast<const float4 *>(pc + k8 * 8 + 4);
+            L = fmaf(lc, w, L);
+            o[0] = fmaf(a.x, w, o[0]); o[1] = fmaf(a.y, w, o[1]); o[2] = fmaf(a.z, w, o[2]); o[3] = fmaf(a.w, w, o[3]);
+            o[4] = fmaf(b.x, w, o[4]); o[5] = fmaf(b.y, w, o[5]); o[6] = fmaf(b.z, w, o[6]); o[7] = fmaf(b.w, w, o[7]);
+        }
+        *reinterpret_cast<float4 *>(&s_o[cl][k8 * 8]) = make_float4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<float4 *>(&s_o[cl][k8 * 8 + 4]) = make_float4(o[4], o[5], o[6], o[7]);
+        if (k8 == 0) s_l[cl] = L;
+    }
+    __syncthreads();
+    if (tid < d8) {
+        float L = 0.f, o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+        for (int g = 0; g < 16; ++g) {
+            L += s_l[g];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += s_o[g][tid * 8 + e];
+        }
+        const float inv = 1.0f / L;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= inv;
+        const int col8 = (head * dh) / 8 + tid;
+        if (att) {
+            *reinterpret_cast<float4 *>(att + (size_t)r * qw + col8 * 8) = make_float4(o[0], o[1], o[2], o[3]);
+            *reinterpret_cast<float4 *>(att + (size_t)r * qw + col8 * 8 + 4) = make_float4(o[4], o[5], o[6], o[7]);
+        }
+        if (pack) store_packed(pack + (size_t)(r >> 6) * (qw / 16) * ncb * 64, ncb, r & 63, col8, o);
+    }
+}
+
 void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, const RowsInline &ri, int chunk, float *att, void *pack, int ncb)
 {
+    if (rows.n <= 8 && nchunks > 8 && nchunks <= 64 && D.dh <= 128) {
+        hipLaunchKernelGGL(attn_merge_wide_kernel, dim3(rows.n, D.Hq), dim3(256), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, ri, chunk, att,
+                           (uint4 *)pack, ncb);
+        return;
+    }
     const int threads = D.qw / 8 >= 512 ? 512 : (D.qw / 8 + 63) / 64 * 64;
     hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(threads), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, ri, chunk, att, (uint4 *)pack, ncb);
 }

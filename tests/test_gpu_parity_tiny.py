@@ -208,3 +208,30 @@ def test_small_bf16_model_on_the_matrix_core_path(tr, tro, B):
     cnt = g.counters()
     for i, slot in enumerate(slots):
         assert g.seq_len(slot) == lens[i] + 4 and cnt[slot][0] == 5
+
+
+@pytest.mark.parametrize("B,ctx", [(3, 1200), (1, 4500), (12, 2300)])
+def test_small_bf16_model_long_contexts(tr, tro, B, ctx):
+    """Long loaded caches with a bf16 KV cache: many attention chunks per row (merged by a separate kernel for a few rows,
+    by the consumer or the batched merge otherwise), chunks longer than 64 keys past 4096 positions, contexts of very
+    different lengths in one call, and decoding right up to the last position of the cache (max_seq not a multiple of 32)."""
+    s = synth.TINY.with_(dtype=synth.BF16, kv_dtype=synth.BF16)
+    w = synth.make_weights(s, SEED + 4, std=0.05, bias_std=0.05, gain_std=0.1)
+    max_seq = ctx + 3
+    g = tr.Model(s.asdict(), w, B, max_seq); o = tro.Model(s.asdict(), w, B, max_seq)
+    lens = [ctx] + [int(n) for n in synth.prompt_lengths(SEED, f"long.lens{B}", B - 1, 1, ctx)]
+    for b, n in enumerate(lens):
+        k, v = synth.kv_fill(SEED, f"long{B}.{b}", s, n)
+        o.load_kv(b, synth.bf16_bits_to_f32(k), synth.bf16_bits_to_f32(v))
+        g.load_kv(b, tr.to_device(k, synth.BF16), tr.to_device(v, synth.BF16))
+    slots = list(range(B))
+    toks = synth.prompt_tokens(SEED, f"long.tok{B}", B, s.vocab)
+    ex = 0
+    for step in range(3):
+        go = g.decode_step(slots, toks, want_logits=True).cpu(); oo = o.decode_step(slots, toks, want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"long B={B} step {step}")
+        toks = oo.token.copy()
+    assert ex <= 1
+    assert g.seq_len(0) == max_seq
+    with pytest.raises(tr.TokrouteError):
+        g.decode_step([0], [1])            # the cache of slot 0 is full
