@@ -329,6 +329,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     const int ctx = (ri.n ? ri.pos[r] : rows.pos[r]) + 1;
     const int j0 = c * chunk, j1 = min(ctx, j0 + chunk);
     const int slot = ri.n ? ri.slot[r] : rows.slot[r];
+    if (j0 >= ctx) return;   // no key of this row in the chunk: the merge never reads its partial
 
     bf16x8 qh[KSQ], ql[KSQ];
     {
