@@ -20,6 +20,8 @@ namespace tr {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int NWAVES = 4;  // wavefronts per workgroup (one per SIMD, 512 registers each); they split K
 constexpr int MAXKW = 14;  // k-steps a wavefront keeps resident (4 wavefronts x 14 x 16 = 896 columns of K per workgroup)
@@ -33,18 +35,20 @@ __device__ __forceinline__ bf16_t m_f32_to_bf16(float f)
 }
 __device__ __forceinline__ float m_bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
-// value = hi + lo with hi = bf16(value), lo = bf16(value - hi)
+// value = hi + lo with hi = bf16(value), lo = bf16(value - hi), both rounded to nearest even by the hardware's packed
+// conversion (two values per instruction)
 __device__ __forceinline__ void split_hi_lo(const float (&v)[8], uint4 &hi, uint4 &lo)
 {
-    uint32_t h[8], l[8];
+    uint32_t h[4], l[4];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const bf16_t hb = m_f32_to_bf16(v[e]);
-        h[e] = hb;
-        l[e] = m_f32_to_bf16(v[e] - m_bf16_to_f32(hb));
+    for (int p = 0; p < 4; ++p) {
+        const f32x2 x = {v[2 * p], v[2 * p + 1]};
+        h[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+        const f32x2 rest = {v[2 * p] - __uint_as_float(h[p] << 16), v[2 * p + 1] - __uint_as_float(h[p] & 0xffff0000u)};
+        l[p] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2));
     }
-    hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-    lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+    hi = make_uint4(h[0], h[1], h[2], h[3]);
+    lo = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
 // Packed activations of one group of up to 64 rows: [k-step][column block][lane] of 16 bytes, column blocks =
@@ -387,12 +391,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
                 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, ql[ks], sacc, 0, 0, 0);
             }
             // register rr of this lane is key t + 16*(rr/8) + 8*hf + rr%8 of head j
+            if (t + 32 > j1) {   // the last block of the row's context may be ragged
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr)
+                    if (t + 16 * (rr >> 3) + 8 * hf + (rr & 7) >= j1) sacc[rr] = -INFINITY;
+            }
             float bm = -INFINITY;
 #pragma unroll
-            for (int rr = 0; rr < 16; ++rr) {
-                if (t + 16 * (rr >> 3) + 8 * hf + (rr & 7) >= j1) sacc[rr] = -INFINITY;
-                bm = fmaxf(bm, sacc[rr]);
-            }
+            for (int rr = 0; rr < 16; ++rr) bm = fmaxf(bm, sacc[rr]);
             bm = fmaxf(bm, __shfl_xor(bm, 32, 64));      // key t is valid, so the pair maximum is finite
             const float mn = fmaxf(m, bm);
             const float corr = __expf(m - mn);           // 0 on the first block
