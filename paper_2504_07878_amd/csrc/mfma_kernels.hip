@@ -118,10 +118,20 @@ __global__ __launch_bounds__(128) void prep_kernel(PrepArgs p)
     if (live) {
         const float4 a = *reinterpret_cast<const float4 *>(xr + k0), b = *reinterpret_cast<const float4 *>(xr + k0 + 4);
         v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-        for (int s = 0; s < p.nsplit; ++s) {
-            const float *pr = p.part + ((size_t)s * p.part_M + p.row0 + m) * d + k0;
-            const float4 c = *reinterpret_cast<const float4 *>(pr), e2 = *reinterpret_cast<const float4 *>(pr + 4);
-            v[0] += c.x; v[1] += c.y; v[2] += c.z; v[3] += c.w; v[4] += e2.x; v[5] += e2.y; v[6] += e2.z; v[7] += e2.w;
+        // the partials are requested eight at a time (indices clamped) and added in their fixed order
+        for (int s0 = 0; s0 < p.nsplit; s0 += 8) {
+            float4 c[8], e2[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float *pr = p.part + ((size_t)min(s0 + u, p.nsplit - 1) * p.part_M + p.row0 + m) * d + k0;
+                c[u] = *reinterpret_cast<const float4 *>(pr); e2[u] = *reinterpret_cast<const float4 *>(pr + 4);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (s0 + u < p.nsplit) {
+                    v[0] += c[u].x; v[1] += c[u].y; v[2] += c[u].z; v[3] += c[u].w;
+                    v[4] += e2[u].x; v[5] += e2[u].y; v[6] += e2[u].z; v[7] += e2[u].w;
+                }
         }
         if (p.nsplit > 0) {
             *reinterpret_cast<float4 *>(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
@@ -496,6 +506,7 @@ struct EpiPartial {   // split-K partial sums: part[split][m][n]
     int N, M;
     __device__ void block(int, int) {}
     __device__ void begin() {}
+    __device__ void row(int) {}
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         const int n = t * 32 + i0;
@@ -517,15 +528,20 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
     KT *kc, *vc;
     int M, Hq, Hkv, dh, max_seq, qw, vts;
     float hold[2][8];
+    int rpos, rslot;          // position and slot of this thread's batch row, fetched ahead of the weight stream
     __device__ void block(int, int) {}
     __device__ void begin() {}
+    __device__ void row(int m) { rpos = pos[min(m, M - 1)]; rslot = slot[min(m, M - 1)]; }
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         const int tph = dh >> 5, halfp = tph >> 1;          // tiles per head, tiles per rotary half
         const int hh = t / tph, sub = t % tph;
         float y[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) y[e] = v[e] + bias[t * 32 + i0 + e];
+        {
+            const float4 b0 = *reinterpret_cast<const float4 *>(bias + t * 32 + i0), b1 = *reinterpret_cast<const float4 *>(bias + t * 32 + i0 + 4);
+            y[0] = v[0] + b0.x; y[1] = v[1] + b0.y; y[2] = v[2] + b0.z; y[3] = v[3] + b0.w;
+            y[4] = v[4] + b1.x; y[5] = v[5] + b1.y; y[6] = v[6] + b1.z; y[7] = v[7] + b1.w;
+        }
         if (sub < halfp) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) hold[sub & 1][e] = y[e];
@@ -533,15 +549,17 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
         }
         if (m >= M) return;
         const int e0 = (sub - halfp) * 32 + i0;              // index inside the first half of the head
-        const int half = dh >> 1, p = pos[m];
+        const int half = dh >> 1, p = rpos;
         float lo[8], hi[8];
         if (hh < Hq + Hkv) {
+            const float4 *rp = reinterpret_cast<const float4 *>(rope + (size_t)p * half + e0);   // 8 (cos, sin) pairs, 64 bytes, aligned
+            const float4 c4[4] = {rp[0], rp[1], rp[2], rp[3]};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float2 cs = rope[(size_t)p * half + e0 + e];
+                const float cs_x = (e & 1) ? c4[e >> 1].z : c4[e >> 1].x, cs_y = (e & 1) ? c4[e >> 1].w : c4[e >> 1].y;
                 const float a = hold[(sub - halfp) & 1][e], b = y[e];
-                lo[e] = a * cs.x - b * cs.y;
-                hi[e] = b * cs.x + a * cs.y;
+                lo[e] = a * cs_x - b * cs_y;
+                hi[e] = b * cs_x + a * cs_y;
             }
         } else {
 #pragma unroll
@@ -556,18 +574,22 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
         } else {
             const int head = hh < Hq + Hkv ? hh - Hq : hh - Hq - Hkv;
             if (hh < Hq + Hkv || vts == 0) {
-                KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)slot[m] * Hkv + head) * max_seq + p) * dh + e0;
+                KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)rslot * Hkv + head) * max_seq + p) * dh + e0;
                 store8(dst, lo);
                 store8(dst + half, hi);
             } else {   // transposed V: one position of 16 dim rows
-                KT *dst = vc + (((size_t)slot[m] * Hkv + head) * dh + e0) * vts + p;
+                KT *dst = vc + (((size_t)rslot * Hkv + head) * dh + e0) * vts + p;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { store1(dst + (size_t)e * vts, lo[e]); store1(dst + (size_t)(half + e) * vts, hi[e]); }
             }
         }
     }
     __device__ static void store1(float *dst, float v) { *dst = v; }
-    __device__ static void store1(bf16_t *dst, float v) { *dst = m_f32_to_bf16(v); }
+    __device__ static void store1(bf16_t *dst, float v)
+    {
+        const f32x2 x = {v, 0.f};
+        *dst = (bf16_t)__builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+    }
     __device__ static void store8(float *dst, const float (&v)[8])
     {
         *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -575,10 +597,13 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
     }
     __device__ static void store8(bf16_t *dst, const float (&v)[8])
     {
-        uint32_t h[8];
+        uint32_t h[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = m_f32_to_bf16(v[e]);
-        *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        for (int e = 0; e < 4; ++e) {
+            const f32x2 x = {v[2 * e], v[2 * e + 1]};
+            h[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
+        }
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
     }
     __device__ void end(float *) {}
 };
@@ -589,6 +614,7 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
     float hold[8];
     __device__ void block(int, int) {}
     __device__ void begin() {}
+    __device__ void row(int) {}
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         if ((t & 1) == 0) {
@@ -599,7 +625,7 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
         if (m >= M) return;
         float h[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = hold[e] / (1.0f + expf(-hold[e])) * v[e];
+        for (int e = 0; e < 8; ++e) h[e] = hold[e] * __frcp_rn(1.0f + __expf(-hold[e])) * v[e];   // hardware exp2 and reciprocal (1 ulp each)
         const int f0 = (t >> 1) * 32 + i0;
         if (f0 < F) store_packed(hpack + (size_t)(m >> 6) * (F / 16) * ncb * 64, ncb, m & 63, f0 >> 3, h);
     }
@@ -616,6 +642,7 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     int idx, bx, grp, nwg;   // nwg: workgroups that own tiles (the grid may be padded)
     __device__ void block(int b, int g) { bx = b; grp = g; }
     __device__ void begin() { mx = -INFINITY; sum = 0.f; idx = 0x7fffffff; }
+    __device__ void row(int) {}
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         if (m >= M) return;
@@ -625,20 +652,32 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
             for (int e = 0; e < 8; ++e)
                 if (n0 + e < V) logits[(size_t)m * V + n0 + e] = v[e];
         }
-        float lm = -INFINITY;
+        float lm = -INFINITY, add = 0.f;
         int li = 0;
+        if (n0 + 8 <= V) {   // all but the ragged end of the vocabulary
 #pragma unroll
-        for (int e = 7; e >= 0; --e)
-            if (n0 + e < V && v[e] >= lm) { lm = v[e]; li = e; }   // descending scan: the lowest index wins ties
-        if (lm > mx) {                                              // strict: earlier tiles win ties
-            sum *= __expf(mx - lm);
-            mx = lm;
-            idx = n0 + li;
+            for (int e = 7; e >= 0; --e)
+                if (v[e] >= lm) { lm = v[e]; li = e; }              // descending scan: the lowest index wins ties
+            if (lm > mx) {                                          // strict: earlier tiles win ties
+                sum *= __expf(mx - lm);
+                mx = lm;
+                idx = n0 + li;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) add += __expf(v[e] - mx);
+        } else {
+#pragma unroll
+            for (int e = 7; e >= 0; --e)
+                if (n0 + e < V && v[e] >= lm) { lm = v[e]; li = e; }
+            if (lm > mx) {
+                sum *= __expf(mx - lm);
+                mx = lm;
+                idx = n0 + li;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (n0 + e < V) add += __expf(v[e] - mx);
         }
-        float add = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (n0 + e < V) add += __expf(v[e] - mx);
         sum += add;
     }
     // the four threads that share a batch row (one per 8-row band) merge through LDS
@@ -769,6 +808,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
 
     epi.begin();
+    epi.row(row0 + j);
     int t = t0;
     if (t1 - t0 >= 4) {
         // long tile ranges: nothing conditional between the first load and the end of the steady state, so the
