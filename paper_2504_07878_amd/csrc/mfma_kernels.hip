@@ -331,11 +331,115 @@ __device__ __forceinline__ void to_hi_lo(const float (&v)[8], bf16x8 &hi, bf16x8
     lo = __builtin_bit_cast(bf16x8, l);
 }
 
+// The walk of one wavefront over the blocks of 32 keys t_begin, t_begin + t_step, ... < j1 of one (row, kv head):
+// running maximum m and sum l of its head column (both lanes of a head agree on m; l is per lane) and the
+// unnormalised output o, accumulator register rr of block db = dim db*32 + 8*(rr/4) + 4*hf + rr%4 of head j.
+template <int DH>
+struct AttnWave {
+    static constexpr int KSQ = DH / 16, DB = DH / 32;
+    float m, l;
+    f32x16 o[DB];
+
+    __device__ __forceinline__ void run(const Dims &D, const float *qrow /* q of this row */, const bf16_t *Kb, const bf16_t *Vb, int g, int t_begin,
+                                        int t_step, int j1)
+    {
+        const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
+        bf16x8 qh[KSQ], ql[KSQ];
+        {
+            const float scale = 1.0f / sqrtf((float)DH);
+            const float *qp = qrow + (size_t)(g * G + (j < G ? j : 0)) * DH + hf * 8;
+#pragma unroll
+            for (int ks = 0; ks < KSQ; ++ks) {
+                float v[8];
+                const float4 a = *reinterpret_cast<const float4 *>(qp + ks * 16), b = *reinterpret_cast<const float4 *>(qp + ks * 16 + 4);
+                v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = j < G ? v[e] * scale : 0.f;
+                to_hi_lo(v, qh[ks], ql[ks]);
+            }
+        }
+        const int krow = (j & 0x13) | ((j & 4) << 1) | ((j & 8) >> 1);   // row j of the A operand holds key krow (bits 2,3 swapped)
+        m = -INFINITY; l = 0.f;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int rr = 0; rr < 16; ++rr) o[db][rr] = 0.f;
+
+        // NB blocks of 32 keys are requested together (64-wide heads: 64 keys in flight at once)
+        constexpr int NB = DH == 64 ? 2 : 1;
+        for (int t0 = t_begin; t0 < j1; t0 += NB * t_step) {
+            uint4 ka[NB][KSQ], va[NB][2][DB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int t = t0 + nb * t_step;   // may start past j1 in the last trip: rows are clamped, V^T rows are padded to 32
+                const bf16_t *kp = Kb + (size_t)min(t + krow, j1 - 1) * DH + hf * 8;
+#pragma unroll
+                for (int ks = 0; ks < KSQ; ++ks) ka[nb][ks] = *reinterpret_cast<const uint4 *>(kp + ks * 16);
+                const int tv = min(t, D.vts - 32);
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+                        va[nb][kk][db] = *reinterpret_cast<const uint4 *>(Vb + (size_t)(db * 32 + j) * D.vts + tv + 16 * kk + 8 * hf);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int t = t0 + nb * t_step;
+                if (t >= j1) break;   // uniform over the wavefront
+                f32x16 sacc;
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) sacc[rr] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KSQ; ++ks) {
+                    const bf16x8 kv = __builtin_bit_cast(bf16x8, ka[nb][ks]);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qh[ks], sacc, 0, 0, 0);
+                    sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, ql[ks], sacc, 0, 0, 0);
+                }
+                // register rr of this lane is key t + 16*(rr/8) + 8*hf + rr%8 of head j
+                if (t + 32 > j1) {   // the last block of the row's context may be ragged
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr)
+                        if (t + 16 * (rr >> 3) + 8 * hf + (rr & 7) >= j1) sacc[rr] = -INFINITY;
+                }
+                float bm = -INFINITY;
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) bm = fmaxf(bm, sacc[rr]);
+                bm = fmaxf(bm, __shfl_xor(bm, 32, 64));      // key t is valid, so the pair maximum is finite
+                const float mn = fmaxf(m, bm);
+                const float corr = __expf(m - mn);           // 0 on the first block
+                float p[16], ps = 0.f;
+#pragma unroll
+                for (int rr = 0; rr < 16; ++rr) { p[rr] = __expf(sacc[rr] - mn); ps += p[rr]; }
+                l = l * corr + ps;
+                m = mn;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int rr = 0; rr < 16; ++rr) o[db][rr] *= corr;
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const float pk[8] = {p[8 * kk], p[8 * kk + 1], p[8 * kk + 2], p[8 * kk + 3], p[8 * kk + 4], p[8 * kk + 5], p[8 * kk + 6], p[8 * kk + 7]};
+                    bf16x8 ph, pl;
+                    to_hi_lo(pk, ph, pl);
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {
+                        const bf16x8 vv = __builtin_bit_cast(bf16x8, va[nb][kk][db]);
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, ph, o[db], 0, 0, 0);
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pl, o[db], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+};
+
+// One wavefront per (query row, chunk of the context), kv head along gridDim.y: partials for the merge, or the final
+// rows when there is a single chunk.
 template <int DH>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, RowsInline ri, int chunk,
                                                         int nchunks, float *part, float *att)
 {
-    constexpr int KSQ = DH / 16, DB = DH / 32, PS = DH + 4;
+    constexpr int DB = DH / 32, PS = DH + 4;
     const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (item >= rows.n * nchunks) return;
     const int r = __builtin_amdgcn_readfirstlane(item / nchunks), c = item % nchunks, g = blockIdx.y;   // one row per wavefront
@@ -345,100 +449,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     const int slot = ri.n ? ri.slot[r] : rows.slot[r];
     if (j0 >= ctx) return;   // no key of this row in the chunk: the merge never reads its partial
 
-    bf16x8 qh[KSQ], ql[KSQ];
-    {
-        const float scale = 1.0f / sqrtf((float)DH);
-        const float *qp = q + (size_t)r * D.qw + (size_t)(g * G + (j < G ? j : 0)) * DH + hf * 8;
-#pragma unroll
-        for (int ks = 0; ks < KSQ; ++ks) {
-            float v[8];
-            const float4 a = *reinterpret_cast<const float4 *>(qp + ks * 16), b = *reinterpret_cast<const float4 *>(qp + ks * 16 + 4);
-            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = j < G ? v[e] * scale : 0.f;
-            to_hi_lo(v, qh[ks], ql[ks]);
-        }
-    }
-    const bf16_t *Kb = kc + ((size_t)slot * D.Hkv + g) * (size_t)D.max_seq * DH;
-    const bf16_t *Vb = vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * D.vts;
-    const int krow = (j & 0x13) | ((j & 4) << 1) | ((j & 8) >> 1);   // row j of the A operand holds key krow (bits 2,3 swapped)
-
-    float m = -INFINITY, l = 0.f;
-    f32x16 o[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int rr = 0; rr < 16; ++rr) o[db][rr] = 0.f;
-
-    // NB blocks of 32 keys are requested together (all loads of 64 keys in flight at once for 64-wide heads)
-    constexpr int NB = DH == 64 ? 2 : 1;
-    for (int t0 = j0; t0 < j1; t0 += 32 * NB) {
-        uint4 ka[NB][KSQ], va[NB][2][DB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int t = t0 + 32 * nb;   // may start past j1 in the last trip: rows are clamped, V^T rows are padded to 32
-            const bf16_t *kp = Kb + (size_t)min(t + krow, j1 - 1) * DH + hf * 8;
-#pragma unroll
-            for (int ks = 0; ks < KSQ; ++ks) ka[nb][ks] = *reinterpret_cast<const uint4 *>(kp + ks * 16);
-            const int tv = min(t, D.vts - 32);
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-                    va[nb][kk][db] = *reinterpret_cast<const uint4 *>(Vb + (size_t)(db * 32 + j) * D.vts + tv + 16 * kk + 8 * hf);
-        }
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int t = t0 + 32 * nb;
-            if (t >= j1) break;   // uniform over the wavefront
-            f32x16 sacc;
-#pragma unroll
-            for (int rr = 0; rr < 16; ++rr) sacc[rr] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KSQ; ++ks) {
-                const bf16x8 kv = __builtin_bit_cast(bf16x8, ka[nb][ks]);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, qh[ks], sacc, 0, 0, 0);
-                sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, ql[ks], sacc, 0, 0, 0);
-            }
-            // register rr of this lane is key t + 16*(rr/8) + 8*hf + rr%8 of head j
-            if (t + 32 > j1) {   // the last block of the row's context may be ragged
-#pragma unroll
-                for (int rr = 0; rr < 16; ++rr)
-                    if (t + 16 * (rr >> 3) + 8 * hf + (rr & 7) >= j1) sacc[rr] = -INFINITY;
-            }
-            float bm = -INFINITY;
-#pragma unroll
-            for (int rr = 0; rr < 16; ++rr) bm = fmaxf(bm, sacc[rr]);
-            bm = fmaxf(bm, __shfl_xor(bm, 32, 64));      // key t is valid, so the pair maximum is finite
-            const float mn = fmaxf(m, bm);
-            const float corr = __expf(m - mn);           // 0 on the first block
-            float p[16], ps = 0.f;
-#pragma unroll
-            for (int rr = 0; rr < 16; ++rr) { p[rr] = __expf(sacc[rr] - mn); ps += p[rr]; }
-            l = l * corr + ps;
-            m = mn;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int rr = 0; rr < 16; ++rr) o[db][rr] *= corr;
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const float pk[8] = {p[8 * kk], p[8 * kk + 1], p[8 * kk + 2], p[8 * kk + 3], p[8 * kk + 4], p[8 * kk + 5], p[8 * kk + 6], p[8 * kk + 7]};
-                bf16x8 ph, pl;
-                to_hi_lo(pk, ph, pl);
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const bf16x8 vv = __builtin_bit_cast(bf16x8, va[nb][kk][db]);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, ph, o[db], 0, 0, 0);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vv, pl, o[db], 0, 0, 0);
-                }
-            }
-        }
-    }
-    const float lt = l + __shfl_xor(l, 32, 64);      // both lanes of a head used the same running maximum
+    AttnWave<DH> w;
+    w.run(D, q + (size_t)r * D.qw, kc + ((size_t)slot * D.Hkv + g) * (size_t)D.max_seq * DH, vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * D.vts, g, j0, 32,
+          j1);
+    const float lt = w.l + __shfl_xor(w.l, 32, 64);      // both lanes of a head used the same running maximum
     if (j >= G) return;
     const int head = g * G + j;
-    // accumulator register rr of block db is dim db*32 + 8*(rr/4) + 4*hf + rr%4
     if (nchunks == 1) {
         const float inv = 1.0f / lt;
         float *dst = att + (size_t)r * D.qw + (size_t)head * DH;
@@ -447,15 +463,77 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)
                 *reinterpret_cast<float4 *>(dst + db * 32 + qd * 8 + hf * 4) =
-                    make_float4(o[db][4 * qd] * inv, o[db][4 * qd + 1] * inv, o[db][4 * qd + 2] * inv, o[db][4 * qd + 3] * inv);
+                    make_float4(w.o[db][4 * qd] * inv, w.o[db][4 * qd + 1] * inv, w.o[db][4 * qd + 2] * inv, w.o[db][4 * qd + 3] * inv);
     } else {
         float *pp = part + (((size_t)r * D.Hq + head) * nchunks + c) * PS;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)
-                *reinterpret_cast<float4 *>(pp + db * 32 + qd * 8 + hf * 4) = make_float4(o[db][4 * qd], o[db][4 * qd + 1], o[db][4 * qd + 2], o[db][4 * qd + 3]);
-        if (hf == 0) { pp[DH] = m; pp[DH + 1] = lt; }
+                *reinterpret_cast<float4 *>(pp + db * 32 + qd * 8 + hf * 4) = make_float4(w.o[db][4 * qd], w.o[db][4 * qd + 1], w.o[db][4 * qd + 2], w.o[db][4 * qd + 3]);
+        if (hf == 0) { pp[DH] = w.m; pp[DH + 1] = lt; }
+    }
+}
+
+// One workgroup of 8 wavefronts per (query row, kv head): wavefront w walks the key blocks w, w + 8, ..., the eight
+// partial results are combined through LDS in a fixed order and the finished row is written as fp32 and/or as packed
+// hi/lo activations. For batches with enough (row, kv head) pairs to fill the chip this replaces the chunked
+// kernel plus the separate merge.
+constexpr int ATT_ROW_WAVES = 8;
+
+template <int DH>
+__global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, RowsInline ri,
+                                                                      float *att, uint4 *pack, int ncb)
+{
+    constexpr int DB = DH / 32, NW = ATT_ROW_WAVES, GMAX = 8;
+    __shared__ float s_m[NW][GMAX], s_l[NW][GMAX];
+    __shared__ __attribute__((aligned(16))) float s_o[NW][GMAX][DH];
+    const int r = blockIdx.x, g = blockIdx.y, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
+    const int ctx = (ri.n ? ri.pos[r] : rows.pos[r]) + 1;
+    const int slot = ri.n ? ri.slot[r] : rows.slot[r];
+
+    if (wv * 32 < ctx) {
+        AttnWave<DH> w;
+        w.run(D, q + (size_t)r * D.qw, kc + ((size_t)slot * D.Hkv + g) * (size_t)D.max_seq * DH, vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * D.vts, g,
+              wv * 32, NW * 32, ctx);
+        const float lt = w.l + __shfl_xor(w.l, 32, 64);
+        if (j < G) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+                    *reinterpret_cast<float4 *>(&s_o[wv][j][db * 32 + qd * 8 + hf * 4]) =
+                        make_float4(w.o[db][4 * qd], w.o[db][4 * qd + 1], w.o[db][4 * qd + 2], w.o[db][4 * qd + 3]);
+            if (hf == 0) { s_m[wv][j] = w.m; s_l[wv][j] = lt; }
+        }
+    }
+    __syncthreads();
+    const int live = min(NW, (ctx + 31) / 32);       // wavefronts that had keys
+    const int task = threadIdx.x;                    // (head of the group, 8 dims)
+    if (task < G * (DH / 8)) {
+        const int h = task / (DH / 8), d0 = (task % (DH / 8)) * 8;
+        float M = -INFINITY;
+        for (int w2 = 0; w2 < live; ++w2) M = fmaxf(M, s_m[w2][h]);
+        float L = 0.f, o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+        for (int w2 = 0; w2 < live; ++w2) {
+            const float c = __expf(s_m[w2][h] - M);
+            L = fmaf(s_l[w2][h], c, L);
+            const float4 a = *reinterpret_cast<const float4 *>(&s_o[w2][h][d0]), b = *reinterpret_cast<const float4 *>(&s_o[w2][h][d0 + 4]);
+            o[0] = fmaf(a.x, c, o[0]); o[1] = fmaf(a.y, c, o[1]); o[2] = fmaf(a.z, c, o[2]); o[3] = fmaf(a.w, c, o[3]);
+            o[4] = fmaf(b.x, c, o[4]); o[5] = fmaf(b.y, c, o[5]); o[6] = fmaf(b.z, c, o[6]); o[7] = fmaf(b.w, c, o[7]);
+        }
+        const float inv = 1.0f / L;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= inv;
+        const int col = (g * G + h) * DH + d0;
+        if (att) {
+            *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col) = make_float4(o[0], o[1], o[2], o[3]);
+            *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col + 4) = make_float4(o[4], o[5], o[6], o[7]);
+        }
+        if (pack) store_packed(pack + (size_t)(r >> 6) * (D.qw / 16) * ncb * 64, ncb, r & 63, col >> 3, o);
     }
 }
 
@@ -463,6 +541,16 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
                            size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
+    if (rows.n * D.Hkv >= 64 && D.G <= 8) {   // enough (row, kv head) pairs to fill the chip with one workgroup each
+        const dim3 grid(rows.n, D.Hkv);
+        if (D.dh == 64)
+            hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri,
+                               pack ? nullptr : att, (uint4 *)pack, ncb);
+        else
+            hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri,
+                               pack ? nullptr : att, (uint4 *)pack, ncb);
+        return;
+    }
     // decode: up to 32 chunks of the context per row, merged afterwards; prompts: one wavefront walks the whole context of a row
     size_t room = part_floats / ((size_t)rows.n * D.Hq * (D.dh + 4));   // chunks per row that fit the partials buffer
     if (room > 64) room = 64;

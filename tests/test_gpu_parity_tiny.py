@@ -210,7 +210,7 @@ def test_small_bf16_model_on_the_matrix_core_path(tr, tro, B):
         assert g.seq_len(slot) == lens[i] + 4 and cnt[slot][0] == 5
 
 
-@pytest.mark.parametrize("B,ctx", [(3, 1200), (1, 4500), (12, 2300)])
+@pytest.mark.parametrize("B,ctx", [(3, 1200), (1, 4500), (12, 2300), (40, 900)])
 def test_small_bf16_model_long_contexts(tr, tro, B, ctx):
     """Long loaded caches with a bf16 KV cache: many attention chunks per row (merged by a separate kernel for a few rows,
     by the consumer or the batched merge otherwise), chunks longer than 64 keys past 4096 positions, contexts of very
