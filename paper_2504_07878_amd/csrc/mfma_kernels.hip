@@ -590,6 +590,7 @@ struct GemmArgs {
 // Epilogues receive, per thread, 8 consecutive output features (rows i0..i0+7 of tile t) of one batch row.
 
 struct EpiPartial {   // split-K partial sums: part[split][m][n]
+    static constexpr bool half_only = false;
     float *part;
     int N, M;
     __device__ void block(int, int) {}
@@ -609,13 +610,15 @@ struct EpiPartial {   // split-K partial sums: part[split][m][n]
 
 template <typename KT>
 struct EpiQkv {       // bias, rotary embedding, q out, cache append
+    static constexpr bool half_only = true;   // launched with GemmArgs::half = 1: 32-row workgroups only
     const float *bias;        // concatenated [qw + 2 kvw]
     const float2 *rope;
     const int *slot, *pos;
     float *q;
     KT *kc, *vc;
     int M, Hq, Hkv, dh, max_seq, qw, vts;
-    float hold[2][8];
+    float hold0[8], hold1[8];   // first rotary half of the head, kept until its partner tile arrives (two arrays with
+                                // constant indices: a runtime index would move the whole functor out of registers)
     int rpos, rslot;          // position and slot of this thread's batch row, fetched ahead of the weight stream
     __device__ void block(int, int) {}
     __device__ void begin() {}
@@ -631,27 +634,34 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
             y[4] = v[4] + b1.x; y[5] = v[5] + b1.y; y[6] = v[6] + b1.z; y[7] = v[7] + b1.w;
         }
         if (sub < halfp) {
+            if (sub & 1) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) hold[sub & 1][e] = y[e];
+                for (int e = 0; e < 8; ++e) hold1[e] = y[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) hold0[e] = y[e];
+            }
             return;
         }
         if (m >= M) return;
         const int e0 = (sub - halfp) * 32 + i0;              // index inside the first half of the head
         const int half = dh >> 1, p = rpos;
-        float lo[8], hi[8];
+        float lo[8], hi[8], first[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) first[e] = ((sub - halfp) & 1) ? hold1[e] : hold0[e];
         if (hh < Hq + Hkv) {
             const float4 *rp = reinterpret_cast<const float4 *>(rope + (size_t)p * half + e0);   // 8 (cos, sin) pairs, 64 bytes, aligned
             const float4 c4[4] = {rp[0], rp[1], rp[2], rp[3]};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float cs_x = (e & 1) ? c4[e >> 1].z : c4[e >> 1].x, cs_y = (e & 1) ? c4[e >> 1].w : c4[e >> 1].y;
-                const float a = hold[(sub - halfp) & 1][e], b = y[e];
+                const float a = first[e], b = y[e];
                 lo[e] = a * cs_x - b * cs_y;
                 hi[e] = b * cs_x + a * cs_y;
             }
         } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { lo[e] = hold[(sub - halfp) & 1][e]; hi[e] = y[e]; }
+            for (int e = 0; e < 8; ++e) { lo[e] = first[e]; hi[e] = y[e]; }
         }
         if (hh < Hq) {
             float *dst = q + (size_t)m * qw + hh * dh + e0;
@@ -697,6 +707,7 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
 };
 
 struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written as packed activations of the down projection
+    static constexpr bool half_only = false;
     uint4 *hpack;     // [group][F/16][NCB][64]
     int M, F, ncb;
     float hold[8];
@@ -723,6 +734,7 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
 // DUMP = false keeps every vector-memory store out of the tile loop, so that the wait counters of the weight stream stay exact
 template <bool DUMP>
 struct EpiLmHead {    // running softmax statistics per batch row; logits optionally dumped
+    static constexpr bool half_only = false;
     float4 *part;     // [gridDim.x][M]
     float *logits;
     int M, V;
@@ -953,7 +965,7 @@ static void launch_gemm(hipStream_t s, const GemmArgs &a, int nsplit, const Epi 
     GemmArgs b = a;
     b.half = 0;
     if (a.M <= 32) launch_gemm_kw<2>(s, b, grid, epi);
-    else launch_gemm_kw<4>(s, b, grid, epi);
+    else if constexpr (!Epi::half_only) launch_gemm_kw<4>(s, b, grid, epi);   // half-only epilogues never get here: no 64-row instance of them
 }
 
 int mfma_ncb(int M) { return M <= 32 ? 2 : 4; }
