@@ -142,93 +142,104 @@ __global__ __launch_bounds__(256) void lmhead_kernel(const WT *head, int V, int 
 
 // ------------------------------------------------------------------ merge the slices, run the router, set the flag
 
+// One workgroup of 16 wavefronts per batch row. Reductions are wavefront shuffles plus one fixed-order pass over the
+// 16 wavefront results, so the outcome does not depend on timing.
+constexpr int TF_WAVES = 16;
+
 template <typename WT>
-__global__ __launch_bounds__(256) void tail_final_kernel(int d, int rh, TailArgs t)
+__global__ __launch_bounds__(64 * TF_WAVES) void tail_final_kernel(int d, int rh, TailArgs t)
 {
-    __shared__ float s_m[256];
-    __shared__ int s_i[256];
-    __shared__ float s_s[256];
+    __shared__ float s_wm[TF_WAVES];
+    __shared__ int s_wi[TF_WAVES];
+    __shared__ float s_ws[2][TF_WAVES];
     __shared__ float s_h[1024];
-    __shared__ float s_u[4096];
-    const int i = blockIdx.x, tid = threadIdx.x, n = t.n;
+    __shared__ __attribute__((aligned(16))) float s_u[4096];
+    const int i = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = t.n;
     const float4 *part = reinterpret_cast<const float4 *>(t.part);
 
     // 1. global maximum and the lowest index that attains it
     float M = -INFINITY; int I = 0x7fffffff;
-    for (int s = tid; s < t.nslices; s += 256) {
+    for (int s = tid; s < t.nslices; s += 64 * TF_WAVES) {
         const float4 p = part[(size_t)s * n + i];
         const int pi = __float_as_int(p.y);
         if (p.x > M || (p.x == M && pi < I)) { M = p.x; I = pi; }
     }
-    s_m[tid] = M; s_i[tid] = I;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) {
-            const float m2 = s_m[tid + o]; const int i2 = s_i[tid + o];
-            if (m2 > s_m[tid] || (m2 == s_m[tid] && i2 < s_i[tid])) { s_m[tid] = m2; s_i[tid] = i2; }
-        }
-        __syncthreads();
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float m2 = __shfl_xor(M, o, 64); const int i2 = __shfl_xor(I, o, 64);
+        if (m2 > M || (m2 == M && i2 < I)) { M = m2; I = i2; }
     }
-    M = s_m[0]; I = s_i[0];
-    // 2. sum of exponentials relative to the global maximum (fixed summation tree)
+    if (lane == 0) { s_wm[wave] = M; s_wi[wave] = I; }
+    __syncthreads();
+    M = -INFINITY; I = 0x7fffffff;
+    for (int w = 0; w < TF_WAVES; ++w) {
+        const float m2 = s_wm[w]; const int i2 = s_wi[w];
+        if (m2 > M || (m2 == M && i2 < I)) { M = m2; I = i2; }
+    }
+    // 2. sum of exponentials relative to the global maximum
     float S = 0.f;
-    for (int s = tid; s < t.nslices; s += 256) {
+    for (int s = tid; s < t.nslices; s += 64 * TF_WAVES) {
         const float4 p = part[(size_t)s * n + i];
         if (p.x > -INFINITY) S += p.z * expf(p.x - M);
     }
-    s_s[tid] = S;
-    __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
-        if (tid < o) s_s[tid] += s_s[tid + o];
-        __syncthreads();
-    }
-    const float conf = 1.0f / s_s[0];
+    S = t_wave_sum(S);
+    if (lane == 0) s_ws[0][wave] = S;
 
-    // 3. router: score = sigmoid(w2 . relu(W1 u + b1) + b2) on the tapped hidden state
+    // 3. router: score = sigmoid(w2 . relu(W1 u + b1) + b2) on the tapped hidden state. A wavefront takes four hidden
+    //    units at a time; its lanes split the columns, so every weight row is read as consecutive 16-byte pieces.
     float score = 1.0f;
     int flag = 0;
     if (rh > 0) {
         const float *u = t.hidden_tap == 0 ? t.hn + (size_t)i * d : t.x + (size_t)(t.gather ? t.gather[i] : i) * d;
         const WT *w1 = (const WT *)t.r_w1, *b1 = (const WT *)t.r_b1, *w2 = (const WT *)t.r_w2, *b2 = (const WT *)t.r_b2;
-        // one hidden unit per thread; the tapped row is staged in LDS and read as a broadcast
-        for (int k = tid; k < d; k += 256) s_u[k] = u[k];
+        for (int k = tid; k < d; k += 64 * TF_WAVES) s_u[k] = u[k];
         __syncthreads();
-        for (int j = tid; j < rh; j += 256) {
-            const WT *wr = w1 + (size_t)j * d;
-            float acc0 = 0.f, acc1 = 0.f;
-#pragma unroll 4
-            for (int k = 0; k < d; k += 8) {
-                float w[8];
-                t_load8(wr + k, w);
+        for (int j0 = wave; j0 < rh; j0 += 4 * TF_WAVES) {
+            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int k = lane * 8; k < d; k += 512) {
+                float w[4][8];
 #pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    acc0 = fmaf(w[e], s_u[k + e], acc0);
-                    acc1 = fmaf(w[e + 1], s_u[k + e + 1], acc1);
+                for (int q = 0; q < 4; ++q) t_load8(w1 + (size_t)min(j0 + q * TF_WAVES, rh - 1) * d + k, w[q]);
+                const float4 x0 = *reinterpret_cast<const float4 *>(s_u + k), x1 = *reinterpret_cast<const float4 *>(s_u + k + 4);
+                const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[q] = fmaf(w[q][e], xv[e], acc[q]);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float h = t_wave_sum(acc[q]);
+                const int j = j0 + q * TF_WAVES;
+                if (lane == 0 && j < rh) {
+                    const float hb = h + (b1 ? t_widen(b1, j) : 0.f);
+                    s_h[j] = hb > 0.f ? hb : 0.f;
                 }
             }
-            const float h = acc0 + acc1 + (b1 ? t_widen(b1, j) : 0.f);
-            s_h[j] = h > 0.f ? h : 0.f;
         }
         __syncthreads();
         float a = 0.f;
-        for (int j = tid; j < rh; j += 256) a = fmaf(t_widen(w2, j), s_h[j], a);
-        s_s[tid] = a;
-        __syncthreads();
-        for (int o = 128; o > 0; o >>= 1) {
-            if (tid < o) s_s[tid] += s_s[tid + o];
-            __syncthreads();
-        }
-        const float pre = s_s[0] + (b2 ? t_widen(b2, 0) : 0.f);
+        for (int j = tid; j < rh; j += 64 * TF_WAVES) a = fmaf(t_widen(w2, j), s_h[j], a);
+        a = t_wave_sum(a);
+        if (lane == 0) s_ws[1][wave] = a;
+    }
+    __syncthreads();
+    if (tid != 0) return;
+    float Ssum = 0.f;
+    for (int w = 0; w < TF_WAVES; ++w) Ssum += s_ws[0][w];
+    const float conf = 1.0f / Ssum;
+    if (rh > 0) {
+        float pre = 0.f;
+        for (int w = 0; w < TF_WAVES; ++w) pre += s_ws[1][w];
+        pre += t.r_b2 ? t_widen((const WT *)t.r_b2, 0) : 0.f;
         score = 1.0f / (1.0f + expf(-pre));
         if (t.mode == 0) flag = t.route_dir == 0 ? (score < t.threshold) : (score > t.threshold);
     }
-    if (tid == 0) {
-        t.token[i] = I; t.conf[i] = conf; t.score[i] = score; t.flag[i] = flag;
-        if (t.counters && t.counter_mode) {
-            long long *c = t.counters + 2 * (size_t)t.slot[i];
-            if (t.counter_mode == 1) { c[0] += 1; c[1] += flag; }
-            else { c[0] = 1; c[1] = flag; }
-        }
+    t.token[i] = I; t.conf[i] = conf; t.score[i] = score; t.flag[i] = flag;
+    if (t.counters && t.counter_mode) {
+        long long *c = t.counters + 2 * (size_t)t.slot[i];
+        if (t.counter_mode == 1) { c[0] += 1; c[1] += flag; }
+        else { c[0] = 1; c[1] = flag; }
     }
 }
 
@@ -251,8 +262,8 @@ void launch_lmhead_gemv(hipStream_t s, int wdt, const Dims &D, const TailArgs &t
 
 void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
 {
-    if (wdt == DT_F32) hipLaunchKernelGGL(tail_final_kernel<float>, dim3(t.n), dim3(256), 0, s, D.d, D.rh, t);
-    else hipLaunchKernelGGL(tail_final_kernel<bf16_t>, dim3(t.n), dim3(256), 0, s, D.d, D.rh, t);
+    if (wdt == DT_F32) hipLaunchKernelGGL(tail_final_kernel<float>, dim3(t.n), dim3(64 * TF_WAVES), 0, s, D.d, D.rh, t);
+    else hipLaunchKernelGGL(tail_final_kernel<bf16_t>, dim3(t.n), dim3(64 * TF_WAVES), 0, s, D.d, D.rh, t);
 }
 
 // the all-streaming tail: norm, LM head slices, merge + router
