@@ -727,11 +727,11 @@ static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, 
 
 // att (fp32 [R][qw]) and/or pack (packed hi/lo activations of the output projection) receive the result.
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, const RowsInline &ri,
-                      int max_ctx, float *part, size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
+                      int max_ctx, float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
     if (kdt == DT_BF16) {   // bf16 cache: V is stored transposed and attention runs on the matrix cores
-        launch_attention_mfma(s, D, q, kc, vc, rows, ri, max_ctx, part, part_floats, att, pack, ncb, defer);
+        launch_attention_mfma(s, D, q, kc, vc, rows, ri, max_ctx, part, part_floats, cnt, att, pack, ncb, defer);
         return;
     }
     bool done = false;

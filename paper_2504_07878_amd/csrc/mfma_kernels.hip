@@ -475,28 +475,35 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     }
 }
 
-// One workgroup of 8 wavefronts per (query row, kv head): wavefront w walks the key blocks w, w + 8, ..., the eight
-// partial results are combined through LDS in a fixed order and the finished row is written as fp32 and/or as packed
-// hi/lo activations. For batches with enough (row, kv head) pairs to fill the chip this replaces the chunked
-// kernel plus the separate merge.
+// One workgroup of 8 wavefronts per (query row, kv head, part of the context): a part is `span` keys (a multiple of
+// 256), wavefront w walks its key blocks w, w + 8, ...; the eight results are combined through LDS in a fixed order.
+// A row whose context fits one part is finished there. Otherwise every part leaves its (max, sum, output) in `part`
+// and counts itself in on cnt[row][kv head]; the workgroup that arrives last combines the parts in their fixed order
+// (whoever arrives last, the arithmetic is the same) and puts the counter back to zero. Nobody waits for anybody.
+// Output: fp32 rows and/or packed hi/lo activations. For batches with enough (row, kv head) pairs to fill the chip
+// this replaces the chunked kernel plus the separate merge.
 constexpr int ATT_ROW_WAVES = 8;
 
 template <int DH>
 __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, RowsInline ri,
-                                                                      float *att, uint4 *pack, int ncb)
+                                                                      int span, float *part, int *cnt, float *att, uint4 *pack, int ncb)
 {
-    constexpr int DB = DH / 32, NW = ATT_ROW_WAVES, GMAX = 8;
+    constexpr int DB = DH / 32, NW = ATT_ROW_WAVES, GMAX = 8, PS = DH + 4;
     __shared__ float s_m[NW][GMAX], s_l[NW][GMAX];
     __shared__ __attribute__((aligned(16))) float s_o[NW][GMAX][DH];
-    const int r = blockIdx.x, g = blockIdx.y, wv = threadIdx.x >> 6;
+    __shared__ int s_last;
+    const int r = blockIdx.x, g = blockIdx.y, pt = blockIdx.z, P = gridDim.z, wv = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
     const int ctx = (ri.n ? ri.pos[r] : rows.pos[r]) + 1;
     const int slot = ri.n ? ri.slot[r] : rows.slot[r];
+    const int j0 = pt * span, j1 = min(ctx, j0 + span);
+    if (j0 >= ctx) return;                            // this part holds no key of the row
+    const int parts = (ctx + span - 1) / span;        // parts of this row that hold keys
 
-    if (wv * 32 < ctx) {
+    if (j0 + wv * 32 < j1) {
         AttnWave<DH> w;
         w.run(D, q + (size_t)r * D.qw, kc + ((size_t)slot * D.Hkv + g) * (size_t)D.max_seq * DH, vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * D.vts, g,
-              wv * 32, NW * 32, ctx);
+              j0 + wv * 32, NW * 32, j1);
         const float lt = w.l + __shfl_xor(w.l, 32, 64);
         if (j < G) {
 #pragma unroll
@@ -509,15 +516,15 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
         }
     }
     __syncthreads();
-    const int live = min(NW, (ctx + 31) / 32);       // wavefronts that had keys
+    const int live = min(NW, (j1 - j0 + 31) / 32);   // wavefronts that had keys
     const int task = threadIdx.x;                    // (head of the group, 8 dims)
-    if (task < G * (DH / 8)) {
-        const int h = task / (DH / 8), d0 = (task % (DH / 8)) * 8;
-        float M = -INFINITY;
-        for (int w2 = 0; w2 < live; ++w2) M = fmaxf(M, s_m[w2][h]);
-        float L = 0.f, o[8];
+    const bool worker = task < G * (DH / 8);
+    const int h = task / (DH / 8), d0 = (task % (DH / 8)) * 8;
+    float M = -INFINITY, L = 0.f, o[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = 0.f;
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+    if (worker) {
+        for (int w2 = 0; w2 < live; ++w2) M = fmaxf(M, s_m[w2][h]);
         for (int w2 = 0; w2 < live; ++w2) {
             const float c = __expf(s_m[w2][h] - M);
             L = fmaf(s_l[w2][h], c, L);
@@ -525,30 +532,79 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
             o[0] = fmaf(a.x, c, o[0]); o[1] = fmaf(a.y, c, o[1]); o[2] = fmaf(a.z, c, o[2]); o[3] = fmaf(a.w, c, o[3]);
             o[4] = fmaf(b.x, c, o[4]); o[5] = fmaf(b.y, c, o[5]); o[6] = fmaf(b.z, c, o[6]); o[7] = fmaf(b.w, c, o[7]);
         }
-        const float inv = 1.0f / L;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] *= inv;
-        const int col = (g * G + h) * DH + d0;
-        if (att) {
-            *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col) = make_float4(o[0], o[1], o[2], o[3]);
-            *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col + 4) = make_float4(o[4], o[5], o[6], o[7]);
-        }
-        if (pack) store_packed(pack + (size_t)(r >> 6) * (D.qw / 16) * ncb * 64, ncb, r & 63, col >> 3, o);
     }
+    if (parts > 1) {
+        // leave this part's result, count in, and go on only as the last arrival of the row
+        // The exchange goes through device-coherent accesses only (write-through stores, loads that bypass the
+        // non-coherent cache levels): each is visible device-wide once it has completed, so waiting for this
+        // wavefront's outstanding stores is all the ordering needed, and no cache is flushed or invalidated as a whole
+        // (a device-scope fence writes back the entire L2 of the XCD, far more than this exchange is worth).
+        if (worker) {
+            float *pp = part + (((size_t)r * D.Hq + g * G + h) * P + pt) * PS;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) __hip_atomic_store(pp + d0 + e, o[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (d0 == 0) {
+                __hip_atomic_store(pp + DH, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(pp + DH + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wavefront's stores have completed
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int *c = cnt + (size_t)r * D.Hkv + g;
+            const int old = __hip_atomic_fetch_add(c, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_last = old == parts - 1;
+            if (old == parts - 1) __hip_atomic_store(c, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // every part has counted: ready for the next launch
+        }
+        __syncthreads();
+        if (!s_last) return;
+        if (worker) {
+            const float *pp = part + ((size_t)r * D.Hq + g * G + h) * P * PS;
+            M = -INFINITY;
+            for (int c = 0; c < parts; ++c) M = fmaxf(M, __hip_atomic_load(pp + c * PS + DH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            L = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = 0.f;
+            for (int c = 0; c < parts; ++c) {
+                const float *pc = pp + c * PS;
+                const float wgt = __expf(__hip_atomic_load(pc + DH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - M);
+                L = fmaf(__hip_atomic_load(pc + DH + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, L);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = fmaf(__hip_atomic_load(pc + d0 + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, o[e]);
+            }
+        }
+    }
+    if (!worker) return;
+    const float inv = 1.0f / L;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] *= inv;
+    const int col = (g * G + h) * DH + d0;
+    if (att) {
+        *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col) = make_float4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col + 4) = make_float4(o[4], o[5], o[6], o[7]);
+    }
+    if (pack) store_packed(pack + (size_t)(r >> 6) * (D.qw / 16) * ncb * 64, ncb, r & 63, col >> 3, o);
 }
 
 void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, const RowsInline &ri, int max_ctx, float *part,
-                           size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer)
+                           size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
     if (rows.n * D.Hkv >= 64 && D.G <= 8) {   // enough (row, kv head) pairs to fill the chip with one workgroup each
-        const dim3 grid(rows.n, D.Hkv);
+        // parts of 512 keys (two key blocks per wavefront), longer ones when the partials buffer or the limit of 16 parts asks for it
+        size_t room = part_floats / ((size_t)rows.n * D.Hq * (D.dh + 4));
+        if (room > 16) room = 16;
+        if (room < 1) room = 1;
+        int span = 512;
+        if ((size_t)(max_ctx + span - 1) / span > room) span = 256 * (int)((max_ctx + 256 * room - 1) / (256 * room));
+        const int P = (max_ctx + span - 1) / span;
+        const dim3 grid(rows.n, D.Hkv, P);
         if (D.dh == 64)
-            hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri,
-                               pack ? nullptr : att, (uint4 *)pack, ncb);
+            hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, span, part,
+                               cnt, pack ? nullptr : att, (uint4 *)pack, ncb);
         else
-            hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri,
-                               pack ? nullptr : att, (uint4 *)pack, ncb);
+            hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, span, part,
+                               cnt, pack ? nullptr : att, (uint4 *)pack, ncb);
         return;
     }
     // decode: up to 32 chunks of the context per row, merged afterwards; prompts: one wavefront walks the whole context of a row

@@ -21,6 +21,7 @@ struct Layout {
     size_t k_layer_bytes, v_layer_bytes;
     size_t kc, vc, rope, counters, slot, tok, pos, gather, x, q, att, h, hn, attn_part, tail_part, total;
     size_t attn_part_floats;
+    size_t attn_cnt;
     int max_rows, nslices;
     // matrix-core path: repacked weights, packed activations, split-K partials
     bool mfma;
@@ -79,6 +80,7 @@ Layout make_layout(const tr_config *c)
     L.x = take(R * c->d_model * 4); L.q = take(R * qw * 4); L.att = take(R * qw * 4); L.h = take(R * c->d_ffn * 4);
     L.hn = take((size_t)c->max_batch * c->d_model * 4);
     L.attn_part = take(L.attn_part_floats * 4);
+    L.attn_cnt = take(R * c->n_kv_heads * 4);
     L.mfma = mfma_supported(c);
     const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab) : 0;
     L.tail_part = take((size_t)(L.nslices > head_wgs ? L.nslices : head_wgs) * c->max_batch * sizeof(float4));
@@ -199,7 +201,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, const RowsInline 
             const LayerW &w = ctx->layers[(size_t)l];
             launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
             launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, ri, max_ctx, ctx->at<float>(L.attn_part),
-                             attn_part_floats, att, nullptr, 0, &pend);
+                             attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, &pend);
             launch_oproj(s, ctx->c.dtype, D, w.wo, att, pend, R, x);
             launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
             launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
@@ -218,7 +220,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, const RowsInline 
         launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
                         ctx->kc_layer(l), ctx->vc_layer(l));
         launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, ri, max_ctx, ctx->at<float>(L.attn_part),
-                         attn_part_floats, att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
+                         attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
         launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
         p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
         launch_prep(s, p);
@@ -337,6 +339,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.counters, 0, (size_t)cfg->max_batch * 2 * sizeof(long long));
     // the attention kernels read whole 32-key blocks and mask afterwards: cache positions never written must hold finite values
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.kc, 0, lay.rope - lay.kc);
+    if (e == hipSuccess) e = hipMemset(ctx->ws + lay.attn_cnt, 0, (size_t)lay.max_rows * cfg->n_kv_heads * 4);
     if (e == hipSuccess && lay.mfma) {
         // one-time repack of the bf16 matrices into matrix-core tiles; q|k|v are concatenated, gate/up interleaved
         for (int l = 0; l < D.L; ++l) {

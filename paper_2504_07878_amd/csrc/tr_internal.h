@@ -88,10 +88,12 @@ void launch_iota_rows(hipStream_t s, int n, int slot, int *d_slot, int *d_pos);
 void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, int d, float *x);
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope,
                 float *q, void *kc, void *vc);
+// cnt: one zero-initialised int per (row, kv head), left at zero again by every launch (arrival counters of the
+// workgroups that share a row when its context is split)
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, const RowsInline &ri,
-                      int max_ctx, float *part, size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer);
+                      int max_ctx, float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
 void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, const RowsInline &ri, int max_ctx, float *part,
-                           size_t part_floats, float *att, void *pack, int ncb, AttnPending *defer);
+                           size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
 void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, const RowsInline &ri, int chunk, float *att, void *pack, int ncb);
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
