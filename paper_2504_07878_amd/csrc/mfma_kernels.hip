@@ -380,7 +380,7 @@ struct AttnWave {
                 for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
                     for (int db = 0; db < DB; ++db)
-                        va[nb][kk][db] = *reinterpret_cast<const uint4 *>(Vb + (size_t)(db * 32 + j) * D.vts + tv + 16 * kk + 8 * hf);
+                        va[nb][kk][db] = *reinterpret_cast<const uint4 *>(Vb + ((size_t)(tv >> 5) * DH + db * 32 + j) * 32 + 16 * kk + 8 * hf);
             }
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
@@ -731,10 +731,10 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append
                 KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)rslot * Hkv + head) * max_seq + p) * dh + e0;
                 store8(dst, lo);
                 store8(dst + half, hi);
-            } else {   // transposed V: one position of 16 dim rows
-                KT *dst = vc + (((size_t)rslot * Hkv + head) * dh + e0) * vts + p;
+            } else {   // block-transposed V: one position of 16 dim rows
+                KT *dst = vc + ((((size_t)rslot * Hkv + head) * (vts >> 5) + (p >> 5)) * dh + e0) * 32 + (p & 31);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) { store1(dst + (size_t)e * vts, lo[e]); store1(dst + (size_t)(half + e) * vts, hi[e]); }
+                for (int e = 0; e < 8; ++e) { store1(dst + e * 32, lo[e]); store1(dst + (half + e) * 32, hi[e]); }
             }
         }
     }

@@ -12,7 +12,8 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 
 struct Dims {
     int L, d, Hq, Hkv, dh, F, V, qw, kvw, G, rh, max_batch, max_seq;
-    int vts;   // bf16 cache: V is stored transposed, [slot][kv head][dim][vts positions] (vts = max_seq rounded up to 32);
+    int vts;   // bf16 cache: V is stored transposed in blocks of 32 positions, [slot][kv head][position / 32][dim][position % 32]
+               // (vts = max_seq rounded up to 32), so that the V^T operand of one block of 32 keys is dh*64 consecutive bytes;
                // 0: V is stored like K, [slot][kv head][position][dim] (fp32 cache)
     float eps;
 };
@@ -20,7 +21,8 @@ struct Dims {
 // element offset of V[slot][head][pos][dim] inside one layer's V cache
 __host__ __device__ inline size_t v_offset(const Dims &D, int slot, int head, int pos, int dim)
 {
-    return D.vts ? (((size_t)slot * D.Hkv + head) * D.dh + dim) * D.vts + pos : (((size_t)slot * D.Hkv + head) * D.max_seq + pos) * D.dh + dim;
+    return D.vts ? ((((size_t)slot * D.Hkv + head) * (D.vts >> 5) + (pos >> 5)) * D.dh + dim) * 32 + (pos & 31)
+                 : (((size_t)slot * D.Hkv + head) * D.max_seq + pos) * D.dh + dim;
 }
 
 // Weights of one decoder layer (device pointers in the model's storage type).
