@@ -591,11 +591,12 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
 {
     if (defer) defer->nchunks = 0;
     if (rows.n * D.Hkv >= 64 && D.G <= 8) {   // enough (row, kv head) pairs to fill the chip with one workgroup each
-        // parts of 512 keys (two key blocks per wavefront), longer ones when the partials buffer or the limit of 16 parts asks for it
+        // parts of 768 keys (three key blocks per wavefront; measured best among 256..1024 on the ragged 64-sequence workload),
+        // longer ones when the partials buffer or the limit of 16 parts asks for it
         size_t room = part_floats / ((size_t)rows.n * D.Hq * (D.dh + 4));
         if (room > 16) room = 16;
         if (room < 1) room = 1;
-        int span = 512;
+        int span = 768;
         if ((size_t)(max_ctx + span - 1) / span > room) span = 256 * (int)((max_ctx + 256 * room - 1) / (256 * room));
         const int P = (max_ctx + span - 1) / span;
         const dim3 grid(rows.n, D.Hkv, P);
