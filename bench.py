@@ -58,9 +58,10 @@ def time_decode(model, slots, tokens_per_step, steps, warmup, out):
         model.decode_step(slots, tokens_per_step[i % len(tokens_per_step)], out)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms, launches = model.profile_read()
+    ms, gap_ms, launches = model.profile_read()
     model.profile_enable(False)
-    return dt, ms, launches, base
+    # kernel duration = bracketed interval minus the empty event interval recorded right behind it on the same stream
+    return dt, ms - gap_ms, launches, base, (ms, gap_ms)
 
 
 def cpu_baseline(s, weights, seconds_budget=20.0):
@@ -162,7 +163,7 @@ def main():
     log(f"prefill of {int(lens.sum())} tokens: {prefill_s:.3f}s")
 
     toks = synth.prompt_tokens(SEED, "cfg3.steps", 512 * B, s.vocab).reshape(512, B)
-    dt, lm_ms, lm_n, base = time_decode(model, slots, toks, steps, args.warmup, out)
+    dt, lm_ms, lm_n, base, lm_raw = time_decode(model, slots, toks, steps, args.warmup, out)
     ms_per_step = dt / steps * 1e3
     tok_s = B * steps / dt
     # algorithmic bytes of the timed steps: weights once per step, each sequence's cache once, new K/V written
@@ -183,7 +184,8 @@ def main():
                    "fraction_of_hbm_roofline": tok_s / roof_tok_s},
         "roofline": {"bound": "hbm", "kernel": "gemm_kernel<4,14,EpiLmHead> (LM head of the routing tail, 64 rows)", "achieved": lm_bytes / lm_avg_s / 1e9 if lm_n else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": (lm_bytes / lm_avg_s / 1e9 / HBM_PEAK_GBPS) if lm_n else None,
-                     "traffic": measured_traffic(), "launches": lm_n, "avg_us": lm_avg_s * 1e6, "algorithmic_bytes_per_launch": lm_bytes},
+                     "traffic": measured_traffic(), "launches": lm_n, "avg_us": lm_avg_s * 1e6, "algorithmic_bytes_per_launch": lm_bytes,
+                     "event_pair_avg_us": lm_raw[0] / max(lm_n, 1) * 1e3, "empty_event_pair_avg_us": lm_raw[1] / max(lm_n, 1) * 1e3},
     }
 
     if not args.no_extras:
@@ -194,7 +196,7 @@ def main():
         out1 = model.outputs(1)
         model.prefill([0], [p1], out1)
         n1 = min(steps, 256)
-        dt1, ms1, l1, _ = time_decode(model, [0], toks[:, :1], n1, args.warmup, out1)
+        dt1, ms1, l1, _, _ = time_decode(model, [0], toks[:, :1], n1, args.warmup, out1)
         b1_bytes = weight_bytes_per_step(s) + (256 + (n1 - 1) / 2 + 1) * kvb
         extras["b1_decode"] = {"tokens_per_s": n1 / dt1, "ms_per_step": dt1 / n1 * 1e3, "steps": n1,
                                "hbm_roofline_tokens_per_s": HBM_PEAK_GBPS * 1e9 / b1_bytes,

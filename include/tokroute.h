@@ -138,10 +138,13 @@ int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, con
 int tr_counters_ptr(const tr_ctx *ctx, const int64_t **dev_counters);
 
 /* Kernel timing for benchmarks: while enabled, the LM-head kernel of every tail launch is bracketed by
- * HIP events on the launch stream. tr_profile_read synchronises those events and returns the summed
- * duration in milliseconds and the number of launches since enabling. */
+ * two HIP events on the launch stream, and a third event is recorded straight after the second, so that
+ * the cost of an event pair with nothing in between is measured in the same place of the same stream.
+ * tr_profile_read synchronises those events and returns, summed over the launches since enabling, the
+ * bracketed duration (ms_total) and the empty intervals (ms_empty_pairs), in milliseconds, and the
+ * number of launches: (ms_total - ms_empty_pairs) / launches estimates the kernel's own duration. */
 int tr_profile_enable(tr_ctx *ctx, int32_t on);
-int tr_profile_read(tr_ctx *ctx, double *ms_total, int64_t *launches);
+int tr_profile_read(tr_ctx *ctx, double *ms_total, double *ms_empty_pairs, int64_t *launches);
 
 const char *tr_last_error(const tr_ctx *ctx);
 

@@ -267,7 +267,7 @@ void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
 }
 
 // the all-streaming tail: norm, LM head slices, merge + router
-void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1)
+void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1, hipEvent_t ev2)
 {
     if (wdt == DT_F32)
         hipLaunchKernelGGL(tail_norm_kernel<float>, dim3(t.n), dim3(256), 0, s, D.d, D.eps, (const float *)t.final_norm, t.x, t.gather, t.hn,
@@ -278,6 +278,7 @@ void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEv
     if (ev0) (void)hipEventRecord(ev0, s);
     launch_lmhead_gemv(s, wdt, D, t);
     if (ev1) (void)hipEventRecord(ev1, s);
+    if (ev2) (void)hipEventRecord(ev2, s);
     launch_tail_final(s, wdt, D, t);
 }
 

@@ -123,9 +123,9 @@ struct tr_ctx {
     std::string err;
     // kernel timing
     bool profile = false;
-    std::vector<hipEvent_t> ev;   // pairs
+    std::vector<hipEvent_t> ev;   // triples: before the kernel, after it, and once more straight away
     size_t ev_used = 0;
-    double prof_ms = 0.0;
+    double prof_ms = 0.0, prof_gap_ms = 0.0;
     long long prof_launches = 0;
 
     template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
@@ -165,24 +165,27 @@ bool slots_ok(const tr_ctx *ctx, int n, const int32_t *slots)
 
 void drain_profile(tr_ctx *ctx)
 {
-    for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
-        float ms = 0.f;
-        if (hipEventSynchronize(ctx->ev[i + 1]) == hipSuccess && hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]) == hipSuccess) {
+    for (size_t i = 0; i + 2 < ctx->ev_used; i += 3) {
+        float ms = 0.f, gap = 0.f;
+        if (hipEventSynchronize(ctx->ev[i + 2]) == hipSuccess && hipEventElapsedTime(&ms, ctx->ev[i], ctx->ev[i + 1]) == hipSuccess &&
+            hipEventElapsedTime(&gap, ctx->ev[i + 1], ctx->ev[i + 2]) == hipSuccess) {
             ctx->prof_ms += ms;
+            ctx->prof_gap_ms += gap;
             ctx->prof_launches += 1;
         }
     }
     ctx->ev_used = 0;
 }
 
-void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1)
+void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1, hipEvent_t *e2)
 {
-    *e0 = *e1 = nullptr;
+    *e0 = *e1 = *e2 = nullptr;
     if (!ctx->profile) return;
-    if (ctx->ev_used + 2 > ctx->ev.size()) drain_profile(ctx);
+    if (ctx->ev_used + 3 > ctx->ev.size()) drain_profile(ctx);
     *e0 = ctx->ev[ctx->ev_used];
     *e1 = ctx->ev[ctx->ev_used + 1];
-    ctx->ev_used += 2;
+    *e2 = ctx->ev[ctx->ev_used + 2];
+    ctx->ev_used += 3;
 }
 
 // All layers over the rows currently described by the device row arrays. Returns the number of split-K partial
@@ -236,11 +239,11 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
 {
     const Dims &D = ctx->D;
     const Layout &L = ctx->lay;
-    hipEvent_t e0, e1;
-    next_events(ctx, &e0, &e1);
+    hipEvent_t e0, e1, e2;
+    next_events(ctx, &e0, &e1, &e2);
     if (!ctx->lay.mfma) {
         t.x = x + (size_t)row0 * D.d;
-        launch_tail(s, ctx->c.dtype, D, t, e0, e1);
+        launch_tail(s, ctx->c.dtype, D, t, e0, e1, e2);
         return;
     }
     PrepArgs p{};
@@ -254,6 +257,7 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     t.nslices = lmhead_mfma_wgs(D.V);
     launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits);
     if (e1) (void)hipEventRecord(e1, s);
+    if (e2) (void)hipEventRecord(e2, s);
     launch_tail_final(s, ctx->c.dtype, D, t);
 }
 
@@ -522,23 +526,24 @@ int tr_profile_enable(tr_ctx *ctx, int32_t on)
 {
     if (!ctx) return TR_ERR_INVALID_ARG;
     if (on && ctx->ev.empty()) {
-        ctx->ev.resize(512);
+        ctx->ev.resize(3 * 256);
         for (auto &e : ctx->ev) {
             hipError_t rc = hipEventCreate(&e);
             if (rc != hipSuccess) { ctx->ev.clear(); return fail_hip(ctx, rc, "tr_profile_enable: hipEventCreate"); }
         }
     }
-    if (on && !ctx->profile) { ctx->prof_ms = 0.0; ctx->prof_launches = 0; ctx->ev_used = 0; }
+    if (on && !ctx->profile) { ctx->prof_ms = ctx->prof_gap_ms = 0.0; ctx->prof_launches = 0; ctx->ev_used = 0; }
     if (!on && ctx->profile) drain_profile(ctx);
     ctx->profile = on != 0;
     return TR_OK;
 }
 
-int tr_profile_read(tr_ctx *ctx, double *ms_total, int64_t *launches)
+int tr_profile_read(tr_ctx *ctx, double *ms_total, double *ms_empty_pairs, int64_t *launches)
 {
-    if (!ctx || !ms_total || !launches) return TR_ERR_INVALID_ARG;
+    if (!ctx || !ms_total || !ms_empty_pairs || !launches) return TR_ERR_INVALID_ARG;
     drain_profile(ctx);
     *ms_total = ctx->prof_ms;
+    *ms_empty_pairs = ctx->prof_gap_ms;
     *launches = ctx->prof_launches;
     return TR_OK;
 }

@@ -100,7 +100,8 @@ void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchu
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x);
-void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1);
+// ev0/ev1 bracket the LM-head kernel, ev2 follows ev1 at once (an empty interval in the same place); all may be null
+void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1, hipEvent_t ev2);
 void launch_load_kv(hipStream_t s, int kdt, const Dims &D, int slot, int len, const void *k, const void *v, void *kc, void *vc);
 void launch_reset_counters(hipStream_t s, long long *counters, int slot);
 

@@ -71,7 +71,7 @@ def load_library():
         L.tr_seq_load_kv.argtypes = [vp, vp, i32, i32, vp, vp]
         L.tr_counters_ptr.argtypes = [vp, C.POINTER(vp)]
         L.tr_profile_enable.argtypes = [vp, i32]
-        L.tr_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.tr_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.tr_last_error.argtypes = [vp]; L.tr_last_error.restype = C.c_char_p
         _lib = L
     return _lib
@@ -239,6 +239,6 @@ class Model:
         self._check(self.lib.tr_profile_enable(self._h, int(bool(on))), "tr_profile_enable")
 
     def profile_read(self):
-        ms, n = C.c_double(), C.c_int64()
-        self._check(self.lib.tr_profile_read(self._h, C.byref(ms), C.byref(n)), "tr_profile_read")
-        return ms.value, n.value
+        ms, gap, n = C.c_double(), C.c_double(), C.c_int64()
+        self._check(self.lib.tr_profile_read(self._h, C.byref(ms), C.byref(gap), C.byref(n)), "tr_profile_read")
+        return ms.value, gap.value, n.value
