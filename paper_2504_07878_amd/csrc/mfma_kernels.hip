@@ -475,13 +475,14 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     }
 }
 
-// One workgroup of 8 wavefronts per (query row, kv head, part of the context): a part is `span` keys (a multiple of
-// 256), wavefront w walks its key blocks w, w + 8, ...; the eight results are combined through LDS in a fixed order.
-// A row whose context fits one part is finished there. Otherwise every part leaves its (max, sum, output) in `part`
-// and counts itself in on cnt[row][kv head]; the workgroup that arrives last combines the parts in their fixed order
-// (whoever arrives last, the arithmetic is the same) and puts the counter back to zero. Nobody waits for anybody.
-// Output: fp32 rows and/or packed hi/lo activations. For batches with enough (row, kv head) pairs to fill the chip
-// this replaces the chunked kernel plus the separate merge.
+// One workgroup of 8 wavefronts per (query row, kv head, part of the context). A row is split into as few parts as
+// `span` (the longest part allowed, a multiple of 256 keys) permits, of equal length so that they finish together;
+// wavefront w walks the key blocks w, w + 8, ... of its part and the eight results are combined through LDS in a
+// fixed order. A row whose context fits one part is finished there. Otherwise every part leaves its (max, sum,
+// output) in `part` and counts itself in on cnt[row][kv head]; the workgroup that arrives last combines the parts in
+// their fixed order (whoever arrives last, the arithmetic is the same) and puts the counter back to zero. Nobody
+// waits for anybody. Output: fp32 rows and/or packed hi/lo activations. For batches with enough (row, kv head)
+// pairs to fill the chip this replaces the chunked kernel plus the separate merge.
 constexpr int ATT_ROW_WAVES = 8;
 
 template <int DH>
@@ -496,9 +497,10 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
     const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
     const int ctx = (ri.n ? ri.pos[r] : rows.pos[r]) + 1;
     const int slot = ri.n ? ri.slot[r] : rows.slot[r];
-    const int j0 = pt * span, j1 = min(ctx, j0 + span);
-    if (j0 >= ctx) return;                            // this part holds no key of the row
-    const int parts = (ctx + span - 1) / span;        // parts of this row that hold keys
+    const int parts = (ctx + span - 1) / span;        // parts this row is split into: as few as the longest part allows ...
+    if (pt >= parts) return;                          // (uniform over the workgroup, before any barrier)
+    const int len = 256 * ((ctx + 256 * parts - 1) / (256 * parts));   // ... and of equal length, so that they finish together
+    const int j0 = pt * len, j1 = min(ctx, j0 + len);
 
     if (j0 + wv * 32 < j1) {
         AttnWave<DH> w;
