@@ -186,10 +186,11 @@ def test_tiny_run_twice_is_bit_identical(tr, tiny_weights):
         assert np.array_equal(x.logits, y.logits) and np.array_equal(x.score, y.score) and np.array_equal(x.conf, y.conf)
 
 
-@pytest.mark.parametrize("B", [9, 33, 70])
+@pytest.mark.parametrize("B", [9, 33, 70, 256])
 def test_small_bf16_model_on_the_matrix_core_path(tr, tro, B):
     """bf16 weights and more than 8 rows take the MFMA kernels: batches of 9 (one column block), 33 (two) and 70 (two row
-    groups), ragged prompts up to several 64-row groups, non-zero biases, non-unit gains."""
+    groups) and 256 (four row groups, the LM head's XCD-aware placement), ragged prompts up to several 64-row groups,
+    non-zero biases, non-unit gains."""
     s = synth.TINY.with_(dtype=synth.BF16, kv_dtype=synth.BF16)
     w = synth.make_weights(s, SEED + 3, std=0.05, bias_std=0.05, gain_std=0.1)
     max_seq = 200
