@@ -103,10 +103,6 @@ template <int MB> struct DotsCfg {
     static constexpr int LDS_FLOATS = MB * KC + 4 * MB;   // the staged chunk, then one sum of squares per wavefront and row
 };
 
-// Row groups per wavefront. More than one amortises the activation staging, but leaves too few wavefronts to fill
-// the chip evenly at the shapes in use (measured: 2 and 4 groups are 5 % and 17 % slower on the 7B-class FFN).
-constexpr int NP_GROUPS = 1;
-
 // Where the staged activations come from: plain fp32 rows ...
 struct StageRows {
     const float *x;
@@ -139,20 +135,22 @@ struct StageAttn {
     __device__ __forceinline__ void advance(int rows) { r0 += rows; }
 };
 
-// Workgroup-wide GEMV step: the 4 wavefronts of a workgroup each own NP groups of NR weight rows; the MB activation
+// Workgroup-wide GEMV step: the 4 wavefronts of a workgroup each own NR weight rows; the MB activation
 // rows are staged through LDS in chunks of KC columns (read once from memory per workgroup, then broadcast from LDS,
 // which keeps the vector-memory pipe free for the weight stream). With NORM the staged values are x*gain and the rows'
 // sums of squares are accumulated while staging, so that W.(g*x/rms) = W.(g*x) / rms needs no normalisation pass and
 // no per-weight work. The weight stream does not depend on the staging, so it runs one batch ahead of the arithmetic
 // in two register sets: the first batch is requested before the activations are staged, and each later batch while
-// the previous one is consumed, across row groups and chunk boundaries. Requests past the end of a row are
+// the previous one is consumed, across chunk boundaries. Requests past the end of a row are
 // redirected to its last 16 bytes (one cache line for the whole wavefront) and their result is unused, which keeps
 // every request unconditional and the number in flight known at compile time.
 // Every wavefront of the workgroup must call this (barriers inside). xs: LDS buffer of DotsCfg<MB>::LDS_FLOATS floats.
 // Rows m >= mvalid are read as zeros. K % 8 == 0. Results are valid in every lane.
-template <typename WT, int NP, int NR, int MB, bool NORM, class Stage>
-__device__ __forceinline__ void wg_dots(const WT *(&wrow)[NP][NR], const WT *gain, const Stage &src, int mvalid, int K, float *xs,
-                                        float (&acc)[NP][NR][MB], float (&ss)[MB])
+// (Several row groups per wavefront, which would amortise the staging, were measured 5 % to 17 % slower on the
+// 7B-class FFN: too few wavefronts are left to fill the chip evenly.)
+template <typename WT, int NR, int MB, bool NORM, class Stage>
+__device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *gain, const Stage &src, int mvalid, int K, float *xs,
+                                        float (&acc)[NR][MB], float (&ss)[MB])
 {
     constexpr int U = DotsCfg<MB>::U, BATCH = DotsCfg<MB>::BATCH, KC = DotsCfg<MB>::KC;
     const int lane = threadIdx.x & 63;
@@ -160,31 +158,29 @@ __device__ __forceinline__ void wg_dots(const WT *(&wrow)[NP][NR], const WT *gai
     for (int m = 0; m < MB; ++m) {
         ss[m] = 0.f;
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
-#pragma unroll
-            for (int r = 0; r < NR; ++r) acc[p][r][m] = 0.f;
+        for (int r = 0; r < NR; ++r) acc[r][m] = 0.f;
     }
     Raw8<WT> rw[2][U][NR];
     const float *xr[MB];
 #pragma unroll
     for (int m = 0; m < MB; ++m) xr[m] = xs + m * KC;
 
-#define TR_ISSUE(SET, P, K0)                                                                  \
+#define TR_ISSUE(SET, K0)                                                                     \
     _Pragma("unroll") for (int u = 0; u < U; ++u) {                                           \
         const int kk = min((K0) + u * 512 + lane * 8, K - 8);                                 \
-        _Pragma("unroll") for (int r = 0; r < NR; ++r) rw[SET][u][r].load(wrow[P][r] + kk);   \
+        _Pragma("unroll") for (int r = 0; r < NR; ++r) rw[SET][u][r].load(wrow[r] + kk);      \
     }
-#define TR_CONSUME(SET, P, K0, KC0)                                                           \
+#define TR_CONSUME(SET, K0, KC0)                                                              \
     if ((K0) + BATCH <= K) {                                                                  \
         _Pragma("unroll") for (int u = 0; u < U; ++u)                                         \
-            dots_step<WT, NR, MB>(rw[SET][u], xr, (K0) - (KC0) + u * 512 + lane * 8, acc[P]); \
+            dots_step<WT, NR, MB>(rw[SET][u], xr, (K0) - (KC0) + u * 512 + lane * 8, acc);    \
     } else {                                                                                  \
         _Pragma("unroll") for (int u = 0; u < U; ++u)                                         \
             if ((K0) + u * 512 + lane * 8 < K)                                                \
-                dots_step<WT, NR, MB>(rw[SET][u], xr, (K0) - (KC0) + u * 512 + lane * 8, acc[P]); \
+                dots_step<WT, NR, MB>(rw[SET][u], xr, (K0) - (KC0) + u * 512 + lane * 8, acc);    \
     }
 
-    TR_ISSUE(0, 0, 0)
+    TR_ISSUE(0, 0)
     for (int kc0 = 0; kc0 < K; kc0 += KC) {
         const int kc = min(KC, K - kc0);
         __syncthreads();
@@ -203,22 +199,17 @@ __device__ __forceinline__ void wg_dots(const WT *(&wrow)[NP][NR], const WT *gai
             }
         }
         __syncthreads();
-#pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            TR_ISSUE(1, p, kc0 + BATCH)
-            TR_CONSUME(0, p, kc0, kc0)
-            if (p + 1 < NP) { TR_ISSUE(0, p + 1, kc0) } else { TR_ISSUE(0, 0, kc0 + KC) }
-            TR_CONSUME(1, p, kc0 + BATCH, kc0)
-        }
+        TR_ISSUE(1, kc0 + BATCH)
+        TR_CONSUME(0, kc0, kc0)
+        TR_ISSUE(0, kc0 + KC)
+        TR_CONSUME(1, kc0 + BATCH, kc0)
     }
 #undef TR_ISSUE
 #undef TR_CONSUME
 #pragma unroll
     for (int m = 0; m < MB; ++m)
 #pragma unroll
-        for (int p = 0; p < NP; ++p)
-#pragma unroll
-            for (int r = 0; r < NR; ++r) acc[p][r][m] = wave_sum(acc[p][r][m]);
+        for (int r = 0; r < NR; ++r) acc[r][m] = wave_sum(acc[r][m]);
     if (NORM) {
         float *red = xs + MB * KC;
 #pragma unroll
@@ -307,90 +298,65 @@ void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, 
 // n = RMSNorm(x; ln1); [q|k|v] = W n + b; rotate q and k at the row's position; append k, v to the cache.
 // One wavefront computes the two output rows (j, j + dh/2) of one head that the rotation pairs up.
 
-template <typename WT, typename KT, int MB, int NP>
+template <typename WT, typename KT, int MB>
 __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float *x, Rows rows, const float2 *rope, float *q, KT *kc,
                                                   KT *vc)
 {
     __shared__ __attribute__((aligned(16))) float xs[DotsCfg<MB>::LDS_FLOATS];
     const int half = D.dh / 2;
     const int npairs = (D.Hq + 2 * D.Hkv) * half;
-    const int pair0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * NP;
-    const WT *wrow[NP][2];
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        const int pair = min(pair0 + p, npairs - 1);   // surplus pairs redo the last one and drop it
-        const int hh = pair / half, j = pair % half;
-        const WT *W;
-        int head;  // head index inside its own matrix
-        if (hh < D.Hq) { W = (const WT *)w.wq; head = hh; }
-        else if (hh < D.Hq + D.Hkv) { W = (const WT *)w.wk; head = hh - D.Hq; }
-        else { W = (const WT *)w.wv; head = hh - D.Hq - D.Hkv; }
-        const int n1 = head * D.dh + j;
-        wrow[p][0] = W + (size_t)n1 * D.d;
-        wrow[p][1] = W + (size_t)(n1 + half) * D.d;
-    }
+    const int pair_raw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int pair = pair_raw < npairs ? pair_raw : npairs - 1;   // surplus wavefronts redo the last pair and drop it
+    const int hh = pair / half, j = pair % half;
+    const WT *W, *bias;
+    int head;  // head index inside its own matrix
+    if (hh < D.Hq) { W = (const WT *)w.wq; bias = (const WT *)w.bq; head = hh; }
+    else if (hh < D.Hq + D.Hkv) { W = (const WT *)w.wk; bias = (const WT *)w.bk; head = hh - D.Hq; }
+    else { W = (const WT *)w.wv; bias = (const WT *)w.bv; head = hh - D.Hq - D.Hkv; }
+    const int n1 = head * D.dh + j, n2 = n1 + half;
+    const WT *const wrow[2] = {W + (size_t)n1 * D.d, W + (size_t)n2 * D.d};
     const int r0 = blockIdx.y * MB;
-    float acc[NP][2][MB], ss[MB];
-    wg_dots<WT, NP, 2, MB, true>(wrow, (const WT *)w.ln1, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, rows.n - r0, D.d, xs, acc, ss);
-    if ((threadIdx.x & 63) != 0) return;
+    float acc[2][MB], ss[MB];
+    wg_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, rows.n - r0, D.d, xs, acc, ss);
+    if ((threadIdx.x & 63) != 0 || pair_raw >= npairs) return;
+    const float b1 = bias ? widen(bias, n1) : 0.f, b2 = bias ? widen(bias, n2) : 0.f;
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        const int pair = pair0 + p;
-        if (pair >= npairs) break;
-        const int hh = pair / half, j = pair % half;
-        const WT *bias;
-        int head;
-        if (hh < D.Hq) { bias = (const WT *)w.bq; head = hh; }
-        else if (hh < D.Hq + D.Hkv) { bias = (const WT *)w.bk; head = hh - D.Hq; }
-        else { bias = (const WT *)w.bv; head = hh - D.Hq - D.Hkv; }
-        const int n1 = head * D.dh + j, n2 = n1 + half;
-        const float b1 = bias ? widen(bias, n1) : 0.f, b2 = bias ? widen(bias, n2) : 0.f;
-#pragma unroll
-        for (int m = 0; m < MB; ++m) {
-            const int r = r0 + m;
-            if (r >= rows.n) break;
-            const float rstd = 1.0f / sqrtf(ss[m] / (float)D.d + D.eps);
-            float y1 = acc[p][0][m] * rstd + b1, y2 = acc[p][1][m] * rstd + b2;
-            const int pos = rows.pos[r];
-            if (hh < D.Hq + D.Hkv) {
-                const float2 cs = rope[(size_t)pos * half + j];
-                const float o1 = y1 * cs.x - y2 * cs.y, o2 = y2 * cs.x + y1 * cs.y;
-                y1 = o1; y2 = o2;
-            }
-            if (hh < D.Hq) {
-                q[(size_t)r * D.qw + n1] = y1;
-                q[(size_t)r * D.qw + n2] = y2;
-            } else if (hh < D.Hq + D.Hkv) {
-                KT *dst = kc + (((size_t)rows.slot[r] * D.Hkv + head) * D.max_seq + pos) * D.dh;
-                store_kv(dst + j, y1);
-                store_kv(dst + j + half, y2);
-            } else {
-                store_kv(vc + v_offset(D, rows.slot[r], head, pos, j), y1);
-                store_kv(vc + v_offset(D, rows.slot[r], head, pos, j + half), y2);
-            }
+    for (int m = 0; m < MB; ++m) {
+        const int r = r0 + m;
+        if (r >= rows.n) break;
+        const float rstd = 1.0f / sqrtf(ss[m] / (float)D.d + D.eps);
+        float y1 = acc[0][m] * rstd + b1, y2 = acc[1][m] * rstd + b2;
+        const int pos = rows.pos[r];
+        if (hh < D.Hq + D.Hkv) {
+            const float2 cs = rope[(size_t)pos * half + j];
+            const float o1 = y1 * cs.x - y2 * cs.y, o2 = y2 * cs.x + y1 * cs.y;
+            y1 = o1; y2 = o2;
+        }
+        if (hh < D.Hq) {
+            q[(size_t)r * D.qw + n1] = y1;
+            q[(size_t)r * D.qw + n2] = y2;
+        } else if (hh < D.Hq + D.Hkv) {
+            KT *dst = kc + (((size_t)rows.slot[r] * D.Hkv + head) * D.max_seq + pos) * D.dh;
+            store_kv(dst + j, y1);
+            store_kv(dst + j + half, y2);
+        } else {
+            store_kv(vc + v_offset(D, rows.slot[r], head, pos, j), y1);
+            store_kv(vc + v_offset(D, rows.slot[r], head, pos, j + half), y2);
         }
     }
-}
-
-template <typename WT, typename KT, int NP>
-static void launch_qkv_np(hipStream_t s, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q, void *kc,
-                          void *vc)
-{
-    const int pairs = (D.Hq + 2 * D.Hkv) * (D.dh / 2), gx = (pairs + 4 * NP - 1) / (4 * NP);
-    if (rows.n == 1)
-        hipLaunchKernelGGL((qkv_kernel<WT, KT, 1, NP>), dim3(gx, 1), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
-    else if (rows.n == 2)
-        hipLaunchKernelGGL((qkv_kernel<WT, KT, 2, NP>), dim3(gx, 1), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
-    else
-        hipLaunchKernelGGL((qkv_kernel<WT, KT, 4, NP>), dim3(gx, (rows.n + 3) / 4), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc,
-                           (KT *)vc);
 }
 
 template <typename WT, typename KT>
 static void launch_qkv_t(hipStream_t s, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q, void *kc,
                          void *vc)
 {
-    launch_qkv_np<WT, KT, NP_GROUPS>(s, D, w, x, rows, rope, q, kc, vc);
+    const int pairs = (D.Hq + 2 * D.Hkv) * (D.dh / 2), gx = (pairs + 3) / 4;
+    if (rows.n == 1)
+        hipLaunchKernelGGL((qkv_kernel<WT, KT, 1>), dim3(gx, 1), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
+    else if (rows.n == 2)
+        hipLaunchKernelGGL((qkv_kernel<WT, KT, 2>), dim3(gx, 1), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
+    else
+        hipLaunchKernelGGL((qkv_kernel<WT, KT, 4>), dim3(gx, (rows.n + 3) / 4), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
 }
 
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q,
@@ -720,18 +686,17 @@ static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, 
     if ((size_t)rows.n * D.Hq * nchunks * (DH + 4) > part_floats) return false;
     hipLaunchKernelGGL((attn_wave_kernel<KT, DH>), dim3(rows.n, D.Hkv, (nchunks + 3) / 4), dim3(256), 0, s, D, q, (const KT *)kc, (const KT *)vc,
                        rows, chunk, nchunks, part);
-    RowsInline none{};
-    launch_attn_merge(s, D, part, nchunks, rows, none, chunk, pack ? nullptr : att, pack, ncb);
+    launch_attn_merge(s, D, part, nchunks, rows, chunk, pack ? nullptr : att, pack, ncb);
     return true;
 }
 
 // att (fp32 [R][qw]) and/or pack (packed hi/lo activations of the output projection) receive the result.
-void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, const RowsInline &ri,
-                      int max_ctx, float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer)
+void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
+                      float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
     if (kdt == DT_BF16) {   // bf16 cache: V is stored transposed and attention runs on the matrix cores
-        launch_attention_mfma(s, D, q, kc, vc, rows, ri, max_ctx, part, part_floats, cnt, att, pack, ncb, defer);
+        launch_attention_mfma(s, D, q, kc, vc, rows, max_ctx, part, part_floats, cnt, att, pack, ncb, defer);
         return;
     }
     bool done = false;
@@ -753,47 +718,34 @@ void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, con
 
 // ------------------------------------------------------------------ attention output: x += Wo a
 
-template <typename WT, int MB, int NP, class Stage>
+template <typename WT, int MB, class Stage>
 __global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, Stage in, int R, int N, int K, float *x)
 {
     __shared__ __attribute__((aligned(16))) float xs[DotsCfg<MB>::LDS_FLOATS];
-    const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * NP * 2;     // 2*NP consecutive output rows per wavefront
-    const WT *wrow[NP][2];
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        wrow[p][0] = W + (size_t)min(n0 + 2 * p, N - 1) * K;
-        wrow[p][1] = W + (size_t)min(n0 + 2 * p + 1, N - 1) * K;
-    }
+    const int n_raw = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 2;     // two consecutive output rows per wavefront
+    const int n = n_raw < N ? n_raw : 0, n2 = n_raw + 1 < N ? n_raw + 1 : n;
+    const WT *const wrow[2] = {W + (size_t)n * K, W + (size_t)n2 * K};
     const int r0 = blockIdx.y * MB;
-    float acc[NP][2][MB], ss[MB];
+    float acc[2][MB], ss[MB];
     Stage src = in;
     src.advance(r0);
-    wg_dots<WT, NP, 2, MB, false>(wrow, nullptr, src, R - r0, K, xs, acc, ss);
-    if ((threadIdx.x & 63) != 0) return;
+    wg_dots<WT, 2, MB, false>(wrow, nullptr, src, R - r0, K, xs, acc, ss);
+    if ((threadIdx.x & 63) != 0 || n_raw >= N) return;
 #pragma unroll
-    for (int p = 0; p < NP; ++p)
-#pragma unroll
-        for (int m = 0; m < MB; ++m)
-            if (r0 + m < R) {
-                const int n = n0 + 2 * p;
-                if (n < N) x[(size_t)(r0 + m) * N + n] += acc[p][0][m];
-                if (n + 1 < N) x[(size_t)(r0 + m) * N + n + 1] += acc[p][1][m];
-            }
-}
-
-template <typename WT, int NP, class Stage>
-static void launch_residual_gemv_np(hipStream_t s, const void *W, const Stage &in, int R, int N, int K, float *x)
-{
-    const int gx = (N + 8 * NP - 1) / (8 * NP);
-    if (R == 1) hipLaunchKernelGGL((residual_gemv_kernel<WT, 1, NP, Stage>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
-    else if (R == 2) hipLaunchKernelGGL((residual_gemv_kernel<WT, 2, NP, Stage>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
-    else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4, NP, Stage>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    for (int m = 0; m < MB; ++m)
+        if (r0 + m < R) {
+            x[(size_t)(r0 + m) * N + n_raw] += acc[0][m];
+            if (n_raw + 1 < N) x[(size_t)(r0 + m) * N + n_raw + 1] += acc[1][m];
+        }
 }
 
 template <typename WT, class Stage>
 static void launch_residual_gemv(hipStream_t s, const void *W, const Stage &in, int R, int N, int K, float *x)
 {
-    launch_residual_gemv_np<WT, NP_GROUPS>(s, W, in, R, N, K, x);
+    const int gx = (N + 7) / 8;
+    if (R == 1) hipLaunchKernelGGL((residual_gemv_kernel<WT, 1, Stage>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    else if (R == 2) hipLaunchKernelGGL((residual_gemv_kernel<WT, 2, Stage>), dim3(gx, 1), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
+    else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4, Stage>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
 }
 
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x)
@@ -818,49 +770,34 @@ void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const fl
 
 // ------------------------------------------------------------------ FFN input: h = silu(Wg n) * (Wu n), n = RMSNorm(x; ln2)
 
-template <typename WT, int MB, int NP>
+template <typename WT, int MB>
 __global__ __launch_bounds__(256) void gateup_kernel(Dims D, const WT *wg, const WT *wu, const WT *gain, const float *x, int R, float *h)
 {
     __shared__ __attribute__((aligned(16))) float xs[DotsCfg<MB>::LDS_FLOATS];
-    const int f0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * NP;
-    const WT *wrow[NP][2];
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-        const int f = min(f0 + p, D.F - 1);
-        wrow[p][0] = wg + (size_t)f * D.d;
-        wrow[p][1] = wu + (size_t)f * D.d;
-    }
+    const int f_raw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int f = f_raw < D.F ? f_raw : D.F - 1;
+    const WT *const wrow[2] = {wg + (size_t)f * D.d, wu + (size_t)f * D.d};
     const int r0 = blockIdx.y * MB;
-    float acc[NP][2][MB], ss[MB];
-    wg_dots<WT, NP, 2, MB, true>(wrow, gain, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, R - r0, D.d, xs, acc, ss);
-    if ((threadIdx.x & 63) != 0) return;
+    float acc[2][MB], ss[MB];
+    wg_dots<WT, 2, MB, true>(wrow, gain, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, R - r0, D.d, xs, acc, ss);
+    if ((threadIdx.x & 63) != 0 || f_raw >= D.F) return;
 #pragma unroll
     for (int m = 0; m < MB; ++m)
         if (r0 + m < R) {
             const float rstd = 1.0f / sqrtf(ss[m] / (float)D.d + D.eps);
-#pragma unroll
-            for (int p = 0; p < NP; ++p)
-                if (f0 + p < D.F) {
-                    const float gt = acc[p][0][m] * rstd, up = acc[p][1][m] * rstd;
-                    h[(size_t)(r0 + m) * D.F + f0 + p] = gt / (1.0f + expf(-gt)) * up;
-                }
+            const float gt = acc[0][m] * rstd, up = acc[1][m] * rstd;
+            h[(size_t)(r0 + m) * D.F + f] = gt / (1.0f + expf(-gt)) * up;
         }
-}
-
-template <typename WT, int NP>
-static void launch_gateup_np(hipStream_t s, const Dims &D, const LayerW &w, const float *x, int R, float *h)
-{
-    const int gx = (D.F + 4 * NP - 1) / (4 * NP);
-    const WT *wg = (const WT *)w.wg, *wu = (const WT *)w.wu, *ln = (const WT *)w.ln2;
-    if (R == 1) hipLaunchKernelGGL((gateup_kernel<WT, 1, NP>), dim3(gx, 1), dim3(256), 0, s, D, wg, wu, ln, x, R, h);
-    else if (R == 2) hipLaunchKernelGGL((gateup_kernel<WT, 2, NP>), dim3(gx, 1), dim3(256), 0, s, D, wg, wu, ln, x, R, h);
-    else hipLaunchKernelGGL((gateup_kernel<WT, 4, NP>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, D, wg, wu, ln, x, R, h);
 }
 
 template <typename WT>
 static void launch_gateup_t(hipStream_t s, const Dims &D, const LayerW &w, const float *x, int R, float *h)
 {
-    launch_gateup_np<WT, NP_GROUPS>(s, D, w, x, R, h);
+    const int gx = (D.F + 3) / 4;
+    const WT *wg = (const WT *)w.wg, *wu = (const WT *)w.wu, *ln = (const WT *)w.ln2;
+    if (R == 1) hipLaunchKernelGGL((gateup_kernel<WT, 1>), dim3(gx, 1), dim3(256), 0, s, D, wg, wu, ln, x, R, h);
+    else if (R == 2) hipLaunchKernelGGL((gateup_kernel<WT, 2>), dim3(gx, 1), dim3(256), 0, s, D, wg, wu, ln, x, R, h);
+    else hipLaunchKernelGGL((gateup_kernel<WT, 4>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, D, wg, wu, ln, x, R, h);
 }
 
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h)

@@ -195,10 +195,10 @@ void launch_pack(hipStream_t s, const float *in, int M, int K, void *pack, int n
 
 // Merge of the per-chunk attention partials of one row (fixed order over chunks), written as fp32 rows and/or as
 // packed hi/lo activations for the output projection. One thread per 8 consecutive dims of a head.
-__global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos, RowsInline ri, int chunk, float *att, uint4 *pack, int ncb)
+__global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos, int chunk, float *att, uint4 *pack, int ncb)
 {
     const int r = blockIdx.x, ps = dh + 4;
-    const int p = ri.n ? ri.pos[r] : pos[r];
+    const int p = pos[r];
     const int live = min(nchunks, (p + chunk) / chunk);   // chunks that hold at least one key of this row
     for (int k8 = threadIdx.x; k8 < qw / 8; k8 += blockDim.x) {
         const int head = (k8 * 8) / dh, d0 = (k8 * 8) % dh;
@@ -246,14 +246,14 @@ __global__ void attn_merge_kernel2(int Hq, int dh, int qw, const float *part, in
 // The same merge for a few rows with many chunks: one workgroup per (row, head), the chunks spread over 16 thread
 // groups whose results are combined through LDS in a fixed order, so that no thread walks more than
 // ceil(nchunks / 16) chunks one after the other. Up to 64 chunks, dh <= 128.
-__global__ __launch_bounds__(256) void attn_merge_wide_kernel(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos, RowsInline ri,
+__global__ __launch_bounds__(256) void attn_merge_wide_kernel(int Hq, int dh, int qw, const float *part, int nchunks, const int *pos,
                                                               int chunk, float *att, uint4 *pack, int ncb)
 {
     __shared__ float s_m[64];
     __shared__ float s_l[16];
     __shared__ __attribute__((aligned(16))) float s_o[16][128];
     const int r = blockIdx.x, head = blockIdx.y, ps = dh + 4, tid = threadIdx.x;
-    const int p = ri.n ? ri.pos[r] : pos[r];
+    const int p = pos[r];
     const int live = min(nchunks, (p + chunk) / chunk);
     const float *pp = part + ((size_t)r * Hq + head) * nchunks * ps;
     if (tid < 64) s_m[tid] = tid < live ? pp[tid * ps + dh] : -INFINITY;
@@ -302,15 +302,15 @@ __global__ __launch_bounds__(256) void attn_merge_wide_kernel(int Hq, int dh, in
     }
 }
 
-void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, const RowsInline &ri, int chunk, float *att, void *pack, int ncb)
+void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb)
 {
     if (rows.n <= 8 && nchunks > 8 && nchunks <= 64 && D.dh <= 128) {
-        hipLaunchKernelGGL(attn_merge_wide_kernel, dim3(rows.n, D.Hq), dim3(256), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, ri, chunk, att,
+        hipLaunchKernelGGL(attn_merge_wide_kernel, dim3(rows.n, D.Hq), dim3(256), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, chunk, att,
                            (uint4 *)pack, ncb);
         return;
     }
     const int threads = D.qw / 8 >= 512 ? 512 : (D.qw / 8 + 63) / 64 * 64;
-    hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(threads), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, ri, chunk, att, (uint4 *)pack, ncb);
+    hipLaunchKernelGGL(attn_merge_kernel2, dim3(rows.n), dim3(threads), 0, s, D.Hq, D.dh, D.qw, part, nchunks, rows.pos, chunk, att, (uint4 *)pack, ncb);
 }
 
 // ------------------------------------------------------------------ grouped-query attention on the matrix cores
@@ -436,7 +436,7 @@ struct AttnWave {
 // One wavefront per (query row, chunk of the context), kv head along gridDim.y: partials for the merge, or the final
 // rows when there is a single chunk.
 template <int DH>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, RowsInline ri, int chunk,
+__global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, int chunk,
                                                         int nchunks, float *part, float *att)
 {
     constexpr int DB = DH / 32, PS = DH + 4;
@@ -444,9 +444,9 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     if (item >= rows.n * nchunks) return;
     const int r = __builtin_amdgcn_readfirstlane(item / nchunks), c = item % nchunks, g = blockIdx.y;   // one row per wavefront
     const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
-    const int ctx = (ri.n ? ri.pos[r] : rows.pos[r]) + 1;
+    const int ctx = rows.pos[r] + 1;
     const int j0 = c * chunk, j1 = min(ctx, j0 + chunk);
-    const int slot = ri.n ? ri.slot[r] : rows.slot[r];
+    const int slot = rows.slot[r];
     if (j0 >= ctx) return;   // no key of this row in the chunk: the merge never reads its partial
 
     AttnWave<DH> w;
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
 constexpr int ATT_ROW_WAVES = 8;
 
 template <int DH>
-__global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, RowsInline ri,
+__global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows,
                                                                       int span, float *part, int *cnt, float *att, uint4 *pack, int ncb)
 {
     constexpr int DB = DH / 32, NW = ATT_ROW_WAVES, GMAX = 8, PS = DH + 4;
@@ -495,8 +495,8 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
     __shared__ int s_last;
     const int r = blockIdx.x, g = blockIdx.y, pt = blockIdx.z, P = gridDim.z, wv = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
-    const int ctx = (ri.n ? ri.pos[r] : rows.pos[r]) + 1;
-    const int slot = ri.n ? ri.slot[r] : rows.slot[r];
+    const int ctx = rows.pos[r] + 1;
+    const int slot = rows.slot[r];
     const int parts = (ctx + span - 1) / span;        // parts this row is split into: as few as the longest part allows ...
     if (pt >= parts) return;                          // (uniform over the workgroup, before any barrier)
     const int len = 256 * ((ctx + 256 * parts - 1) / (256 * parts));   // ... and of equal length, so that they finish together
@@ -588,7 +588,7 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
     if (pack) store_packed(pack + (size_t)(r >> 6) * (D.qw / 16) * ncb * 64, ncb, r & 63, col >> 3, o);
 }
 
-void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, const RowsInline &ri, int max_ctx, float *part,
+void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
                            size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
@@ -603,10 +603,10 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
         const int P = (max_ctx + span - 1) / span;
         const dim3 grid(rows.n, D.Hkv, P);
         if (D.dh == 64)
-            hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, span, part,
+            hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, span, part,
                                cnt, pack ? nullptr : att, (uint4 *)pack, ncb);
         else
-            hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, span, part,
+            hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, span, part,
                                cnt, pack ? nullptr : att, (uint4 *)pack, ncb);
         return;
     }
@@ -621,14 +621,14 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
     const dim3 grid((rows.n * nchunks + 3) / 4, D.Hkv);
     float *direct = nchunks == 1 ? att : nullptr;
     if (D.dh == 64)
-        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, chunk, nchunks, part, direct);
+        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
     else
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, ri, chunk, nchunks, part, direct);
+        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
     if (nchunks > 1 && defer && !pack && rows.n <= 4 && nchunks <= 16) {   // the consumer merges
         defer->part = part; defer->pos = rows.pos; defer->nchunks = nchunks; defer->chunk = chunk;
         return;
     }
-    if (nchunks > 1) launch_attn_merge(s, D, part, nchunks, rows, ri, chunk, pack ? nullptr : att, pack, ncb);
+    if (nchunks > 1) launch_attn_merge(s, D, part, nchunks, rows, chunk, pack ? nullptr : att, pack, ncb);
     else if (pack) launch_pack(s, att, rows.n, D.qw, pack, ncb);
 }
 

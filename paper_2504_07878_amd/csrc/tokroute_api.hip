@@ -190,7 +190,7 @@ void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1, hipEvent_t *e2)
 
 // All layers over the rows currently described by the device row arrays. Returns the number of split-K partial
 // buffers of the last down projection that still have to be added to the residual stream (matrix-core path).
-int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, const RowsInline &ri)
+int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
 {
     const Dims &D = ctx->D;
     const Layout &L = ctx->lay;
@@ -203,7 +203,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, const RowsInline 
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
             launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
-            launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, ri, max_ctx, ctx->at<float>(L.attn_part),
+            launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
                              attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, &pend);
             launch_oproj(s, ctx->c.dtype, D, w.wo, att, pend, R, x);
             launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
@@ -222,7 +222,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, const RowsInline 
         launch_prep(s, p);
         launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
                         ctx->kc_layer(l), ctx->vc_layer(l));
-        launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, ri, max_ctx, ctx->at<float>(L.attn_part),
+        launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
                          attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
         launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
         p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
@@ -440,8 +440,7 @@ int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, c
         hipError_t e = hipMemcpyAsync(ctx->at<int>(L.tok), tokens_flat + offsets[i], (size_t)T * 4, hipMemcpyHostToDevice, s);
         if (e != hipSuccess) return fail_hip(ctx, e, "tr_prefill: token upload");
         launch_iota_rows(s, T, slot, ctx->at<int>(L.slot), ctx->at<int>(L.pos));
-        RowsInline none{};
-        const int pending = run_layers(ctx, s, T, T, none);
+        const int pending = run_layers(ctx, s, T, T);
         TailArgs t = tail_args(ctx, out, i, 1);
         t.gather = nullptr;
         t.slot = ctx->at<int>(L.slot);   // every row holds this slot
@@ -472,12 +471,7 @@ int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slot
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const Layout &L = ctx->lay;
     launch_setup_rows(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos));
-    RowsInline ri{};
-    if (n <= 64) {
-        ri.n = n;
-        for (int i = 0; i < n; ++i) { ri.slot[i] = slots[i]; ri.pos[i] = pos[(size_t)i]; }
-    }
-    const int pending = run_layers(ctx, s, n, max_ctx, ri);
+    const int pending = run_layers(ctx, s, n, max_ctx);
     TailArgs t = tail_args(ctx, out, 0, n);
     t.gather = nullptr;
     t.slot = ctx->at<int>(L.slot);

@@ -36,13 +36,6 @@ struct Rows {
     int n;
 };
 
-// Slot and position of up to 64 rows carried in the kernel arguments: kernels whose first action depends on them
-// (attention) save one dependent memory round trip. n == 0: use the device arrays.
-struct RowsInline {
-    int n;
-    int slot[64], pos[64];
-};
-
 // Attention partials that have not been merged yet: the consumer (the output projection of the GEMV path) merges them
 // while it stages its activations, which saves a kernel when only a few rows are in flight.
 struct AttnPending {
@@ -92,11 +85,11 @@ void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w,
                 float *q, void *kc, void *vc);
 // cnt: one zero-initialised int per (row, kv head), left at zero again by every launch (arrival counters of the
 // workgroups that share a row when its context is split)
-void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, const RowsInline &ri,
-                      int max_ctx, float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
-void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, const RowsInline &ri, int max_ctx, float *part,
+void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
+                      float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
+void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
                            size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
-void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, const RowsInline &ri, int chunk, float *att, void *pack, int ncb);
+void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb);
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x);
