@@ -525,3 +525,40 @@ int tro_decode_step(tro_ctx *cx, int32_t n, const int32_t *slots, const int32_t 
     free(x); free(nrm); free(q); free(a); free(o); free(g); free(u); free(logits_tmp);
     return TRO_OK;
 }
+
+/* ---------------------------------------------------------------- catch-up: T cached decode steps, the last one visible */
+
+int tro_extend(tro_ctx *cx, int32_t n, const int32_t *slots, const int32_t *tokens_flat, const int32_t *offsets, const tro_out *out)
+{
+    if (!cx || !slots || !tokens_flat || !offsets || !out) return TRO_ERR_INVALID_ARG;
+    if (!slots_ok(cx, n, slots)) return TRO_ERR_INVALID_ARG;
+    const tro_config *c = &cx->c;
+    if (offsets[0] != 0) return TRO_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i) {
+        int32_t T = offsets[i + 1] - offsets[i];
+        if (T < 1) return TRO_ERR_INVALID_ARG;
+        if (cx->len[slots[i]] < 0) return TRO_ERR_STATE;
+        if ((int64_t)cx->len[slots[i]] + T > c->max_seq) return TRO_ERR_CAPACITY;
+    }
+    if (!tokens_ok(c, tokens_flat, offsets[n])) return TRO_ERR_INVALID_ARG;
+    /* outputs of the steps that stay invisible go here */
+    int32_t tok_tmp, flag_tmp;
+    float conf_tmp, score_tmp;
+    tro_out hidden_steps = {&tok_tmp, &conf_tmp, &score_tmp, &flag_tmp, NULL, NULL};
+    for (int32_t i = 0; i < n; ++i) {
+        int32_t T = offsets[i + 1] - offsets[i], slot = slots[i];
+        const int32_t *tok = tokens_flat + offsets[i];
+        int64_t saved[2] = {cx->counters[2 * slot], cx->counters[2 * slot + 1]};
+        for (int32_t t = 0; t + 1 < T; ++t) {
+            int rc = tro_decode_step(cx, 1, &slot, tok + t, &hidden_steps);
+            if (rc != TRO_OK) return rc;
+        }
+        cx->counters[2 * slot] = saved[0];
+        cx->counters[2 * slot + 1] = saved[1];
+        tro_out last = {out->token + i, out->conf + i, out->score + i, out->flag + i,
+                        out->hidden ? out->hidden + (size_t)i * c->d_model : NULL, out->logits ? out->logits + (size_t)i * c->vocab : NULL};
+        int rc = tro_decode_step(cx, 1, &slot, tok + T - 1, &last);
+        if (rc != TRO_OK) return rc;
+    }
+    return TRO_OK;
+}

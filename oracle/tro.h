@@ -83,6 +83,12 @@ void tro_destroy(tro_ctx *);
 int tro_prefill(tro_ctx *, int32_t n, const int32_t *slots, const int32_t *tokens_flat, const int32_t *offsets, const tro_out *);
 /* One token per listed slot, attending over the slot's cache. */
 int tro_decode_step(tro_ctx *, int32_t n, const int32_t *slots, const int32_t *in_tokens, const tro_out *);
+/* Catch-up ("extend") step: each listed slot ingests the T >= 1 tokens of its segment, which some other model produced
+ * (Section 3.2, Figure 2: several rounds of prefill and decode inside one request; the prototype of Section 4.1 re-runs
+ * the whole prefix instead), at positions len .. len+T-1 over its existing cache. By definition this is T cached
+ * decode steps of which only the last one is visible: its outputs are returned and the counters move as for one
+ * decode step. Segments are given like prompts (tokens_flat, offsets[n+1]). */
+int tro_extend(tro_ctx *, int32_t n, const int32_t *slots, const int32_t *tokens_flat, const int32_t *offsets, const tro_out *);
 int tro_set_threshold(tro_ctx *, float);
 int tro_set_mode(tro_ctx *, int32_t);
 int tro_seq_len(const tro_ctx *, int32_t slot, int32_t *len);

@@ -68,6 +68,7 @@ def lib():
         L.tro_destroy.argtypes = [vp]; L.tro_destroy.restype = None
         L.tro_prefill.argtypes = [vp, i32, vp, vp, vp, C.POINTER(Out)]
         L.tro_decode_step.argtypes = [vp, i32, vp, vp, C.POINTER(Out)]
+        L.tro_extend.argtypes = [vp, i32, vp, vp, vp, C.POINTER(Out)]
         L.tro_set_threshold.argtypes = [vp, f32]
         L.tro_set_mode.argtypes = [vp, i32]
         L.tro_seq_len.argtypes = [vp, i32, C.POINTER(i32)]
@@ -240,6 +241,18 @@ class Model:
         rc = lib().tro_prefill(self._h, len(slots), _p(slots), _p(flat), _p(offs), C.byref(st))
         if rc:
             raise OracleError(rc, "tro_prefill")
+        return o
+
+    def extend(self, slots, segments, want_logits=False):
+        """segments: list of int sequences, one per slot, ingested over the slot's existing cache."""
+        slots = np.ascontiguousarray(slots, dtype=np.int32)
+        flat = np.ascontiguousarray(np.concatenate([np.asarray(p, dtype=np.int32) for p in segments]), dtype=np.int32)
+        offs = np.zeros(len(segments) + 1, np.int32); offs[1:] = np.cumsum([len(p) for p in segments])
+        o = self._out(len(slots), want_logits)
+        st = o.struct()
+        rc = lib().tro_extend(self._h, len(slots), _p(slots), _p(flat), _p(offs), C.byref(st))
+        if rc:
+            raise OracleError(rc, "tro_extend")
         return o
 
     def decode_step(self, slots, in_tokens, want_logits=False):

@@ -483,3 +483,49 @@ def test_load_kv_then_decode_equals_prefilled_cache(tro):
     m.load_kv(1, np.stack(ks), np.stack(vs))
     a, b = m.decode_step([0], [3], want_logits=True), m.decode_step([1], [3], want_logits=True)
     assert np.array_equal(a.logits, b.logits) and m.seq_len(1) == 7
+
+
+# ------------------------------------------------------------------ catch-up step (several rounds of prefill and decode, Section 3.2 / Figure 2)
+
+@pytest.mark.parametrize("kv_dtype", [synth.F32, synth.BF16])
+def test_extend_equals_brute_force_forward_of_the_whole_prefix(tro, kv_dtype):
+    """Ingesting a segment over an existing cache must give what the cache-free forward of prompt + segment gives at its
+    last position (the brute-force path shares no cache code with the catch-up step), for segments of 1 and of many tokens,
+    several slots in one call, twice in a row."""
+    s = small_shape(kv_dtype=kv_dtype)
+    m, _ = build(tro, s)
+    toks = synth.prompt_tokens(SEED, "ext", 40, s.vocab)
+    m.prefill([0, 1], [toks[:7], toks[:3]])
+    a = m.extend([1, 0], [toks[3:4], toks[7:21]], want_logits=True)          # 1 token for slot 1, 14 for slot 0
+    for row, T in ((0, 4), (1, 21)):
+        hid, lg = m.forward_all(toks[:T])
+        assert np.allclose(a.logits[row], lg[-1], rtol=1e-6, atol=1e-6) and np.allclose(a.hidden[row], hid[-1], rtol=1e-6, atol=1e-6)
+        assert a.token[row] == int(np.argmax(lg[-1]))
+    b = m.extend([0], [toks[21:40]], want_logits=True)
+    hid, lg = m.forward_all(toks)
+    assert np.allclose(b.logits[0], lg[-1], rtol=1e-6, atol=1e-6)
+    assert m.seq_len(0) == 40 and m.seq_len(1) == 4
+
+
+def test_extend_bookkeeping_and_errors(tro):
+    """The counters move as for ONE decode step whatever the segment length (only its last position emits a token); a
+    segment that does not fit, an empty one, or a slot without a cache are refused and leave everything as it was."""
+    s = small_shape()
+    m, _ = build(tro, s, max_batch=3, max_seq=16)
+    toks = synth.prompt_tokens(SEED, "extbk", 16, s.vocab)
+    m.prefill([0], [toks[:4]])
+    before = m.counters(0)
+    assert before[0] == 1
+    o = m.extend([0], [toks[4:9]])
+    assert m.counters(0) == (before[0] + 1, before[1] + int(o.flag[0])) and m.seq_len(0) == 9
+    with pytest.raises(tro.OracleError):
+        m.extend([0], [toks[:8]])           # 9 + 8 > 16
+    with pytest.raises(tro.OracleError):
+        m.extend([1], [toks[:2]])           # never prefilled
+    with pytest.raises(tro.OracleError):
+        m.extend([0], [[]])                 # empty segment
+    assert m.seq_len(0) == 9 and m.counters(0)[0] == 2
+    # set_mode(small_only) => the visible step does not route
+    m.set_mode(1)
+    o = m.extend([0], [toks[9:12]])
+    assert o.flag[0] == 0 and m.counters(0)[0] == 3
