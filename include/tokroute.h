@@ -115,6 +115,17 @@ int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, c
 int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens,
                    const tr_out *out);
 
+/* Catch-up ("extend") step: each listed slot ingests the T >= 1 tokens of its segment, which another model
+ * produced (Section 3.2, Figure 2: several rounds of prefill and decode inside one request; the prototype of
+ * Section 4.1 re-runs the whole prefix instead), at positions len .. len+T-1 over its existing cache, and
+ * returns the outputs of the last of them: the same result as T decode steps of which only the last is
+ * visible. The counters move as for one decode step. Segments are given like prompts: tokens_flat (HOST)
+ * holds them back to back, offsets (HOST, n+1 entries, offsets[0] = 0) delimit them; row i of out belongs to
+ * slots[i]. Errors (a slot without a cache, a segment that does not fit, an empty segment, a bad token) are
+ * detected before anything is enqueued and leave all state unchanged. */
+int tr_extend(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *tokens_flat,
+              const int32_t *offsets, const tr_out *out);
+
 /* The routing tail alone on n rows of residual stream x (DEVICE, fp32 [n][d_model]): final RMSNorm, LM
  * head, softmax confidence + argmax, router, flag. Touches no sequence state and no counters.
  * n <= max_batch. */

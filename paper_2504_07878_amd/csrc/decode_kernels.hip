@@ -254,18 +254,18 @@ void launch_setup_rows(hipStream_t s, int n, const int *slots, const int *toks, 
     }
 }
 
-__global__ void iota_rows_kernel(int n, int slot, int *d_slot, int *d_pos)
+__global__ void iota_rows_kernel(int n, int slot, int base, int *d_slot, int *d_pos)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) {
         d_slot[i] = slot;
-        d_pos[i] = i;
+        d_pos[i] = base + i;
     }
 }
 
-void launch_iota_rows(hipStream_t s, int n, int slot, int *d_slot, int *d_pos)
+void launch_iota_rows(hipStream_t s, int n, int slot, int base, int *d_slot, int *d_pos)
 {
-    hipLaunchKernelGGL(iota_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, slot, d_slot, d_pos);
+    hipLaunchKernelGGL(iota_rows_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, slot, base, d_slot, d_pos);
 }
 
 __global__ void reset_counters_kernel(long long *counters, int slot)

@@ -114,7 +114,8 @@ __global__ __launch_bounds__(128) void prep_kernel(PrepArgs p)
     float v[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = 0.f;
-    float *xr = p.x + (size_t)(p.row0 + m) * d;
+    const int row = p.gather ? p.gather[m] : p.row0 + m;
+    float *xr = p.x + (size_t)row * d;
     if (live) {
         const float4 a = *reinterpret_cast<const float4 *>(xr + k0), b = *reinterpret_cast<const float4 *>(xr + k0 + 4);
         v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(128) void prep_kernel(PrepArgs p)
             float4 c[8], e2[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const float *pr = p.part + ((size_t)min(s0 + u, p.nsplit - 1) * p.part_M + p.row0 + m) * d + k0;
+                const float *pr = p.part + ((size_t)min(s0 + u, p.nsplit - 1) * p.part_M + row) * d + k0;
                 c[u] = *reinterpret_cast<const float4 *>(pr); e2[u] = *reinterpret_cast<const float4 *>(pr + 4);
             }
 #pragma unroll

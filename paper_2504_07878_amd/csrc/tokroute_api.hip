@@ -19,7 +19,7 @@ size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {
     size_t k_layer_bytes, v_layer_bytes;
-    size_t kc, vc, rope, counters, slot, tok, pos, gather, x, q, att, h, hn, attn_part, tail_part, total;
+    size_t kc, vc, rope, counters, slot, tok, pos, gather, out_slot, x, q, att, h, hn, attn_part, tail_part, total;
     size_t attn_part_floats;
     size_t attn_cnt;
     int max_rows, nslices;
@@ -76,7 +76,7 @@ Layout make_layout(const tr_config *c)
     L.kc = take(L.k_layer_bytes * c->n_layers); L.vc = take(L.v_layer_bytes * c->n_layers);
     L.rope = take((size_t)c->max_seq * (c->head_dim / 2) * sizeof(float2));
     L.counters = take((size_t)c->max_batch * 2 * sizeof(long long));
-    L.slot = take(R * 4); L.tok = take(R * 4); L.pos = take(R * 4); L.gather = take((size_t)c->max_batch * 4);
+    L.slot = take(R * 4); L.tok = take(R * 4); L.pos = take(R * 4); L.gather = take((size_t)c->max_batch * 4); L.out_slot = take((size_t)c->max_batch * 4);
     L.x = take(R * c->d_model * 4); L.q = take(R * qw * 4); L.att = take(R * qw * 4); L.h = take(R * c->d_ffn * 4);
     L.hn = take((size_t)c->max_batch * c->d_model * 4);
     L.attn_part = take(L.attn_part_floats * 4);
@@ -247,7 +247,8 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
         return;
     }
     PrepArgs p{};
-    p.x = x; p.row0 = row0; p.part = ctx->at<float>(L.part); p.nsplit = pending; p.part_M = part_M; p.M = t.n; p.d = D.d; p.eps = D.eps;
+    p.x = x; p.row0 = row0; p.gather = t.gather; p.part = ctx->at<float>(L.part); p.nsplit = pending; p.part_M = part_M; p.M = t.n; p.d = D.d;
+    p.eps = D.eps;
     p.gain = (const bf16_t *)ctx->final_norm; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = mfma_ncb(t.n);
     p.hn = t.hn; p.hidden = t.hidden; p.hidden_tap = t.hidden_tap;
     launch_prep(s, p);
@@ -280,6 +281,49 @@ TailArgs tail_args(tr_ctx *ctx, const tr_out *out, int out_offset, int n)
 }
 
 }  // namespace
+
+// Segments of several slots through all layers in as few passes as the row buffers allow (whole segments per pass):
+// segment i is tokens_flat[offsets[i] .. offsets[i+1]) at positions base_i .. base_i+T_i-1, base_i = the slot's length
+// (from_len) or 0. Keys and values of all rows are appended before any row attends, each row over positions 0..its own;
+// the tail runs on the last row of every segment. counter_mode: 1 add, 2 set. Returns TR_OK or an error code.
+static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const int32_t *tokens_flat, const int32_t *offsets, bool from_len,
+                  const tr_out *out, int counter_mode, const char *who)
+{
+    const Layout &L = ctx->lay;
+    struct Pass { std::vector<int> slot, pos, gather, out_slot; };
+    std::vector<Pass> passes;   // kept until the end: the uploads below read them
+    passes.reserve((size_t)n);
+    int i = 0;
+    while (i < n) {
+        passes.emplace_back();
+        Pass &ps = passes.back();
+        int rows = 0, max_ctx = 0, j = i;
+        for (; j < n; ++j) {
+            const int T = offsets[j + 1] - offsets[j], base = from_len ? ctx->len[(size_t)slots[j]] : 0;
+            if (j > i && rows + T > L.max_rows) break;
+            for (int t = 0; t < T; ++t) { ps.slot.push_back(slots[j]); ps.pos.push_back(base + t); }
+            rows += T;
+            ps.gather.push_back(rows - 1);
+            ps.out_slot.push_back(slots[j]);
+            if (base + T > max_ctx) max_ctx = base + T;
+        }
+        // pageable sources: each copy has left the host array when the call returns
+        hipError_t e = hipMemcpyAsync(ctx->at<int>(L.tok), tokens_flat + offsets[i], (size_t)rows * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.slot), ps.slot.data(), (size_t)rows * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.pos), ps.pos.data(), (size_t)rows * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.gather), ps.gather.data(), (size_t)(j - i) * 4, hipMemcpyHostToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.out_slot), ps.out_slot.data(), (size_t)(j - i) * 4, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return fail_hip(ctx, e, who);
+        const int pending = run_layers(ctx, s, rows, max_ctx);
+        TailArgs t = tail_args(ctx, out, i, j - i);
+        t.gather = ctx->at<int>(L.gather);
+        t.slot = ctx->at<int>(L.out_slot);
+        t.counter_mode = counter_mode;
+        run_tail(ctx, s, t, ctx->at<float>(L.x), 0, pending, rows);
+        i = j;
+    }
+    return TR_OK;
+}
 
 extern "C" {
 
@@ -433,23 +477,37 @@ int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, c
         if (tokens_flat[i] < 0 || tokens_flat[i] >= ctx->c.vocab) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: token out of range");
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const Layout &L = ctx->lay;
-    for (int i = 0; i < n; ++i) {
-        const int T = offsets[i + 1] - offsets[i], slot = slots[i];
-        // pageable source: the copy has left the caller's array when this returns
-        hipError_t e = hipMemcpyAsync(ctx->at<int>(L.tok), tokens_flat + offsets[i], (size_t)T * 4, hipMemcpyHostToDevice, s);
-        if (e != hipSuccess) return fail_hip(ctx, e, "tr_prefill: token upload");
-        launch_iota_rows(s, T, slot, ctx->at<int>(L.slot), ctx->at<int>(L.pos));
-        const int pending = run_layers(ctx, s, T, T);
-        TailArgs t = tail_args(ctx, out, i, 1);
-        t.gather = nullptr;
-        t.slot = ctx->at<int>(L.slot);   // every row holds this slot
-        t.counter_mode = 2;
-        run_tail(ctx, s, t, ctx->at<float>(L.x), T - 1, pending, T);
-        ctx->len[(size_t)slot] = T;
-    }
+    const int rc = ingest(ctx, s, n, slots, tokens_flat, offsets, false, out, 2, "tr_prefill");
+    if (rc != TR_OK) return rc;
+    for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] = offsets[i + 1] - offsets[i];
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_prefill: launch");
+    return TR_OK;
+}
+
+int tr_extend(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *tokens_flat, const int32_t *offsets,
+              const tr_out *out)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (!slots || !tokens_flat || !offsets || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: null argument");
+    if (!slots_ok(ctx, n, slots)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: bad slot list");
+    if (offsets[0] != 0) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: offsets[0] must be 0");
+    for (int i = 0; i < n; ++i) {
+        const long long T = (long long)offsets[i + 1] - offsets[i];
+        const int len = ctx->len[(size_t)slots[i]];
+        if (T < 1) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: empty segment");
+        if (len < 0) return fail(ctx, TR_ERR_STATE, "tr_extend: slot was never prefilled");
+        if (len + T > ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_extend: segment does not fit the cache");
+    }
+    for (int i = 0; i < offsets[n]; ++i)
+        if (tokens_flat[i] < 0 || tokens_flat[i] >= ctx->c.vocab) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: token out of range");
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int rc = ingest(ctx, s, n, slots, tokens_flat, offsets, true, out, 1, "tr_extend");
+    if (rc != TR_OK) return rc;
+    for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] += offsets[i + 1] - offsets[i];
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_extend: launch");
     return TR_OK;
 }
 

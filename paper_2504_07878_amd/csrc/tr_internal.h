@@ -48,8 +48,9 @@ constexpr int MAX_SPLITS = 16;   // most split-K partial buffers a linear layer 
 
 // residual update + RMSNorm + pack (see mfma_kernels.hip)
 struct PrepArgs {
-    float *x;                // residual stream, row of output m is row0 + m
+    float *x;                // residual stream, row of output m is gather[m], or row0 + m without a gather list
     int row0;
+    const int *gather;
     const float *part;       // [nsplit][part_M][d] split-K partials to add first (rows indexed like x)
     int nsplit, part_M;
     int M, d;
@@ -79,7 +80,8 @@ struct TailArgs {
 
 // ---- launchers (enqueue only) ----
 void launch_setup_rows(hipStream_t s, int n, const int *slots, const int *toks, const int *poss, int *d_slot, int *d_tok, int *d_pos);
-void launch_iota_rows(hipStream_t s, int n, int slot, int *d_slot, int *d_pos);
+// rows 0..n-1 of one slot at positions base..base+n-1
+void launch_iota_rows(hipStream_t s, int n, int slot, int base, int *d_slot, int *d_pos);
 void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, int d, float *x);
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope,
                 float *q, void *kc, void *vc);

@@ -21,7 +21,7 @@ JOINT, SMALL_ONLY = 0, 1
 ROUTE_IF_BELOW, ROUTE_IF_ABOVE = 0, 1
 POST_FINAL_NORM, PRE_FINAL_NORM = 0, 1
 
-EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_tail", "tr_set_threshold",
+EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_extend", "tr_tail", "tr_set_threshold",
            "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable",
            "tr_profile_read", "tr_last_error"]
 
@@ -62,6 +62,7 @@ def load_library():
         L.tr_create.argtypes = [C.POINTER(tr_config), C.POINTER(tr_weights), vp, C.c_size_t, C.POINTER(vp)]
         L.tr_destroy.argtypes = [vp]; L.tr_destroy.restype = None
         L.tr_prefill.argtypes = [vp, vp, i32, vp, vp, vp, C.POINTER(tr_out)]
+        L.tr_extend.argtypes = [vp, vp, i32, vp, vp, vp, C.POINTER(tr_out)]
         L.tr_decode_step.argtypes = [vp, vp, i32, vp, vp, C.POINTER(tr_out)]
         L.tr_tail.argtypes = [vp, vp, i32, vp, C.POINTER(tr_out)]
         L.tr_set_threshold.argtypes = [vp, f32]
@@ -186,6 +187,15 @@ class Model:
         out = out or self.outputs(len(slots), want_logits)
         self._check(self.lib.tr_prefill(self._h, self._stream(), len(slots), slots.ctypes.data, flat.ctypes.data, offs.ctypes.data,
                                         C.byref(out.struct)), "tr_prefill")
+        return out
+
+    def extend(self, slots, segments, out: Outputs = None, want_logits=False):
+        slots = np.ascontiguousarray(slots, dtype=np.int32)
+        flat = np.ascontiguousarray(np.concatenate([np.asarray(p, dtype=np.int32) for p in segments]), dtype=np.int32)
+        offs = np.zeros(len(segments) + 1, np.int32); offs[1:] = np.cumsum([len(p) for p in segments])
+        out = out or self.outputs(len(slots), want_logits)
+        self._check(self.lib.tr_extend(self._h, self._stream(), len(slots), slots.ctypes.data, flat.ctypes.data, offs.ctypes.data,
+                                       C.byref(out.struct)), "tr_extend")
         return out
 
     def decode_step(self, slots, in_tokens, out: Outputs = None, want_logits=False):

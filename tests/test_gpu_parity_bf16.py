@@ -128,3 +128,26 @@ def test_isolated_tail_256_rows(tr, tro, weights, dev_weights):
     # without the debug logits buffer the decisions are the same, bit for bit
     g2 = g.tail(torch.from_numpy(x).cuda(), want_logits=False).cpu()
     assert np.array_equal(g2.token, go.token) and np.array_equal(g2.conf, go.conf) and np.array_equal(g2.score, go.score)
+
+
+def test_catch_up_steps_at_the_small_models_shapes(tr, tro, weights, dev_weights):
+    """tr_extend on the 0.5B-class model: three sequences with caches of 40, 300 and 700 tokens ingest segments of 14 (the
+    mean gap between routed tokens at 7 % routing), 3 and 40 tokens, then take one ordinary decode step."""
+    g = tr.Model(S.asdict(), dev_weights, 3, 800)
+    o = tro.Model(S.asdict(), weights, 3, 800)
+    lens = [40, 300, 700]
+    for b, n in enumerate(lens):
+        k, v = synth.kv_fill(SEED, f"cu05.{b}", S, n)
+        o.load_kv(b, synth.bf16_bits_to_f32(k), synth.bf16_bits_to_f32(v))
+        g.load_kv(b, tr.to_device(k, synth.BF16), tr.to_device(v, synth.BF16))
+    segs = [synth.prompt_tokens(SEED, f"cu05.s{b}", n, S.vocab) for b, n in enumerate((14, 3, 40))]
+    t = time.time()
+    go = g.extend([0, 1, 2], segs, want_logits=True).cpu()
+    oo = o.extend([0, 1, 2], segs, want_logits=True)
+    say(f"[extend: oracle {time.time() - t:.1f}s]")
+    ex = compare_outputs(go, oo, S.dtype, S.threshold, "0.5B extend")
+    go = g.decode_step([0, 1, 2], oo.token, want_logits=True).cpu()
+    oo = o.decode_step([0, 1, 2], oo.token, want_logits=True)
+    ex += compare_outputs(go, oo, S.dtype, S.threshold, "0.5B decode after extend")
+    assert ex <= 1
+    assert [g.seq_len(b) for b in range(3)] == [55, 304, 741]

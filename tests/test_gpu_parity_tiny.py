@@ -236,3 +236,47 @@ def test_small_bf16_model_long_contexts(tr, tro, B, ctx):
     assert g.seq_len(0) == max_seq
     with pytest.raises(tr.TokrouteError):
         g.decode_step([0], [1])            # the cache of slot 0 is full
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_catch_up_step_over_an_existing_cache(tr, tro, dtype):
+    """tr_extend against the oracle's definition (cached decode steps, only the last one visible): segments of 1, 5, 14
+    (the paper's ~7 % routing means about 14 small-model tokens between two routed ones), 40 and 130 tokens — up to 8 rows
+    run the GEMV kernels, more run the matrix-core ones — over caches of very different lengths, several slots per call,
+    alternating with ordinary decode steps; counters, lengths and error paths included."""
+    s = synth.TINY.with_(dtype=dtype, kv_dtype=dtype)
+    w = synth.make_weights(s, SEED + 5, std=0.05, bias_std=0.05, gain_std=0.1)
+    B, max_seq = 5, 700
+    g = tr.Model(s.asdict(), w, B, max_seq); o = tro.Model(s.asdict(), w, B, max_seq)
+    lens = [3, 64, 200, 511, 33]
+    prompts = [synth.prompt_tokens(SEED, f"cu.p{i}", n, s.vocab) for i, n in enumerate(lens)]
+    slots = list(range(B))
+    g.prefill(slots, prompts); o.prefill(slots, prompts)
+    ex = 0
+    for rnd, seg_lens in enumerate(([1, 5, 14, 40, 130], [14, 130, 1, 5, 40])):
+        segs = [synth.prompt_tokens(SEED, f"cu.s{rnd}.{i}", n, s.vocab) for i, n in enumerate(seg_lens)]
+        order = [4, 2, 0, 3, 1] if rnd else slots
+        go = g.extend(order, [segs[i] for i in order], want_logits=True).cpu()
+        oo = o.extend(order, [segs[i] for i in order], want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"extend round {rnd}")
+        go = g.decode_step(slots, oo.token[np.argsort(order)], want_logits=True).cpu()
+        oo = o.decode_step(slots, oo.token[np.argsort(order)], want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"decode after extend round {rnd}")
+    assert ex <= 1
+    cnt = g.counters()
+    total = [1 + 14, 5 + 130, 14 + 1, 40 + 5, 130 + 40]
+    for b in range(B):
+        assert g.seq_len(b) == o.seq_len(b) == lens[b] + total[b] + 2 and tuple(cnt[b]) == o.counters(b)
+        assert cnt[b][0] == 5                     # prefill + 2 x (extend + decode step)
+    room = max_seq - g.seq_len(3)
+    with pytest.raises(tr.TokrouteError):
+        g.extend([3], [synth.prompt_tokens(SEED, "cu.big", room + 1, s.vocab)])
+    with pytest.raises(tr.TokrouteError):
+        g.extend([0], [[]])
+    fresh = tr.Model(s.asdict(), w, 2, 16)
+    with pytest.raises(tr.TokrouteError):
+        fresh.extend([0], [[1, 2]])               # no cache yet
+    assert g.seq_len(3) == max_seq - room and g.seq_len(0) == lens[0] + total[0] + 2
+    go = g.extend([3], [synth.prompt_tokens(SEED, "cu.fill", room, s.vocab)], want_logits=True).cpu()      # exactly up to the last position
+    oo = o.extend([3], [synth.prompt_tokens(SEED, "cu.fill", room, s.vocab)], want_logits=True)
+    assert compare_outputs(go, oo, s.dtype, s.threshold, "extend to the end of the cache") == 0 and g.seq_len(3) == max_seq
