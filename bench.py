@@ -104,6 +104,53 @@ def counters_workload(s):
     log("counters workload done: 1 copy of 1 GiB, 5 tail calls at 64 rows")
 
 
+def joint_workload(s, new_tokens=32, B=64):
+    """Joint decoding of B sequences: 0.5B-class small model + router, 7B-class large model called on the flagged positions.
+
+    The router of a random-weight model knows nothing, so the threshold is set to the quantile of its scores that routes
+    about 7 % of the positions (the paper's operating point, abstract). The large model's weights are drawn on the GPU
+    (N(0, 0.02), seeded) because drawing 7.6 G values on the host takes minutes. Prints one JSON line of its own.
+    """
+    import numpy as np
+    import torch
+    from paper_2504_07878_amd import joint, synth, tokroute
+    L = synth.LLM_7B
+    max_seq = 128
+    weights = synth.make_weights(s, SEED, workers=8)
+    slm = tokroute.Model(s.asdict(), weights, B, max_seq)
+    torch.manual_seed(SEED)
+    one = synth.make_weights(L.with_(n_layers=1), SEED)
+    lw = {}
+    for k, v in one.items():
+        if k.startswith("l0."):
+            for l in range(L.n_layers):
+                lw[f"l{l}." + k[3:]] = (torch.randn(v.shape, device="cuda").mul_(0.02).to(torch.bfloat16) if v.ndim == 2 else tokroute.to_device(v, L.dtype))
+        else:
+            lw[k] = torch.randn(v.shape, device="cuda").mul_(0.02).to(torch.bfloat16) if v.ndim == 2 else tokroute.to_device(v, L.dtype)
+    llm = tokroute.Model(L.asdict(), lw, B, max_seq)
+    prompts = [synth.prompt_tokens(SEED, f"joint.p{b}", 32, s.vocab) for b in range(B)]
+    # scores of a plain small-model run fix the threshold
+    slm.set_mode(1)
+    out = slm.prefill(list(range(B)), prompts).cpu()
+    scores = [out.score.copy()]
+    for _ in range(8):
+        out = slm.decode_step(list(range(B)), out.token).cpu()
+        scores.append(out.score.copy())
+    tau = float(np.quantile(np.concatenate(scores), 0.07))
+    slm.set_mode(0); slm.set_threshold(tau)
+    joint.generate(slm, llm, prompts, 4)              # warm-up (every run starts with a prefill, which overwrites the caches)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    tokens, routed = joint.generate(slm, llm, prompts, new_tokens)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    print(json.dumps({"metric": "joint decoding tokens/s (0.5B-class small model + router, 7B-class large model on the routed positions)",
+                      "value": B * new_tokens / dt, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                      "config": {"workload": f"{B} sequences, 32-token prompts, {new_tokens} new tokens each, threshold at the 7 % quantile of the router scores",
+                                 "threshold": tau, "routed_fraction": float(routed.mean()), "seconds": dt,
+                                 "note": "prefill of both models is inside the timed region; the 7B-class shapes run the GEMV kernels for any row count"}}), flush=True)
+
+
 def measured_traffic():
     """HBM traffic of the LM-head kernel from hardware counters, valid only for the kernel source it was taken on."""
     import hashlib
@@ -123,9 +170,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="b64", choices=["b64", "counters"],
+    ap.add_argument("--workload", default="b64", choices=["b64", "counters", "joint"],
                     help="b64: the benchmark; counters: one 1 GiB device copy (calibration) and a few routing-tail calls at 64 rows, "
-                         "short enough for a hardware-counter pass of rocprofv3")
+                         "short enough for a hardware-counter pass of rocprofv3; joint: the two-model routing loop end to end")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -143,6 +190,9 @@ def main():
     s = synth.SLM_0P5B
     if args.workload == "counters":
         counters_workload(s)
+        return
+    if args.workload == "joint":
+        joint_workload(s)
         return
     t0 = time.perf_counter()
     weights = synth.make_weights(s, SEED, workers=8)
