@@ -176,6 +176,13 @@ float tro_router_score(const float *u, const void *w1, const void *b1, const voi
     return (float)(1.0 / (1.0 + exp(-acc)));
 }
 
+/* score = sigmoid( w . u + b ): a single linear head (Section 2.2's deferral probability has this shape) */
+float tro_linear_score(const float *u, const void *w, const void *b, int32_t dtype, int32_t d)
+{
+    double acc = (b ? (double)w_at(b, dtype, 0) : 0.0) + dot_row(w, dtype, 0, d, u);
+    return (float)(1.0 / (1.0 + exp(-acc)));
+}
+
 /* Section 3.1: route when the score falls below the threshold (strict); small_only disables routing.
  * TRO_ROUTE_IF_ABOVE is the opposite sense used by the deferral rule of Section 2.2. */
 int32_t tro_route_flag(float score, float threshold, int32_t route_dir, int32_t mode)
@@ -196,6 +203,7 @@ static int check_config(const tro_config *c)
     if (c->dtype != TRO_F32 && c->dtype != TRO_BF16) return TRO_ERR_INVALID_ARG;
     if (c->kv_dtype != TRO_F32 && c->kv_dtype != TRO_BF16) return TRO_ERR_INVALID_ARG;
     if (c->router_hidden < 0) return TRO_ERR_SHAPE;
+    if (c->route_policy < TRO_POLICY_MLP || c->route_policy > TRO_POLICY_LINEAR) return TRO_ERR_INVALID_ARG;
     return TRO_OK;
 }
 
@@ -214,7 +222,8 @@ int tro_create(const tro_config *c, const tro_weights *w, tro_ctx **out)
     if (rc) return rc;
     if (!w->tok_emb || !w->final_norm || (!c->tie_lm_head && !w->lm_head)) return TRO_ERR_INVALID_ARG;
     if (!w->ln1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->ln2 || !w->wg || !w->wu || !w->wd) return TRO_ERR_INVALID_ARG;
-    if (c->router_hidden > 0 && (!w->r_w1 || !w->r_w2)) return TRO_ERR_INVALID_ARG;
+    if (c->route_policy == TRO_POLICY_MLP && c->router_hidden > 0 && (!w->r_w1 || !w->r_w2)) return TRO_ERR_INVALID_ARG;
+    if (c->route_policy == TRO_POLICY_LINEAR && !w->r_w2) return TRO_ERR_INVALID_ARG;
     tro_ctx *x = (tro_ctx *)calloc(1, sizeof *x);
     x->c = *c;
     x->w = *w;
@@ -334,7 +343,13 @@ static void tail_row(const tro_ctx *cx, const float *x, const tro_out *out, int3
     const float *tap = c->hidden_tap == TRO_POST_FINAL_NORM ? hn : x;
     float score = 1.0f;
     int32_t flag = 0;
-    if (c->router_hidden > 0) {
+    if (c->route_policy == TRO_POLICY_CONFIDENCE) {
+        score = conf;
+        flag = tro_route_flag(score, cx->threshold, c->route_dir, cx->mode);
+    } else if (c->route_policy == TRO_POLICY_LINEAR) {
+        score = tro_linear_score(tap, cx->w.r_w2, cx->w.r_b2, c->dtype, d);
+        flag = tro_route_flag(score, cx->threshold, c->route_dir, cx->mode);
+    } else if (c->router_hidden > 0) {
         score = tro_router_score(tap, cx->w.r_w1, cx->w.r_b1, cx->w.r_w2, cx->w.r_b2, c->dtype, d, c->router_hidden);
         flag = tro_route_flag(score, cx->threshold, c->route_dir, cx->mode);
     }

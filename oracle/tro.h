@@ -40,6 +40,11 @@ enum { TRO_OK = 0, TRO_ERR_INVALID_ARG = -1, TRO_ERR_SHAPE = -2, TRO_ERR_CAPACIT
 enum { TRO_JOINT = 0, TRO_SMALL_ONLY = 1 };
 enum { TRO_ROUTE_IF_BELOW = 0, TRO_ROUTE_IF_ABOVE = 1 };
 enum { TRO_POST_FINAL_NORM = 0, TRO_PRE_FINAL_NORM = 1 };
+/* What the routing score is: the MLP router of Section 3.1 (default); the small model's own confidence, i.e. the
+ * maximum softmax probability (the "low confidence" of Figure 1 taken literally; no router weights);
+ * a single linear head with a sigmoid, the shape of a learned deferral probability compared with ">" (Section 2.2;
+ * the head's weights are r_w2 [d] and r_b2). The rule (below / above the threshold) stays route_dir. */
+enum { TRO_POLICY_MLP = 0, TRO_POLICY_CONFIDENCE = 1, TRO_POLICY_LINEAR = 2 };
 
 typedef struct tro_config {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -53,6 +58,7 @@ typedef struct tro_config {
     int32_t route_dir;
     int32_t hidden_tap;
     int32_t max_batch, max_seq;
+    int32_t route_policy;
 } tro_config;
 
 /* All pointers are HOST pointers, borrowed (must outlive the context), row-major [out][in]. */
@@ -113,6 +119,8 @@ void tro_attend(const float *q, const float *K, const float *V, int32_t ctx, int
 float tro_silu(float u);
 void tro_softmax_stats(const float *z, int32_t V, int32_t *argmax, float *max_prob);
 float tro_router_score(const float *u, const void *w1, const void *b1, const void *w2, const void *b2, int32_t dtype, int32_t d, int32_t rh);
+/* sigmoid(w . u + b) */
+float tro_linear_score(const float *u, const void *w, const void *b, int32_t dtype, int32_t d);
 int32_t tro_route_flag(float score, float threshold, int32_t route_dir, int32_t mode);
 float tro_bf16_to_f32(uint16_t);
 float tro_round_to_bf16(float); /* nearest-even, result widened back to fp32 */

@@ -20,6 +20,7 @@ F32, BF16 = 0, 1
 OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_STATE = 0, -1, -2, -3, -4
 JOINT, SMALL_ONLY = 0, 1
 ROUTE_IF_BELOW, ROUTE_IF_ABOVE = 0, 1
+POLICY_MLP, POLICY_CONFIDENCE, POLICY_LINEAR = 0, 1, 2
 POST_FINAL_NORM, PRE_FINAL_NORM = 0, 1
 
 
@@ -37,7 +38,7 @@ class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + [
         ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32), ("kv_dtype", C.c_int32),
         ("tie_lm_head", C.c_int32), ("router_hidden", C.c_int32), ("threshold", C.c_float), ("route_dir", C.c_int32),
-        ("hidden_tap", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+        ("hidden_tap", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("route_policy", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -84,6 +85,7 @@ def lib():
         L.tro_silu.argtypes = [f32]; L.tro_silu.restype = f32
         L.tro_softmax_stats.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(f32)]; L.tro_softmax_stats.restype = None
         L.tro_router_score.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32]; L.tro_router_score.restype = f32
+        L.tro_linear_score.argtypes = [vp, vp, vp, i32, i32]; L.tro_linear_score.restype = f32
         L.tro_route_flag.argtypes = [f32, f32, i32, i32]; L.tro_route_flag.restype = i32
         L.tro_bf16_to_f32.argtypes = [C.c_uint16]; L.tro_bf16_to_f32.restype = f32
         L.tro_round_to_bf16.argtypes = [f32]; L.tro_round_to_bf16.restype = f32
@@ -152,6 +154,11 @@ def router_score(u, w1, b1, w2, b2, dtype):
     return lib().tro_router_score(_p(u), _p(_check_w(w1, dtype)), _p(b1), _p(_check_w(w2, dtype)), _p(b2), dtype, d, rh)
 
 
+def linear_score(u, w, b, dtype):
+    u = np.ascontiguousarray(u, np.float32)
+    return lib().tro_linear_score(_p(u), _p(_check_w(w, dtype)), _p(b), dtype, u.size)
+
+
 def route_flag(score, threshold, route_dir=ROUTE_IF_BELOW, mode=JOINT):
     return lib().tro_route_flag(float(score), float(threshold), route_dir, mode)
 
@@ -188,12 +195,12 @@ class Model:
     """A tro context over borrowed numpy weights (dict of name -> array, per-layer names ``l{i}.wq`` ...)."""
 
     def __init__(self, shape: dict, weights: dict, max_batch: int, max_seq: int, route_dir=ROUTE_IF_BELOW,
-                 hidden_tap=POST_FINAL_NORM):
+                 hidden_tap=POST_FINAL_NORM, route_policy=POLICY_MLP):
         self.shape = dict(shape)
         s = self.shape
         self.cfg = Config(s["n_layers"], s["d_model"], s["n_q_heads"], s["n_kv_heads"], s["head_dim"], s["d_ffn"], s["vocab"],
                           s["rms_eps"], s["rope_theta"], s["dtype"], s["kv_dtype"], s["tie_lm_head"], s["router_hidden"],
-                          s["threshold"], route_dir, hidden_tap, max_batch, max_seq)
+                          s["threshold"], route_dir, hidden_tap, max_batch, max_seq, route_policy)
         self._keep = weights
         dt, L = s["dtype"], s["n_layers"]
 

@@ -529,3 +529,42 @@ def test_extend_bookkeeping_and_errors(tro):
     m.set_mode(1)
     o = m.extend([0], [toks[9:12]])
     assert o.flag[0] == 0 and m.counters(0)[0] == 3
+
+
+# ------------------------------------------------------------------ other routing scores (Figure 1 caption; Section 2.2)
+
+def test_confidence_policy_routes_on_the_maximum_softmax_probability(tro):
+    """Score = the small model's own confidence. With every matrix zero the logits are all equal, so the confidence is exactly
+    1/V whatever the input: routed iff 1/V < threshold. On a random model the score must be the max of torch's softmax."""
+    s = small_shape(router_hidden=0)
+    w = synth.make_weights(s, SEED, std=0.0)
+    for thr, want in ((1.0 / s.vocab + 1e-4, 1), (1.0 / s.vocab - 1e-4, 0)):
+        m = tro.Model(s.with_(threshold=thr).asdict(), w, 1, 8, route_policy=tro.POLICY_CONFIDENCE)
+        o = m.prefill([0], [[3, 1, 4]])
+        assert o.score[0] == pytest.approx(1.0 / s.vocab, rel=1e-6) and o.conf[0] == o.score[0] and o.flag[0] == want
+    m, _ = build(tro, s, route_policy=tro.POLICY_CONFIDENCE)
+    o = m.prefill([0], [synth.prompt_tokens(SEED, "confpol", 9, s.vocab)], want_logits=True)
+    p = torch.softmax(torch.from_numpy(o.logits[0]).double(), -1).max().item()
+    assert o.score[0] == pytest.approx(p, rel=1e-6) and o.flag[0] == int(o.score[0] < s.threshold)
+    m.set_mode(tro.SMALL_ONLY)
+    assert m.decode_step([0], [1]).flag[0] == 0
+
+
+def test_linear_deferral_head_closed_form(tro):
+    """Score = sigmoid(w.h + b) on the exposed hidden state, compared with '>' (the deferral rule of Section 2.2). A one-hot
+    w picks one coordinate of the returned hidden state; w = 0 gives sigmoid(b)."""
+    s = small_shape(router_hidden=0)
+    w = synth.make_weights(s, SEED, std=0.08, gain_std=0.1)
+    k, b = 5, -0.25
+    w["r_w2"] = np.zeros(s.d_model, np.float32); w["r_w2"][k] = 1.5
+    w["r_b2"] = np.array([b], np.float32)
+    m = tro.Model(s.asdict(), w, 1, 16, route_dir=tro.ROUTE_IF_ABOVE, route_policy=tro.POLICY_LINEAR)
+    o = m.prefill([0], [synth.prompt_tokens(SEED, "linpol", 7, s.vocab)])
+    want = 1.0 / (1.0 + math.exp(-(1.5 * float(o.hidden[0][k]) + b)))
+    assert o.score[0] == pytest.approx(want, rel=1e-6) and o.flag[0] == int(o.score[0] > s.threshold)
+    w["r_w2"] = np.zeros(s.d_model, np.float32)
+    m = tro.Model(s.asdict(), w, 1, 16, route_dir=tro.ROUTE_IF_ABOVE, route_policy=tro.POLICY_LINEAR)
+    assert m.prefill([0], [[2, 2]]).score[0] == pytest.approx(1.0 / (1.0 + math.exp(-b)), rel=1e-6)
+    u = synth.hidden_rows(SEED, "linpol.u", 1, s.d_model, False)[0]
+    ww = synth.normal(SEED, "linpol.w", (s.d_model,), 0.3, synth.F32)
+    assert tro.linear_score(u, ww, w["r_b2"], synth.F32) == pytest.approx(torch.sigmoid(torch.tensor(float(u.astype(np.float64) @ ww.astype(np.float64)) + b)).item(), rel=1e-6)
