@@ -40,6 +40,12 @@ enum { TR_F32 = 0, TR_BF16 = 1 };
 enum { TR_JOINT = 0, TR_SMALL_ONLY = 1 };                 /* inference modes of Section 3.1 */
 enum { TR_ROUTE_IF_BELOW = 0, TR_ROUTE_IF_ABOVE = 1 };    /* Section 3.1 rule | the deferral rule of Section 2.2 */
 enum { TR_POST_FINAL_NORM = 0, TR_PRE_FINAL_NORM = 1 };   /* which tensor is the "last-layer hidden state" */
+/* What the routing score is. TR_POLICY_MLP: the MLP router on the hidden state (Section 3.1). TR_POLICY_CONFIDENCE:
+ * the small model's own confidence, i.e. the maximum softmax probability (Figure 1: tokens of low confidence are
+ * routed); needs no router weights. TR_POLICY_LINEAR: sigmoid(r_w2 . hidden + r_b2) with r_w2 of length d_model, the
+ * shape of a learned deferral probability, normally used with TR_ROUTE_IF_ABOVE (Section 2.2). The comparison with
+ * the threshold is route_dir in every case. */
+enum { TR_POLICY_MLP = 0, TR_POLICY_CONFIDENCE = 1, TR_POLICY_LINEAR = 2 };
 
 typedef struct tr_ctx tr_ctx;
 
@@ -57,6 +63,7 @@ typedef struct tr_config {
     int32_t hidden_tap;    /* tensor returned as hidden state and fed to the router */
     int32_t max_batch;     /* number of sequence slots */
     int32_t max_seq;       /* cache capacity per slot, in tokens */
+    int32_t route_policy;  /* TR_POLICY_*; router_hidden is ignored unless TR_POLICY_MLP */
 } tr_config;
 
 /* DEVICE pointers, row-major [out][in], all in tr_config.dtype. BORROWED: they must stay valid and
@@ -69,7 +76,7 @@ typedef struct tr_weights {
     const void *final_norm; /* [d_model] */
     const void *const *ln1, *const *wq, *const *wk, *const *wv, *const *bq, *const *bk, *const *bv;
     const void *const *wo, *const *ln2, *const *wg, *const *wu, *const *wd;
-    const void *r_w1, *r_b1, *r_w2, *r_b2; /* router: [rh][d_model], [rh], [rh], [1] */
+    const void *r_w1, *r_b1, *r_w2, *r_b2; /* router: [rh][d_model], [rh], [rh], [1]; TR_POLICY_LINEAR: r_w2 is [d_model] */
 } tr_weights;
 
 /* Caller-owned DEVICE output buffers; row i belongs to the i-th sequence of the call.

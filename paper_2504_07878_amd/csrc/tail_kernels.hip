@@ -189,7 +189,16 @@ __global__ __launch_bounds__(64 * TF_WAVES) void tail_final_kernel(int d, int rh
     //    units at a time; its lanes split the columns, so every weight row is read as consecutive 16-byte pieces.
     float score = 1.0f;
     int flag = 0;
-    if (rh > 0) {
+    const bool mlp = t.policy == 0 && rh > 0, linear = t.policy == 2;
+    if (linear) {   // one linear head: the block's threads split the columns
+        const float *u = t.hidden_tap == 0 ? t.hn + (size_t)i * d : t.x + (size_t)(t.gather ? t.gather[i] : i) * d;
+        const WT *w = (const WT *)t.r_w2;
+        float a = 0.f;
+        for (int k = tid; k < d; k += 64 * TF_WAVES) a = fmaf(t_widen(w, k), u[k], a);
+        a = t_wave_sum(a);
+        if (lane == 0) s_ws[1][wave] = a;
+    }
+    if (mlp) {
         const float *u = t.hidden_tap == 0 ? t.hn + (size_t)i * d : t.x + (size_t)(t.gather ? t.gather[i] : i) * d;
         const WT *w1 = (const WT *)t.r_w1, *b1 = (const WT *)t.r_b1, *w2 = (const WT *)t.r_w2, *b2 = (const WT *)t.r_b2;
         for (int k = tid; k < d; k += 64 * TF_WAVES) s_u[k] = u[k];
@@ -228,13 +237,15 @@ __global__ __launch_bounds__(64 * TF_WAVES) void tail_final_kernel(int d, int rh
     float Ssum = 0.f;
     for (int w = 0; w < TF_WAVES; ++w) Ssum += s_ws[0][w];
     const float conf = 1.0f / Ssum;
-    if (rh > 0) {
+    if (mlp || linear) {
         float pre = 0.f;
         for (int w = 0; w < TF_WAVES; ++w) pre += s_ws[1][w];
         pre += t.r_b2 ? t_widen((const WT *)t.r_b2, 0) : 0.f;
         score = 1.0f / (1.0f + expf(-pre));
-        if (t.mode == 0) flag = t.route_dir == 0 ? (score < t.threshold) : (score > t.threshold);
+    } else if (t.policy == 1) {
+        score = conf;
     }
+    if ((mlp || linear || t.policy == 1) && t.mode == 0) flag = t.route_dir == 0 ? (score < t.threshold) : (score > t.threshold);
     t.token[i] = I; t.conf[i] = conf; t.score[i] = score; t.flag[i] = flag;
     if (t.counters && t.counter_mode) {
         long long *c = t.counters + 2 * (size_t)t.slot[i];

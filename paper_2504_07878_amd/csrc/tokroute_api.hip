@@ -53,6 +53,7 @@ int check_config(const tr_config *c)
     if (c->router_hidden < 0 || c->router_hidden > 1024 || (c->router_hidden > 0 && c->d_model > 4096)) return TR_ERR_SHAPE;
     if ((c->dtype != TR_F32 && c->dtype != TR_BF16) || (c->kv_dtype != TR_F32 && c->kv_dtype != TR_BF16)) return TR_ERR_INVALID_ARG;
     if (c->route_dir != TR_ROUTE_IF_BELOW && c->route_dir != TR_ROUTE_IF_ABOVE) return TR_ERR_INVALID_ARG;
+    if (c->route_policy < TR_POLICY_MLP || c->route_policy > TR_POLICY_LINEAR) return TR_ERR_INVALID_ARG;
     if (c->hidden_tap != TR_POST_FINAL_NORM && c->hidden_tap != TR_PRE_FINAL_NORM) return TR_ERR_INVALID_ARG;
     if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return TR_ERR_INVALID_ARG;
     if ((long long)c->max_batch * c->max_seq > (1ll << 31)) return TR_ERR_CAPACITY;
@@ -277,6 +278,7 @@ TailArgs tail_args(tr_ctx *ctx, const tr_out *out, int out_offset, int n)
     t.logits = out->logits ? out->logits + (size_t)out_offset * ctx->D.V : nullptr;
     t.counters = ctx->at<long long>(L.counters);
     t.threshold = ctx->threshold; t.route_dir = ctx->c.route_dir; t.mode = ctx->mode; t.hidden_tap = ctx->c.hidden_tap;
+    t.policy = ctx->c.route_policy;
     return t;
 }
 
@@ -341,7 +343,8 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     if ((uintptr_t)workspace % ALIGN) return TR_ERR_INVALID_ARG;
     if (!w->tok_emb || !w->final_norm || (!cfg->tie_lm_head && !w->lm_head)) return TR_ERR_INVALID_ARG;
     if (!w->ln1 || !w->wq || !w->wk || !w->wv || !w->wo || !w->ln2 || !w->wg || !w->wu || !w->wd) return TR_ERR_INVALID_ARG;
-    if (cfg->router_hidden > 0 && (!w->r_w1 || !w->r_w2)) return TR_ERR_INVALID_ARG;
+    if (cfg->route_policy == TR_POLICY_MLP && cfg->router_hidden > 0 && (!w->r_w1 || !w->r_w2)) return TR_ERR_INVALID_ARG;
+    if (cfg->route_policy == TR_POLICY_LINEAR && !w->r_w2) return TR_ERR_INVALID_ARG;
     Layout lay = make_layout(cfg);
     if (workspace_bytes < lay.total) return TR_ERR_CAPACITY;
 

@@ -76,6 +76,7 @@ struct TailArgs {
     long long *counters;     // [max_batch][2] or NULL
     int counter_mode;        // 0 none, 1 add (decode), 2 set (prefill)
     float threshold; int route_dir, mode, hidden_tap;
+    int policy;              // TR_POLICY_*
 };
 
 // ---- launchers (enqueue only) ----

@@ -19,6 +19,7 @@ OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_STATE, ERR_HIP = 0, -1, -2, -3
 F32, BF16 = 0, 1
 JOINT, SMALL_ONLY = 0, 1
 ROUTE_IF_BELOW, ROUTE_IF_ABOVE = 0, 1
+POLICY_MLP, POLICY_CONFIDENCE, POLICY_LINEAR = 0, 1, 2
 POST_FINAL_NORM, PRE_FINAL_NORM = 0, 1
 
 EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_extend", "tr_tail", "tr_set_threshold",
@@ -30,7 +31,7 @@ class tr_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + [
         ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32), ("kv_dtype", C.c_int32),
         ("tie_lm_head", C.c_int32), ("router_hidden", C.c_int32), ("threshold", C.c_float), ("route_dir", C.c_int32),
-        ("hidden_tap", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32)]
+        ("hidden_tap", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("route_policy", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -119,7 +120,7 @@ class Model:
     """A tr_ctx over device copies of numpy weights (dict name -> array; per-layer names ``l{i}.wq`` ...)."""
 
     def __init__(self, shape: dict, weights: dict, max_batch: int, max_seq: int, route_dir=ROUTE_IF_BELOW,
-                 hidden_tap=POST_FINAL_NORM, device="cuda:0"):
+                 hidden_tap=POST_FINAL_NORM, device="cuda:0", route_policy=POLICY_MLP):
         if not torch.cuda.is_available():
             raise RuntimeError("tokroute needs a GPU: no CPU path exists")
         self.lib = load_library()
@@ -127,7 +128,7 @@ class Model:
         s = self.shape = dict(shape)
         self.cfg = tr_config(s["n_layers"], s["d_model"], s["n_q_heads"], s["n_kv_heads"], s["head_dim"], s["d_ffn"], s["vocab"],
                              s["rms_eps"], s["rope_theta"], s["dtype"], s["kv_dtype"], s["tie_lm_head"], s["router_hidden"],
-                             s["threshold"], route_dir, hidden_tap, max_batch, max_seq)
+                             s["threshold"], route_dir, hidden_tap, max_batch, max_seq, route_policy)
         dt, L = s["dtype"], s["n_layers"]
         self.dev = {k: (v if isinstance(v, torch.Tensor) else to_device(v, dt, device)) for k, v in weights.items()}
         self._arrs = []

@@ -280,3 +280,36 @@ def test_catch_up_step_over_an_existing_cache(tr, tro, dtype):
     go = g.extend([3], [synth.prompt_tokens(SEED, "cu.fill", room, s.vocab)], want_logits=True).cpu()      # exactly up to the last position
     oo = o.extend([3], [synth.prompt_tokens(SEED, "cu.fill", room, s.vocab)], want_logits=True)
     assert compare_outputs(go, oo, s.dtype, s.threshold, "extend to the end of the cache") == 0 and g.seq_len(3) == max_seq
+
+
+@pytest.mark.parametrize("dtype,B", [(synth.F32, 3), (synth.BF16, 20)])
+def test_other_routing_scores(tr, tro, dtype, B):
+    """The softmax-confidence score (Figure 1) and the linear deferral head compared with '>' (Section 2.2) in the fused tail,
+    on the GEMV path (3 rows, fp32) and on the matrix-core path (20 rows, bf16), against the oracle."""
+    s = synth.TINY.with_(dtype=dtype, kv_dtype=dtype, router_hidden=0)
+    w = synth.make_weights(s, SEED + 6, std=0.05, bias_std=0.05, gain_std=0.1)
+    w["r_w2"] = synth.normal(SEED, "lin.w", (s.d_model,), 0.1, dtype)
+    w["r_b2"] = synth.normal(SEED, "lin.b", (1,), 0.1, dtype)
+    prompts = [synth.prompt_tokens(SEED, f"pol{b}", 3 + 5 * b, s.vocab) for b in range(B)]
+    slots = list(range(B))
+    # a threshold inside the range of the confidences the model actually produces, so that both outcomes occur
+    probe = tro.Model(s.asdict(), w, B, 128, route_policy=tro.POLICY_CONFIDENCE).prefill(slots, prompts)
+    conf_thr = float(np.median(probe.conf))
+    for policy, thr, below in ((tr.POLICY_CONFIDENCE, conf_thr, True), (tr.POLICY_LINEAR, 0.5, False)):
+        sh = s.with_(threshold=thr).asdict()
+        rd = tr.ROUTE_IF_BELOW if below else tr.ROUTE_IF_ABOVE
+        g = tr.Model(sh, w, B, 128, route_dir=rd, route_policy=policy)
+        o = tro.Model(sh, w, B, 128, route_dir=rd, route_policy=policy)
+        go = g.prefill(slots, prompts, want_logits=True).cpu(); oo = o.prefill(slots, prompts, want_logits=True)
+        ex = compare_outputs(go, oo, s.dtype, thr, f"policy {policy} prefill", route_dir_below=below)
+        flags = list(oo.flag)
+        for step in range(3):
+            go = g.decode_step(slots, oo.token, want_logits=True).cpu(); oo = o.decode_step(slots, oo.token, want_logits=True)
+            ex += compare_outputs(go, oo, s.dtype, thr, f"policy {policy} step {step}", route_dir_below=below)
+            flags += list(oo.flag)
+        assert ex <= 2 and 0 < sum(flags) < len(flags)
+        if policy == tr.POLICY_CONFIDENCE:
+            assert np.array_equal(go.score, go.conf)
+        cnt = g.counters()
+        for b in range(B):
+            assert tuple(cnt[b]) == o.counters(b)
