@@ -162,7 +162,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "bce7b44d5df577bd37ce23f7dd236f3f41e3e5ac69399e5d91f50bc2cb22d3c5", "fetch_bytes": 274399246, "write_bytes": 256000}
+LMHEAD_TRAFFIC = {"source_sha256": "dfbd16a59e2d2b3156275e91948d9fabfd0efccf997f2f813dcd140fbdf4cd2d", "fetch_bytes": 274409558, "write_bytes": 256000}
 
 
 def main():
