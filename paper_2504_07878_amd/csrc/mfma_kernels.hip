@@ -105,9 +105,9 @@ void launch_widen_bias(hipStream_t s, const void *b, int n, float *out)
 // x[m] += sum of the split-K partials of the previous linear layer (fixed order), then
 // n = x * g / rms(x) is written as packed hi/lo activations. One workgroup per row.
 
-__global__ __launch_bounds__(128) void prep_kernel(PrepArgs p)
+__global__ __launch_bounds__(512) void prep_kernel(PrepArgs p)   // d / 8 threads rounded up to whole wavefronts, d <= 4096
 {
-    __shared__ float red[2];
+    __shared__ float red[8];
     const int m = blockIdx.x, tid = threadIdx.x;
     const int d = p.d, k0 = tid * 8;
     const bool live = k0 < d;
@@ -146,8 +146,10 @@ __global__ __launch_bounds__(128) void prep_kernel(PrepArgs p)
     for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
-    const float rstd = 1.0f / sqrtf((red[0] + red[1]) / (float)d + p.eps);
-    if (!live) return;
+    if (!live || !p.pack) return;
+    float tot = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += red[w];
+    const float rstd = 1.0f / sqrtf(tot / (float)d + p.eps);
     const uint4 gbits = *reinterpret_cast<const uint4 *>(p.gain + k0);
     const uint32_t gw[4] = {gbits.x, gbits.y, gbits.z, gbits.w};
     float n[8];
@@ -172,7 +174,8 @@ __global__ __launch_bounds__(128) void prep_kernel(PrepArgs p)
 
 void launch_prep(hipStream_t s, const PrepArgs &p)
 {
-    hipLaunchKernelGGL(prep_kernel, dim3(p.M), dim3(128), 0, s, p);
+    const int threads = p.d / 8 <= 128 ? 128 : (p.d / 8 + 63) / 64 * 64;
+    hipLaunchKernelGGL(prep_kernel, dim3(p.M), dim3(threads), 0, s, p);
 }
 
 // fp32 rows -> packed hi/lo activations (attention output ahead of the output projection)
@@ -1031,6 +1034,82 @@ static void launch_gemm(hipStream_t s, const GemmArgs &a, int nsplit, const Epi 
 int mfma_ncb(int M) { return M <= 32 ? 2 : 4; }
 
 // split-K plan for the linear layers whose epilogue is a plain sum
+// ------------------------------------------------------------------ finishing kernels of the split-K path (wide models)
+
+// One workgroup per batch row; a thread takes the two features (j, j + dh/2) of a head that the rotation pairs up.
+template <typename KT>
+__global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *part, int nsplit, int M, const float *bias, Rows rows, const float2 *rope,
+                                                         float *q, KT *kc, KT *vc)
+{
+    const int m = blockIdx.x, half = D.dh / 2, N = D.qw + 2 * D.kvw, npairs = (D.Hq + 2 * D.Hkv) * half;
+    const int pos = rows.pos[m], slot = rows.slot[m];
+    for (int pr = threadIdx.x; pr < npairs; pr += blockDim.x) {
+        const int hh = pr / half, j = pr % half, n1 = hh * D.dh + j, n2 = n1 + half;
+        float y1 = bias[n1], y2 = bias[n2];
+        for (int sp = 0; sp < nsplit; ++sp) {   // fixed order
+            const float *src = part + ((size_t)sp * M + m) * N;
+            y1 += src[n1]; y2 += src[n2];
+        }
+        if (hh < D.Hq + D.Hkv) {
+            const float2 cs = rope[(size_t)pos * half + j];
+            const float o1 = y1 * cs.x - y2 * cs.y, o2 = y2 * cs.x + y1 * cs.y;
+            y1 = o1; y2 = o2;
+        }
+        if (hh < D.Hq) {
+            q[(size_t)m * D.qw + n1] = y1;
+            q[(size_t)m * D.qw + n2] = y2;
+        } else if (hh < D.Hq + D.Hkv) {
+            KT *dst = kc + (((size_t)slot * D.Hkv + (hh - D.Hq)) * D.max_seq + pos) * D.dh;
+            EpiQkv<KT>::store1(dst + j, y1);
+            EpiQkv<KT>::store1(dst + j + half, y2);
+        } else {
+            const int head = hh - D.Hq - D.Hkv;
+            EpiQkv<KT>::store1(vc + v_offset(D, slot, head, pos, j), y1);
+            EpiQkv<KT>::store1(vc + v_offset(D, slot, head, pos, j + half), y2);
+        }
+    }
+}
+
+// One workgroup per batch row; a thread takes 8 consecutive FFN features (gate columns (f/32)*64 + f%32, up columns 32 further).
+__global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, int nsplit, int M, int F, uint4 *hpack, int ncb)
+{
+    const int m = blockIdx.x;
+    const size_t N = 2 * (size_t)((F + 31) / 32) * 32;
+    for (int f8 = threadIdx.x; f8 < F / 8; f8 += blockDim.x) {
+        const int f = f8 * 8;
+        const size_t col = (size_t)(f / 32) * 64 + f % 32;
+        float g[8], u[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { g[e] = 0.f; u[e] = 0.f; }
+        for (int sp = 0; sp < nsplit; ++sp) {   // fixed order
+            const float *src = part + ((size_t)sp * M + m) * N + col;
+            const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
+            const float4 c = *reinterpret_cast<const float4 *>(src + 32), d4 = *reinterpret_cast<const float4 *>(src + 36);
+            g[0] += a.x; g[1] += a.y; g[2] += a.z; g[3] += a.w; g[4] += b.x; g[5] += b.y; g[6] += b.z; g[7] += b.w;
+            u[0] += c.x; u[1] += c.y; u[2] += c.z; u[3] += c.w; u[4] += d4.x; u[5] += d4.y; u[6] += d4.z; u[7] += d4.w;
+        }
+        float h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = g[e] * __frcp_rn(1.0f + __expf(-g[e])) * u[e];
+        store_packed(hpack + (size_t)(m >> 6) * (F / 16) * ncb * 64, ncb, m & 63, f8, h);
+    }
+}
+
+void launch_qkv_finish(hipStream_t s, int kdt, const Dims &D, const float *part, int nsplit, const float *bias, Rows rows, const float2 *rope, float *q,
+                       void *kc, void *vc)
+{
+    if (kdt == DT_F32)
+        hipLaunchKernelGGL(qkv_finish_kernel<float>, dim3(rows.n), dim3(256), 0, s, D, part, nsplit, rows.n, bias, rows, rope, q, (float *)kc, (float *)vc);
+    else
+        hipLaunchKernelGGL(qkv_finish_kernel<bf16_t>, dim3(rows.n), dim3(256), 0, s, D, part, nsplit, rows.n, bias, rows, rope, q, (bf16_t *)kc,
+                           (bf16_t *)vc);
+}
+
+void launch_swiglu_finish(hipStream_t s, const Dims &D, const float *part, int nsplit, int M, void *hpack)
+{
+    hipLaunchKernelGGL(swiglu_finish_kernel, dim3(M), dim3(256), 0, s, part, nsplit, M, D.F, (uint4 *)hpack, mfma_ncb(M));
+}
+
 void plan_partial(int KS, int n_tiles, int *nsplit, int *ksw, int *tiles_per_wg)
 {
     int S = (KS + NWAVES * MAXKW - 1) / (NWAVES * MAXKW);
@@ -1044,6 +1123,13 @@ void plan_partial(int KS, int n_tiles, int *nsplit, int *ksw, int *tiles_per_wg)
     *ksw = w;
     int tpw = (n_tiles * S + 255) / 256;
     *tiles_per_wg = tpw < 1 ? 1 : tpw;
+}
+
+int gemm_partial_splits(int K, int N)
+{
+    int S, ksw, tpw;
+    plan_partial(K / 16, (N + 31) / 32, &S, &ksw, &tpw);
+    return S;
 }
 
 void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out)

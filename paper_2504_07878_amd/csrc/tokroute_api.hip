@@ -4,6 +4,7 @@
 #include "../../include/tokroute.h"
 #include "tr_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -23,8 +24,10 @@ struct Layout {
     size_t attn_part_floats;
     size_t attn_cnt;
     int max_rows, nslices;
-    // matrix-core path: repacked weights, packed activations, split-K partials
-    bool mfma;
+    // matrix-core paths: repacked weights, packed activations, split-K partials.
+    // mfma: K of the layers with a non-linear epilogue fits one workgroup (d <= 896), those layers are fused GEMMs and the
+    // LM head runs on the matrix cores too. split: wider models, every layer through split-K partials plus finishing kernels.
+    bool mfma, split;
     size_t wt_layers, wt_layer_stride, wt_qkv, wt_o, wt_gu, wt_d, wt_head, bias, bias_stride;
     size_t pack_d, pack_a, pack_h, part;
 };
@@ -37,6 +40,12 @@ bool mfma_supported(const tr_config *c)
 {
     return c->dtype == TR_BF16 && c->d_model % 16 == 0 && c->d_model <= 896 && c->d_ffn % 16 == 0 && (c->n_q_heads * c->head_dim) % 32 == 0 &&
            (c->max_batch > GEMV_MAX_ROWS || c->max_seq > GEMV_MAX_ROWS);
+}
+
+bool split_supported(const tr_config *c)
+{
+    return c->dtype == TR_BF16 && c->d_model % 16 == 0 && c->d_model > 896 && c->d_model <= 4096 && c->d_ffn % 32 == 0 &&
+           (c->n_q_heads * c->head_dim) % 32 == 0 && (c->max_batch > GEMV_MAX_ROWS || c->max_seq > GEMV_MAX_ROWS);
 }
 
 size_t elem_size(int dt) { return dt == TR_F32 ? 4 : 2; }
@@ -83,9 +92,10 @@ Layout make_layout(const tr_config *c)
     L.attn_part = take(L.attn_part_floats * 4);
     L.attn_cnt = take(R * c->n_kv_heads * 4);
     L.mfma = mfma_supported(c);
+    L.split = split_supported(c);
     const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab) : 0;
     L.tail_part = take((size_t)(L.nslices > head_wgs ? L.nslices : head_wgs) * c->max_batch * sizeof(float4));
-    if (L.mfma) {
+    if (L.mfma || L.split) {
         const size_t d = (size_t)c->d_model, F = (size_t)c->d_ffn;
         auto tiles = [](size_t n) { return (n + 31) / 32; };
         const size_t tile_d = d / 16 * 1024, tile_q = qw / 16 * 1024, tile_f = F / 16 * 1024;   // bytes of one 32-row tile over K
@@ -96,14 +106,23 @@ Layout make_layout(const tr_config *c)
         L.wt_d = o2;   o2 += tiles(d) * tile_f;
         L.wt_layer_stride = align_up(o2);
         L.wt_layers = take(L.wt_layer_stride * c->n_layers);
-        L.wt_head = take(tiles((size_t)c->vocab) * tile_d);
+        L.wt_head = L.mfma ? take(tiles((size_t)c->vocab) * tile_d) : 0;
         L.bias_stride = align_up((qw + 2 * kvw) * 4);
         L.bias = take(L.bias_stride * c->n_layers);
         const size_t groups = (R + 63) / 64;
         L.pack_d = take(groups * (d / 16) * 4 * 1024);
         L.pack_a = take(groups * (qw / 16) * 4 * 1024);
         L.pack_h = take(groups * (F / 16) * 4 * 1024);
-        L.part = take((size_t)MAX_SPLITS * R * d * 4);
+        // widest set of partial buffers any layer produces: splits x output columns
+        size_t pcols = (size_t)MAX_SPLITS * d;
+        if (L.split) {
+            const size_t n_qkv = qw + 2 * kvw, n_gu = 2 * tiles(F) * 32;
+            pcols = (size_t)gemm_partial_splits((int)d, (int)n_qkv) * n_qkv;
+            pcols = std::max(pcols, (size_t)gemm_partial_splits((int)d, (int)n_gu) * n_gu);
+            pcols = std::max(pcols, (size_t)gemm_partial_splits((int)qw, (int)d) * d);
+            pcols = std::max(pcols, (size_t)gemm_partial_splits((int)F, (int)d) * d);
+        }
+        L.part = take(pcols * R * 4);
     }
     L.total = off;
     return L;
@@ -135,6 +154,7 @@ struct tr_ctx {
     char *wt(int l, size_t which) const { return ws + lay.wt_layers + (size_t)l * lay.wt_layer_stride + which; }
     float *bias(int l) const { return reinterpret_cast<float *>(ws + lay.bias + (size_t)l * lay.bias_stride); }
     bool use_mfma(int rows) const { return lay.mfma && rows > GEMV_MAX_ROWS; }
+    bool use_split(int rows) const { return lay.split && rows > GEMV_MAX_ROWS; }
 };
 
 namespace {
@@ -199,6 +219,30 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
     float *x = ctx->at<float>(L.x), *q = ctx->at<float>(L.q), *att = ctx->at<float>(L.att), *h = ctx->at<float>(L.h);
     const size_t attn_part_floats = R <= ctx->c.max_batch ? L.attn_part_floats : 0;
     launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
+    if (ctx->use_split(R)) {
+        // wide model: every linear layer leaves split-K partials; rotary/cache append and SwiGLU are finished by kernels of their own
+        const int ncb = mfma_ncb(R);
+        float *part = ctx->at<float>(L.part);
+        int pending = 0, ns = 0;
+        for (int l = 0; l < D.L; ++l) {
+            const LayerW &w = ctx->layers[(size_t)l];
+            PrepArgs p{};
+            p.x = x; p.row0 = 0; p.part = part; p.nsplit = pending; p.part_M = R; p.M = R; p.d = D.d; p.eps = D.eps;
+            p.gain = (const bf16_t *)w.ln1; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = ncb;
+            launch_prep(s, p);
+            launch_gemm_partial(s, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), D.d, D.qw + 2 * D.kvw, R, part, &ns);
+            launch_qkv_finish(s, ctx->c.kv_dtype, D, part, ns, ctx->bias(l), rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+            launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
+                             attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
+            launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
+            p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
+            launch_prep(s, p);
+            launch_gemm_partial(s, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), D.d, 2 * ((D.F + 31) / 32) * 32, R, part, &ns);
+            launch_swiglu_finish(s, D, part, ns, R, ctx->at<uint4>(L.pack_h));
+            launch_gemm_partial(s, ctx->wt(l, L.wt_d), ctx->at<uint4>(L.pack_h), D.F, D.d, R, part, &pending);
+        }
+        return pending;
+    }
     if (!ctx->use_mfma(R)) {
         AttnPending pend{};
         for (int l = 0; l < D.L; ++l) {
@@ -243,6 +287,12 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     hipEvent_t e0, e1, e2;
     next_events(ctx, &e0, &e1, &e2);
     if (!ctx->lay.mfma) {
+        if (pending > 0) {   // wide model: add the last down projection's partials to the rows the tail reads
+            PrepArgs p{};
+            p.x = x; p.row0 = row0; p.gather = t.gather; p.part = ctx->at<float>(L.part); p.nsplit = pending; p.part_M = part_M; p.M = t.n; p.d = D.d;
+            p.eps = D.eps;
+            launch_prep(s, p);
+        }
         t.x = x + (size_t)row0 * D.d;
         launch_tail(s, ctx->c.dtype, D, t, e0, e1, e2);
         return;
@@ -391,7 +441,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     // the attention kernels read whole 32-key blocks and mask afterwards: cache positions never written must hold finite values
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.kc, 0, lay.rope - lay.kc);
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.attn_cnt, 0, (size_t)lay.max_rows * cfg->n_kv_heads * 4);
-    if (e == hipSuccess && lay.mfma) {
+    if (e == hipSuccess && (lay.mfma || lay.split)) {
         // one-time repack of the bf16 matrices into matrix-core tiles; q|k|v are concatenated, gate/up interleaved
         for (int l = 0; l < D.L; ++l) {
             const LayerW &lw = ctx->layers[(size_t)l];
@@ -406,7 +456,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
             launch_widen_bias(nullptr, lw.bk, D.kvw, ctx->bias(l) + D.qw);
             launch_widen_bias(nullptr, lw.bv, D.kvw, ctx->bias(l) + D.qw + D.kvw);
         }
-        launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1);
+        if (lay.mfma) launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1);
         e = hipMemset(ctx->ws + lay.pack_d, 0, lay.part - lay.pack_d);   // padding rows of the packed activations stay zero
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess) e = hipGetLastError();

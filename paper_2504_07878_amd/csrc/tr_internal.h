@@ -44,7 +44,7 @@ struct AttnPending {
     int nchunks, chunk;  // nchunks == 0: nothing pending, the merged rows are in the fp32 buffer
 };
 
-constexpr int MAX_SPLITS = 16;   // most split-K partial buffers a linear layer may produce
+constexpr int MAX_SPLITS = 32;   // most split-K partial buffers a linear layer may produce
 
 // residual update + RMSNorm + pack (see mfma_kernels.hip)
 struct PrepArgs {
@@ -56,7 +56,7 @@ struct PrepArgs {
     int M, d;
     float eps;
     const bf16_t *gain;
-    uint4 *pack;             // packed hi/lo activations out
+    uint4 *pack;             // packed hi/lo activations out, or NULL: only the residual update is wanted
     int ncb;
     float *hn;               // optional fp32 copy of the normalised rows [M][d]
     float *hidden;           // optional exposed hidden state [M][d]
@@ -115,6 +115,15 @@ void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K,
 void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, const void *pack, const float *bias, Rows rows, const float2 *rope,
                      float *q, void *kc, void *vc);
 void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack);
+// Wide models (K beyond what one workgroup keeps resident): every linear layer goes through split-K partials, and the
+// layers with a non-linear epilogue are finished by a small kernel of their own.
+// number of partial buffers launch_gemm_partial will produce for a K x N layer
+int gemm_partial_splits(int K, int N);
+// [q|k|v] = sum of partials + bias, rotary embedding, q out, cache append
+void launch_qkv_finish(hipStream_t s, int kdt, const Dims &D, const float *part, int nsplit, const float *bias, Rows rows, const float2 *rope, float *q,
+                       void *kc, void *vc);
+// h = silu(gate) * up from the partials of the interleaved gate/up tiles, written as packed activations
+void launch_swiglu_finish(hipStream_t s, const Dims &D, const float *part, int nsplit, int M, void *hpack);
 int lmhead_mfma_wgs(int V);
 void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits);
 

@@ -313,3 +313,31 @@ def test_other_routing_scores(tr, tro, dtype, B):
         cnt = g.counters()
         for b in range(B):
             assert tuple(cnt[b]) == o.counters(b)
+
+
+@pytest.mark.parametrize("B", [12, 70])
+def test_wide_bf16_model_on_the_split_k_path(tr, tro, B):
+    """A model wider than one workgroup's share of K (d_model 1024 > 896, head dim 128): with more than 8 rows every linear
+    layer goes through split-K partials and the rotary/cache-append and SwiGLU steps are finished by their own kernels; the
+    tail stays on the streaming kernels. Ragged prefill, decode steps, a catch-up step, and the row counts in between."""
+    s = synth.TINY.with_(name="wide", d_model=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ffn=2048, dtype=synth.BF16, kv_dtype=synth.BF16)
+    w = synth.make_weights(s, SEED + 7, std=0.03, bias_std=0.05, gain_std=0.1)
+    max_seq = 260
+    g = tr.Model(s.asdict(), w, B, max_seq); o = tro.Model(s.asdict(), w, B, max_seq)
+    lens = synth.prompt_lengths(SEED, f"wide.lens{B}", B, 1, 150)
+    lens[0], lens[1], lens[2] = 1, 9, 150
+    prompts = [synth.prompt_tokens(SEED, f"wide{B}.{i}", int(n), s.vocab) for i, n in enumerate(lens)]
+    slots = list(np.random.default_rng(B).permutation(B))
+    go = g.prefill(slots, prompts, want_logits=True).cpu(); oo = o.prefill(slots, prompts, want_logits=True)
+    ex = compare_outputs(go, oo, s.dtype, s.threshold, f"wide B={B} prefill")
+    for step in range(3):
+        toks = oo.token.copy()
+        go = g.decode_step(slots, toks, want_logits=True).cpu(); oo = o.decode_step(slots, toks, want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"wide B={B} step {step}")
+    segs = [synth.prompt_tokens(SEED, f"wide{B}.seg{i}", 1 + (7 * i) % 40, s.vocab) for i in range(B)]
+    go = g.extend(slots, segs, want_logits=True).cpu(); oo = o.extend(slots, segs, want_logits=True)
+    ex += compare_outputs(go, oo, s.dtype, s.threshold, f"wide B={B} extend")
+    assert ex <= 2
+    cnt = g.counters()
+    for i, slot in enumerate(slots):
+        assert g.seq_len(slot) == lens[i] + 3 + len(segs[i]) and tuple(cnt[slot]) == o.counters(slot)
