@@ -1036,14 +1036,14 @@ int mfma_ncb(int M) { return M <= 32 ? 2 : 4; }
 // split-K plan for the linear layers whose epilogue is a plain sum
 // ------------------------------------------------------------------ finishing kernels of the split-K path (wide models)
 
-// One workgroup per batch row; a thread takes the two features (j, j + dh/2) of a head that the rotation pairs up.
+// Workgroups along x share a batch row (gridDim.y rows); a thread takes the two features (j, j + dh/2) of a head that the rotation pairs up.
 template <typename KT>
 __global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *part, int nsplit, int M, const float *bias, Rows rows, const float2 *rope,
                                                          float *q, KT *kc, KT *vc)
 {
-    const int m = blockIdx.x, half = D.dh / 2, N = D.qw + 2 * D.kvw, npairs = (D.Hq + 2 * D.Hkv) * half;
+    const int m = blockIdx.y, half = D.dh / 2, N = D.qw + 2 * D.kvw, npairs = (D.Hq + 2 * D.Hkv) * half;
     const int pos = rows.pos[m], slot = rows.slot[m];
-    for (int pr = threadIdx.x; pr < npairs; pr += blockDim.x) {
+    for (int pr = blockIdx.x * blockDim.x + threadIdx.x; pr < npairs; pr += gridDim.x * blockDim.x) {
         const int hh = pr / half, j = pr % half, n1 = hh * D.dh + j, n2 = n1 + half;
         float y1 = bias[n1], y2 = bias[n2];
         for (int sp = 0; sp < nsplit; ++sp) {   // fixed order
@@ -1070,12 +1070,13 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *pa
     }
 }
 
-// One workgroup per batch row; a thread takes 8 consecutive FFN features (gate columns (f/32)*64 + f%32, up columns 32 further).
+// Workgroups along x share a batch row (gridDim.y rows); a thread takes 8 consecutive FFN features (gate columns
+// (f/32)*64 + f%32, up columns 32 further).
 __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, int nsplit, int M, int F, uint4 *hpack, int ncb)
 {
-    const int m = blockIdx.x;
+    const int m = blockIdx.y;
     const size_t N = 2 * (size_t)((F + 31) / 32) * 32;
-    for (int f8 = threadIdx.x; f8 < F / 8; f8 += blockDim.x) {
+    for (int f8 = blockIdx.x * blockDim.x + threadIdx.x; f8 < F / 8; f8 += gridDim.x * blockDim.x) {
         const int f = f8 * 8;
         const size_t col = (size_t)(f / 32) * 64 + f % 32;
         float g[8], u[8];
@@ -1095,19 +1096,69 @@ __global__ __launch_bounds__(256) void swiglu_finish_kernel(const float *part, i
     }
 }
 
+// One workgroup per (vocabulary slice, batch row): thread t takes columns t*8 .. t*8+7 of the slice (8 columns x 256 threads).
+__global__ __launch_bounds__(256) void lmhead_finish_kernel(const float *part, int nsplit, int M, int V, float4 *slice_part, float *logits)
+{
+    __shared__ float s_m[256], s_s[256];
+    __shared__ int s_i[256];
+    const int m = blockIdx.y, v0 = blockIdx.x * LMHEAD_FINISH_COLS + threadIdx.x * 8, tid = threadIdx.x;
+    float mx = -INFINITY, sum = 0.f;
+    int idx = 0x7fffffff;
+    if (v0 < V) {   // V % 8 == 0
+        float z[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = 0.f;
+        for (int sp = 0; sp < nsplit; ++sp) {   // fixed order
+            const float *src = part + ((size_t)sp * M + m) * V + v0;
+            const float4 a = *reinterpret_cast<const float4 *>(src), b = *reinterpret_cast<const float4 *>(src + 4);
+            z[0] += a.x; z[1] += a.y; z[2] += a.z; z[3] += a.w; z[4] += b.x; z[5] += b.y; z[6] += b.z; z[7] += b.w;
+        }
+        if (logits) {
+            *reinterpret_cast<float4 *>(logits + (size_t)m * V + v0) = make_float4(z[0], z[1], z[2], z[3]);
+            *reinterpret_cast<float4 *>(logits + (size_t)m * V + v0 + 4) = make_float4(z[4], z[5], z[6], z[7]);
+        }
+#pragma unroll
+        for (int e = 7; e >= 0; --e)
+            if (z[e] >= mx) { mx = z[e]; idx = v0 + e; }   // descending scan: the lowest index wins ties
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum += __expf(z[e] - mx);
+    }
+    s_m[tid] = mx; s_i[tid] = idx; s_s[tid] = sum;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {   // fixed tree; value first, then the lower index
+        if (tid < o) {
+            const float m2 = s_m[tid + o], m1 = s_m[tid];
+            const int i2 = s_i[tid + o];
+            const float M2 = fmaxf(m1, m2);
+            const float a = m1 > -INFINITY ? s_s[tid] * __expf(m1 - M2) : 0.f, b = m2 > -INFINITY ? s_s[tid + o] * __expf(m2 - M2) : 0.f;
+            if (m2 > m1 || (m2 == m1 && i2 < s_i[tid])) s_i[tid] = i2;
+            s_m[tid] = M2; s_s[tid] = a + b;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) slice_part[(size_t)blockIdx.x * M + m] = make_float4(s_m[0], __int_as_float(s_i[0]), s_s[0], 0.f);
+}
+
+void launch_lmhead_finish(hipStream_t s, const float *part, int nsplit, int M, int V, float *slice_part, float *logits)
+{
+    hipLaunchKernelGGL(lmhead_finish_kernel, dim3((V + LMHEAD_FINISH_COLS - 1) / LMHEAD_FINISH_COLS, M), dim3(256), 0, s, part, nsplit, M, V,
+                       (float4 *)slice_part, logits);
+}
+
 void launch_qkv_finish(hipStream_t s, int kdt, const Dims &D, const float *part, int nsplit, const float *bias, Rows rows, const float2 *rope, float *q,
                        void *kc, void *vc)
 {
+    const int npairs = (D.Hq + 2 * D.Hkv) * (D.dh / 2);
+    const dim3 grid((npairs + 255) / 256, rows.n);
     if (kdt == DT_F32)
-        hipLaunchKernelGGL(qkv_finish_kernel<float>, dim3(rows.n), dim3(256), 0, s, D, part, nsplit, rows.n, bias, rows, rope, q, (float *)kc, (float *)vc);
+        hipLaunchKernelGGL(qkv_finish_kernel<float>, grid, dim3(256), 0, s, D, part, nsplit, rows.n, bias, rows, rope, q, (float *)kc, (float *)vc);
     else
-        hipLaunchKernelGGL(qkv_finish_kernel<bf16_t>, dim3(rows.n), dim3(256), 0, s, D, part, nsplit, rows.n, bias, rows, rope, q, (bf16_t *)kc,
-                           (bf16_t *)vc);
+        hipLaunchKernelGGL(qkv_finish_kernel<bf16_t>, grid, dim3(256), 0, s, D, part, nsplit, rows.n, bias, rows, rope, q, (bf16_t *)kc, (bf16_t *)vc);
 }
 
 void launch_swiglu_finish(hipStream_t s, const Dims &D, const float *part, int nsplit, int M, void *hpack)
 {
-    hipLaunchKernelGGL(swiglu_finish_kernel, dim3(M), dim3(256), 0, s, part, nsplit, M, D.F, (uint4 *)hpack, mfma_ncb(M));
+    hipLaunchKernelGGL(swiglu_finish_kernel, dim3((D.F / 8 + 255) / 256, M), dim3(256), 0, s, part, nsplit, M, D.F, (uint4 *)hpack, mfma_ncb(M));
 }
 
 void plan_partial(int KS, int n_tiles, int *nsplit, int *ksw, int *tiles_per_wg)

@@ -28,6 +28,7 @@ struct Layout {
     // mfma: K of the layers with a non-linear epilogue fits one workgroup (d <= 896), those layers are fused GEMMs and the
     // LM head runs on the matrix cores too. split: wider models, every layer through split-K partials plus finishing kernels.
     bool mfma, split;
+    bool split_head;   // wide model whose LM head runs through split-K partial logits (vocabulary a multiple of 8)
     size_t wt_layers, wt_layer_stride, wt_qkv, wt_o, wt_gu, wt_d, wt_head, bias, bias_stride;
     size_t pack_d, pack_a, pack_h, part;
 };
@@ -45,7 +46,7 @@ bool mfma_supported(const tr_config *c)
 bool split_supported(const tr_config *c)
 {
     return c->dtype == TR_BF16 && c->d_model % 16 == 0 && c->d_model > 896 && c->d_model <= 4096 && c->d_ffn % 32 == 0 &&
-           (c->n_q_heads * c->head_dim) % 32 == 0 && (c->max_batch > GEMV_MAX_ROWS || c->max_seq > GEMV_MAX_ROWS);
+           (c->n_q_heads * c->head_dim) % 32 == 0 && (c->max_batch > 4 || c->max_seq > 4);
 }
 
 size_t elem_size(int dt) { return dt == TR_F32 ? 4 : 2; }
@@ -106,7 +107,8 @@ Layout make_layout(const tr_config *c)
         L.wt_d = o2;   o2 += tiles(d) * tile_f;
         L.wt_layer_stride = align_up(o2);
         L.wt_layers = take(L.wt_layer_stride * c->n_layers);
-        L.wt_head = L.mfma ? take(tiles((size_t)c->vocab) * tile_d) : 0;
+        L.wt_head = (L.mfma || (L.split && c->vocab % 8 == 0)) ? take(tiles((size_t)c->vocab) * tile_d) : 0;
+        L.split_head = L.split && c->vocab % 8 == 0;
         L.bias_stride = align_up((qw + 2 * kvw) * 4);
         L.bias = take(L.bias_stride * c->n_layers);
         const size_t groups = (R + 63) / 64;
@@ -122,7 +124,10 @@ Layout make_layout(const tr_config *c)
             pcols = std::max(pcols, (size_t)gemm_partial_splits((int)qw, (int)d) * d);
             pcols = std::max(pcols, (size_t)gemm_partial_splits((int)F, (int)d) * d);
         }
-        L.part = take(pcols * R * 4);
+        size_t part_bytes = pcols * R * 4;
+        if (L.split_head)   // partial logits of a tail call: up to max_batch rows
+            part_bytes = std::max(part_bytes, (size_t)gemm_partial_splits((int)d, c->vocab) * c->vocab * c->max_batch * 4);
+        L.part = take(part_bytes);
     }
     L.total = off;
     return L;
@@ -154,7 +159,8 @@ struct tr_ctx {
     char *wt(int l, size_t which) const { return ws + lay.wt_layers + (size_t)l * lay.wt_layer_stride + which; }
     float *bias(int l) const { return reinterpret_cast<float *>(ws + lay.bias + (size_t)l * lay.bias_stride); }
     bool use_mfma(int rows) const { return lay.mfma && rows > GEMV_MAX_ROWS; }
-    bool use_split(int rows) const { return lay.split && rows > GEMV_MAX_ROWS; }
+    // wide models: the streaming kernels take 4 rows per pass over the weights, so the matrix cores win from 5 rows on
+    bool use_split(int rows) const { return lay.split && rows > 4; }
 };
 
 namespace {
@@ -286,6 +292,26 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     const Layout &L = ctx->lay;
     hipEvent_t e0, e1, e2;
     next_events(ctx, &e0, &e1, &e2);
+    if (ctx->lay.split_head && t.n > 4) {
+        // wide model, more rows than one pass of the streaming head takes: final norm + pack, the head as split-K partial
+        // logits on the matrix cores, softmax statistics per vocabulary slice from the partials
+        PrepArgs p{};
+        p.x = x; p.row0 = row0; p.gather = t.gather; p.part = ctx->at<float>(L.part); p.nsplit = pending; p.part_M = part_M; p.M = t.n; p.d = D.d;
+        p.eps = D.eps;
+        p.gain = (const bf16_t *)ctx->final_norm; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = mfma_ncb(t.n);
+        p.hn = t.hn; p.hidden = t.hidden; p.hidden_tap = t.hidden_tap;
+        launch_prep(s, p);
+        t.x = x + (size_t)row0 * D.d;
+        if (e0) (void)hipEventRecord(e0, s);
+        int ns = 0;
+        launch_gemm_partial(s, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), D.d, D.V, t.n, ctx->at<float>(L.part), &ns);
+        if (e1) (void)hipEventRecord(e1, s);
+        if (e2) (void)hipEventRecord(e2, s);
+        launch_lmhead_finish(s, ctx->at<float>(L.part), ns, t.n, D.V, t.part, t.logits);
+        t.nslices = (D.V + LMHEAD_FINISH_COLS - 1) / LMHEAD_FINISH_COLS;
+        launch_tail_final(s, ctx->c.dtype, D, t);
+        return;
+    }
     if (!ctx->lay.mfma) {
         if (pending > 0) {   // wide model: add the last down projection's partials to the rows the tail reads
             PrepArgs p{};
@@ -456,7 +482,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
             launch_widen_bias(nullptr, lw.bk, D.kvw, ctx->bias(l) + D.qw);
             launch_widen_bias(nullptr, lw.bv, D.kvw, ctx->bias(l) + D.qw + D.kvw);
         }
-        if (lay.mfma) launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1);
+        if (lay.mfma || lay.split_head) launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1);
         e = hipMemset(ctx->ws + lay.pack_d, 0, lay.part - lay.pack_d);   // padding rows of the packed activations stay zero
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess) e = hipGetLastError();

@@ -124,6 +124,10 @@ void launch_qkv_finish(hipStream_t s, int kdt, const Dims &D, const float *part,
                        void *kc, void *vc);
 // h = silu(gate) * up from the partials of the interleaved gate/up tiles, written as packed activations
 void launch_swiglu_finish(hipStream_t s, const Dims &D, const float *part, int nsplit, int M, void *hpack);
+// Softmax statistics of vocabulary slices of LMHEAD_FINISH_COLS columns from split-K partial logits [nsplit][M][V]:
+// writes slice_part[slice][m] = {max, lowest argmax, sum-exp} (what the tail's final kernel merges) and, when asked, the logits.
+constexpr int LMHEAD_FINISH_COLS = 2048;
+void launch_lmhead_finish(hipStream_t s, const float *part, int nsplit, int M, int V, float *slice_part, float *logits);
 int lmhead_mfma_wgs(int V);
 void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits);
 
