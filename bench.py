@@ -148,7 +148,7 @@ def joint_workload(s, new_tokens=32, B=64):
                       "value": B * new_tokens / dt, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
                       "config": {"workload": f"{B} sequences, 32-token prompts, {new_tokens} new tokens each, threshold at the 7 % quantile of the router scores",
                                  "threshold": tau, "routed_fraction": float(routed.mean()), "seconds": dt,
-                                 "note": "prefill of both models is inside the timed region; the 7B-class shapes run the GEMV kernels for any row count"}}), flush=True)
+                                 "note": "prefill of both models is inside the timed region"}}), flush=True)
 
 
 def measured_traffic():

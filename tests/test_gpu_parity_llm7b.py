@@ -54,7 +54,7 @@ def test_routed_subset_decode_on_7b_shapes(tro):
         go = g.decode_step(active, toks[step, active], want_logits=True).cpu()
         gpu_s += time.perf_counter() - t0; gpu_tokens += len(active)
         for b in active:
-            if b in watch and compared < 8:
+            if b in watch:                     # every activation of the followed slots, so that both sides hold the same caches
                 oo = o.decode_step([watch.index(b)], [toks[step, b]], want_logits=True)
                 i = active.index(b)
                 sub = type("O", (), dict(token=go.token[i:i + 1], conf=go.conf[i:i + 1], score=go.score[i:i + 1], flag=go.flag[i:i + 1],
@@ -67,3 +67,13 @@ def test_routed_subset_decode_on_7b_shapes(tro):
     for b in range(B):
         assert g.seq_len(b) == CTX + int(flags[:, b].sum())
     say(f"[7b: {gpu_tokens} routed tokens in {gpu_s * 1e3:.1f} ms of GPU steps (incl. logits copy) = {gpu_tokens / gpu_s:.0f} routed tok/s]")
+    # catch-up of 12 tokens on the two followed slots: more than 4 rows, i.e. the split-K matrix-core path of wide models
+    # (all linear layers through partials, rotary/cache append, SwiGLU and the head's softmax statistics finished separately)
+    segs = [synth.prompt_tokens(SEED, f"cfg5.seg{b}", 12, S.vocab) for b in watch]
+    t = time.time()
+    go = g.extend(watch, segs, want_logits=True).cpu()
+    oo = o.extend([0, 1], segs, want_logits=True)
+    say(f"[7b catch-up of 2 x 12 tokens: oracle {time.time() - t:.0f}s]")
+    assert compare_outputs(go, oo, S.dtype, 0.5, "7b extend") <= 1
+    for i, b in enumerate(watch):
+        assert g.seq_len(b) == o.seq_len(i)
