@@ -85,7 +85,7 @@ def cpu_baseline(s, weights, seconds_budget=20.0):
 
 
 def counters_workload(s):
-    """A plain copy kernel of known size, then the routing tail at 64 rows: the two things a --pmc pass compares."""
+    """A plain copy kernel of known size, then the routing tail at 64 rows (and at 256 rows, for the matrix-core counters)."""
     import torch
     from paper_2504_07878_amd import synth, tokroute
     src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
@@ -101,7 +101,13 @@ def counters_workload(s):
     for _ in range(5):
         m.tail(x, out)
     torch.cuda.synchronize()
-    log("counters workload done: 1 copy of 1 GiB, 5 tail calls at 64 rows")
+    m256 = tokroute.Model(one.asdict(), m.dev, 256, 8)
+    x256 = torch.from_numpy(synth.hidden_rows(SEED, "counters.x256", 256, s.d_model, False)).cuda()
+    out256 = m256.outputs(256)
+    for _ in range(3):
+        m256.tail(x256, out256)
+    torch.cuda.synchronize()
+    log("counters workload done: 1 copy of 1 GiB, 5 tail calls at 64 rows, 3 tail calls at 256 rows")
 
 
 def joint_workload(s, new_tokens=32, B=64):
@@ -162,7 +168,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "dfbd16a59e2d2b3156275e91948d9fabfd0efccf997f2f813dcd140fbdf4cd2d", "fetch_bytes": 274409558, "write_bytes": 256000}
+LMHEAD_TRAFFIC = {"source_sha256": "8eef4d15b54f2710942d62278e5dbfd144c8c53d0bdcc6c40c18d330181f1553", "fetch_bytes": 274384629, "write_bytes": 256000}
 
 
 def main():
