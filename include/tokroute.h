@@ -146,6 +146,11 @@ int tr_set_mode(tr_ctx *ctx, int32_t mode);
 int tr_seq_len(const tr_ctx *ctx, int32_t slot, int32_t *len);
 int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len);
 
+/* Copy a slot's whole state (cache up to its length, length, counters) into another slot, after which the two
+ * continue independently from the same prefix: a shared prompt, or a rollback point kept aside (the cache management
+ * for alternating stages that Section 3 asks for). Enqueues device-to-device copies on the stream. */
+int tr_seq_fork(tr_ctx *ctx, void *hip_stream, int32_t src_slot, int32_t dst_slot);
+
 /* Overwrite a slot's cache with len tokens of given keys/values (DEVICE pointers in kv_dtype, layout
  * [layer][kv_head][len][head_dim], keys already rotated) and set its length; counters are cleared. */
 int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, const void *k, const void *v);

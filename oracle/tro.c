@@ -276,6 +276,24 @@ int tro_seq_truncate(tro_ctx *x, int32_t slot, int32_t new_len)
     x->len[slot] = new_len;
     return TRO_OK;
 }
+int tro_seq_fork(tro_ctx *x, int32_t src, int32_t dst)
+{
+    if (!x || src < 0 || src >= x->c.max_batch || dst < 0 || dst >= x->c.max_batch || src == dst) return TRO_ERR_INVALID_ARG;
+    if (x->len[src] < 0) return TRO_ERR_STATE;
+    const tro_config *c = &x->c;
+    size_t kvw = (size_t)c->n_kv_heads * c->head_dim;
+    for (int32_t l = 0; l < c->n_layers; ++l)
+        for (int32_t p = 0; p < x->len[src]; ++p) {
+            size_t so = (((size_t)l * c->max_batch + src) * c->max_seq + p) * kvw, d_ = (((size_t)l * c->max_batch + dst) * c->max_seq + p) * kvw;
+            memcpy(x->kc + d_, x->kc + so, sizeof(float) * kvw);
+            memcpy(x->vc + d_, x->vc + so, sizeof(float) * kvw);
+        }
+    x->len[dst] = x->len[src];
+    x->counters[2 * dst] = x->counters[2 * src];
+    x->counters[2 * dst + 1] = x->counters[2 * src + 1];
+    return TRO_OK;
+}
+
 int tro_counters(const tro_ctx *x, int32_t slot, int64_t *counters)
 {
     if (!x || !counters || slot < 0 || slot >= x->c.max_batch) return TRO_ERR_INVALID_ARG;

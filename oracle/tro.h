@@ -99,6 +99,9 @@ int tro_set_threshold(tro_ctx *, float);
 int tro_set_mode(tro_ctx *, int32_t);
 int tro_seq_len(const tro_ctx *, int32_t slot, int32_t *len);
 int tro_seq_truncate(tro_ctx *, int32_t slot, int32_t new_len);
+/* Copy a slot's whole state (cache up to its length, length, counters) into another slot: both continue independently
+ * from the same prefix (one way of sharing a prompt between requests, or of keeping a rollback point). */
+int tro_seq_fork(tro_ctx *, int32_t src_slot, int32_t dst_slot);
 /* counters[2] = {n_generated, n_routed} of a slot */
 int tro_counters(const tro_ctx *, int32_t slot, int64_t *counters);
 /* Overwrite a slot's cache with given K/V ([layer][kv_head][len][head_dim], fp32) and set its length. */

@@ -70,6 +70,7 @@ def lib():
         L.tro_prefill.argtypes = [vp, i32, vp, vp, vp, C.POINTER(Out)]
         L.tro_decode_step.argtypes = [vp, i32, vp, vp, C.POINTER(Out)]
         L.tro_extend.argtypes = [vp, i32, vp, vp, vp, C.POINTER(Out)]
+        L.tro_seq_fork.argtypes = [vp, i32, i32]
         L.tro_set_threshold.argtypes = [vp, f32]
         L.tro_set_mode.argtypes = [vp, i32]
         L.tro_seq_len.argtypes = [vp, i32, C.POINTER(i32)]
@@ -280,6 +281,11 @@ class Model:
         if rc:
             raise OracleError(rc, "tro_forward_all")
         return hid, lg
+
+    def seq_fork(self, src, dst):
+        rc = lib().tro_seq_fork(self._h, int(src), int(dst))
+        if rc:
+            raise OracleError(rc, "tro_seq_fork")
 
     def set_threshold(self, t):
         rc = lib().tro_set_threshold(self._h, float(t))

@@ -880,7 +880,6 @@ template <int NCB, int KW, class Epi>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmArgs a, Epi epi_in)
 {
     constexpr int NCO = NCB / 2;
-    constexpr int P0 = KW >= 8 ? 1 : 0, P1 = KW >= 8 ? 5 : (KW > 1 ? 1 : 0), P2 = KW >= 8 ? 8 : KW - 1;   // k-steps after which the slices go
     __shared__ __attribute__((aligned(16))) float red[RED_FLOATS];
     Epi epi = epi_in;   // per-thread epilogue state lives in registers
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;

@@ -638,6 +638,29 @@ int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_o
     return TR_OK;
 }
 
+int tr_seq_fork(tr_ctx *ctx, void *hip_stream, int32_t src, int32_t dst)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (src < 0 || src >= ctx->c.max_batch || dst < 0 || dst >= ctx->c.max_batch || src == dst)
+        return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_fork: bad slot pair");
+    if (ctx->len[(size_t)src] < 0) return fail(ctx, TR_ERR_STATE, "tr_seq_fork: source slot was never filled");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const Layout &L = ctx->lay;
+    // a slot's keys (and values) of one layer are one contiguous block; whole blocks are copied, whatever the length
+    const size_t kb = L.k_layer_bytes / (size_t)ctx->c.max_batch, vb = L.v_layer_bytes / (size_t)ctx->c.max_batch;
+    for (int l = 0; l < ctx->D.L; ++l) {
+        char *k = static_cast<char *>(ctx->kc_layer(l)), *v = static_cast<char *>(ctx->vc_layer(l));
+        hipError_t e = hipMemcpyAsync(k + (size_t)dst * kb, k + (size_t)src * kb, kb, hipMemcpyDeviceToDevice, s);
+        if (e == hipSuccess) e = hipMemcpyAsync(v + (size_t)dst * vb, v + (size_t)src * vb, vb, hipMemcpyDeviceToDevice, s);
+        if (e != hipSuccess) return fail_hip(ctx, e, "tr_seq_fork: copy");
+    }
+    long long *cnt = ctx->at<long long>(L.counters);
+    hipError_t e = hipMemcpyAsync(cnt + 2 * (size_t)dst, cnt + 2 * (size_t)src, 2 * sizeof(long long), hipMemcpyDeviceToDevice, s);
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_seq_fork: copy");
+    ctx->len[(size_t)dst] = ctx->len[(size_t)src];
+    return TR_OK;
+}
+
 int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, const void *k, const void *v)
 {
     if (!ctx) return TR_ERR_INVALID_ARG;

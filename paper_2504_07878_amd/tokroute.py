@@ -23,7 +23,7 @@ POLICY_MLP, POLICY_CONFIDENCE, POLICY_LINEAR = 0, 1, 2
 POST_FINAL_NORM, PRE_FINAL_NORM = 0, 1
 
 EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_extend", "tr_tail", "tr_set_threshold",
-           "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable",
+           "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_fork", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable",
            "tr_profile_read", "tr_last_error"]
 
 
@@ -70,6 +70,7 @@ def load_library():
         L.tr_set_mode.argtypes = [vp, i32]
         L.tr_seq_len.argtypes = [vp, i32, C.POINTER(i32)]
         L.tr_seq_truncate.argtypes = [vp, i32, i32]
+        L.tr_seq_fork.argtypes = [vp, vp, i32, i32]
         L.tr_seq_load_kv.argtypes = [vp, vp, i32, i32, vp, vp]
         L.tr_counters_ptr.argtypes = [vp, C.POINTER(vp)]
         L.tr_profile_enable.argtypes = [vp, i32]
@@ -229,6 +230,9 @@ class Model:
 
     def seq_truncate(self, slot, new_len):
         self._check(self.lib.tr_seq_truncate(self._h, int(slot), int(new_len)), "tr_seq_truncate")
+
+    def seq_fork(self, src, dst):
+        self._check(self.lib.tr_seq_fork(self._h, self._stream(), int(src), int(dst)), "tr_seq_fork")
 
     def load_kv(self, slot, k: torch.Tensor, v: torch.Tensor):
         """k, v: device tensors [layer][kv_head][len][head_dim] in the cache storage type."""

@@ -341,3 +341,30 @@ def test_wide_bf16_model_on_the_split_k_path(tr, tro, B):
     cnt = g.counters()
     for i, slot in enumerate(slots):
         assert g.seq_len(slot) == lens[i] + 3 + len(segs[i]) and tuple(cnt[slot]) == o.counters(slot)
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_fork_of_a_sequence(tr, tro, dtype):
+    """tr_seq_fork against the oracle: the copy and the original continue independently and each matches the oracle's
+    corresponding slot, for the row-major fp32 cache and for the block-transposed bf16 V cache."""
+    s = synth.TINY.with_(dtype=dtype, kv_dtype=dtype)
+    w = synth.make_weights(s, SEED + 8, std=0.05, bias_std=0.05, gain_std=0.1)
+    g = tr.Model(s.asdict(), w, 3, 200); o = tro.Model(s.asdict(), w, 3, 200)
+    toks = synth.prompt_tokens(SEED, "fork", 140, s.vocab)
+    for m in (g, o):
+        m.prefill([0, 2], [toks[:77], toks[:5]])
+        m.seq_fork(0, 2)                              # replaces slot 2
+        m.seq_fork(0, 1)                              # fills an empty slot
+    assert [g.seq_len(b) for b in range(3)] == [77, 77, 77]
+    ex = 0
+    for step in range(3):
+        t3 = [toks[100 + step], toks[110 + step], toks[120 + step]]      # the three copies diverge
+        go = g.decode_step([0, 1, 2], t3, want_logits=True).cpu(); oo = o.decode_step([0, 1, 2], t3, want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"fork step {step}")
+    assert ex == 0
+    cnt = g.counters()
+    for b in range(3):
+        assert tuple(cnt[b]) == o.counters(b)
+    fresh = tr.Model(s.asdict(), w, 2, 16)
+    with pytest.raises(tr.TokrouteError):
+        fresh.seq_fork(0, 1)

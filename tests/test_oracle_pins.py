@@ -568,3 +568,28 @@ def test_linear_deferral_head_closed_form(tro):
     u = synth.hidden_rows(SEED, "linpol.u", 1, s.d_model, False)[0]
     ww = synth.normal(SEED, "linpol.w", (s.d_model,), 0.3, synth.F32)
     assert tro.linear_score(u, ww, w["r_b2"], synth.F32) == pytest.approx(torch.sigmoid(torch.tensor(float(u.astype(np.float64) @ ww.astype(np.float64)) + b)).item(), rel=1e-6)
+
+
+def test_fork_gives_two_independent_continuations_of_one_prefix(tro):
+    """After a fork both slots answer the same token identically (and like a slot prefilled with the same prompt); tokens fed
+    to one of them afterwards leave the other untouched; forking into a used slot replaces it; a never-filled source is refused."""
+    s = small_shape()
+    m, _ = build(tro, s, max_batch=3)
+    toks = synth.prompt_tokens(SEED, "fork", 12, s.vocab)
+    m.prefill([0], [toks[:9]])
+    m.prefill([1], [toks[:4]])                       # will be overwritten
+    m.seq_fork(0, 1)
+    assert m.seq_len(1) == 9 and m.counters(1) == m.counters(0)
+    a = m.decode_step([0, 1], [toks[9], toks[9]], want_logits=True)
+    assert np.array_equal(a.logits[0], a.logits[1]) and a.token[0] == a.token[1]
+    m.decode_step([1], [toks[10]])                    # only the copy moves on
+    b = m.decode_step([0], [toks[10]], want_logits=True)
+    m.prefill([2], [toks[:9]])
+    m.decode_step([2], [toks[9]])
+    c = m.decode_step([2], [toks[10]], want_logits=True)
+    assert np.array_equal(b.logits[0], c.logits[0]) and m.seq_len(0) == 11 and m.seq_len(1) == 11
+    fresh, _ = build(tro, s, max_batch=2)
+    with pytest.raises(tro.OracleError):
+        fresh.seq_fork(0, 1)
+    with pytest.raises(tro.OracleError):
+        m.seq_fork(1, 1)
