@@ -54,7 +54,11 @@ def time_decode(model, slots, tokens_per_step, steps, warmup, out):
     model.profile_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    room = min(model.cfg.max_seq - n for n in base)          # steps that fit before the longest sequence fills its cache
     for i in range(steps):
+        if i and i % room == 0:                          # more steps asked for than the cache holds: start over from the prompts (host bookkeeping only)
+            for sl, n in zip(slots, base):
+                model.seq_truncate(sl, n)
         model.decode_step(slots, tokens_per_step[i % len(tokens_per_step)], out)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
@@ -174,7 +178,7 @@ LMHEAD_TRAFFIC = {"source_sha256": "b921af43056ba0df9d01d62972a00469604513068612
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="b64", choices=["b64", "counters", "joint"],
                     help="b64: the benchmark; counters: one 1 GiB device copy (calibration) and a few routing-tail calls at 64 rows, "
@@ -205,7 +209,7 @@ def main():
     log(f"weights drawn in {time.perf_counter() - t0:.1f}s")
 
     B, MAX_SEQ = 64, 1536
-    steps = max(1, min(args.steps, 512))
+    steps = max(1, args.steps)
     model = tokroute.Model(s.asdict(), weights, B, MAX_SEQ)
     lens = synth.prompt_lengths(SEED, "cfg3.lens", B, 128, 1024)
     prompts = [synth.prompt_tokens(SEED, f"cfg3.prompt{b}", int(n), s.vocab) for b, n in enumerate(lens)]
@@ -224,13 +228,15 @@ def main():
     tok_s = B * steps / dt
     # algorithmic bytes of the timed steps: weights once per step, each sequence's cache once, new K/V written
     kvb = kv_bytes_per_token(s)
-    ctx_sum = sum(int(n) * steps + steps * (steps - 1) // 2 for n in base)      # sum over steps and sequences of cached tokens read
+    room = min(MAX_SEQ - int(n) for n in base)           # time_decode starts over from the prompts every `room` steps
+    ctx_sum = sum(int(n) + i % room for n in base for i in range(steps))        # sum over steps and sequences of cached tokens read
     step_bytes = weight_bytes_per_step(s) + (ctx_sum + B * steps) * kvb / steps
     roof_tok_s = B / (step_bytes / (HBM_PEAK_GBPS * 1e9))
     lm_bytes = 2 * s.vocab * s.d_model
     lm_avg_s = lm_ms / 1e3 / max(lm_n, 1)
     result = {
-        "metric": "SLM decode tokens/s at B=64 (0.5B-class bf16, routing tail included)", "value": tok_s, "unit": "tokens/s",
+        # the metric names three figures: value is the batch-64 one (the workload below); batch 1 and the isolated tail are in extras
+        "metric": "SLM decode tokens/s at B=1/64 + fused routing-tail GB/s, % of HBM roofline", "value": tok_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "0.5B-class bf16 decoder + router, 64 concurrent sequences, prompts U[128,1024], contiguous KV cache, "
@@ -249,7 +255,9 @@ def main():
         # catch-up step: every one of the 64 sequences ingests 14 tokens that another model produced (at ~7 % routing
         # about 14 small-model tokens lie between two routed ones); one call, the sequences one after the other
         seg = synth.prompt_tokens(SEED, "ext.seg", 14 * B, s.vocab).reshape(B, 14)
-        lens0 = [model.seq_len(sl) for sl in slots]
+        for sl, n in zip(slots, base):                   # back to the prompts: room for the segments
+            model.seq_truncate(sl, n)
+        lens0 = list(base)
         reps = 3
         t0 = 0.0
         for r in range(reps + 1):            # first round is the warm-up
