@@ -230,30 +230,6 @@ struct SetupArgs {
     int slot[256], tok[256], pos[256];
 };
 
-__global__ void setup_rows_kernel(SetupArgs a, int *d_slot, int *d_tok, int *d_pos, int base)
-{
-    int i = threadIdx.x;
-    if (i < a.n) {
-        d_slot[base + i] = a.slot[i];
-        d_tok[base + i] = a.tok[i];
-        d_pos[base + i] = a.pos[i];
-    }
-}
-
-void launch_setup_rows(hipStream_t s, int n, const int *slots, const int *toks, const int *poss, int *d_slot, int *d_tok, int *d_pos)
-{
-    for (int base = 0; base < n; base += 256) {
-        SetupArgs a;
-        a.n = n - base < 256 ? n - base : 256;
-        for (int i = 0; i < a.n; ++i) {
-            a.slot[i] = slots[base + i];
-            a.tok[i] = toks[base + i];
-            a.pos[i] = poss[base + i];
-        }
-        hipLaunchKernelGGL(setup_rows_kernel, dim3(1), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base);
-    }
-}
-
 __global__ void iota_rows_kernel(int n, int slot, int base, int *d_slot, int *d_pos)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -286,6 +262,38 @@ __global__ void embed_kernel(const WT *E, const int *tok, int d, float *x)
     const int r = blockIdx.x;
     const WT *e = E + (size_t)tok[r] * d;
     for (int j = threadIdx.x; j < d; j += blockDim.x) x[(size_t)r * d + j] = widen(e, j);
+}
+
+// Row metadata from the kernel arguments and the embedding lookup of the same rows in one launch (a decode step's first kernel)
+template <typename WT>
+__global__ void setup_embed_kernel(SetupArgs a, int *d_slot, int *d_tok, int *d_pos, int base, const WT *E, int d, float *x)
+{
+    const int i = blockIdx.x, r = base + i;
+    if (threadIdx.x == 0) {
+        d_slot[r] = a.slot[i];
+        d_tok[r] = a.tok[i];
+        d_pos[r] = a.pos[i];
+    }
+    const WT *e = E + (size_t)a.tok[i] * d;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) x[(size_t)r * d + j] = widen(e, j);
+}
+
+void launch_setup_rows_embed(hipStream_t s, int n, const int *slots, const int *toks, const int *poss, int *d_slot, int *d_tok, int *d_pos, int wdt,
+                             const void *E, int d, float *x)
+{
+    for (int base = 0; base < n; base += 256) {
+        SetupArgs a;
+        a.n = n - base < 256 ? n - base : 256;
+        for (int i = 0; i < a.n; ++i) {
+            a.slot[i] = slots[base + i];
+            a.tok[i] = toks[base + i];
+            a.pos[i] = poss[base + i];
+        }
+        if (wdt == DT_F32)
+            hipLaunchKernelGGL(setup_embed_kernel<float>, dim3(a.n), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base, (const float *)E, d, x);
+        else
+            hipLaunchKernelGGL(setup_embed_kernel<bf16_t>, dim3(a.n), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base, (const bf16_t *)E, d, x);
+    }
 }
 
 void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, int d, float *x)

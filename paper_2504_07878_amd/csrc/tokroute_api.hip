@@ -217,14 +217,14 @@ void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1, hipEvent_t *e2)
 
 // All layers over the rows currently described by the device row arrays. Returns the number of split-K partial
 // buffers of the last down projection that still have to be added to the residual stream (matrix-core path).
-int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx)
+int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true)
 {
     const Dims &D = ctx->D;
     const Layout &L = ctx->lay;
     Rows rows{ctx->at<int>(L.slot), ctx->at<int>(L.pos), ctx->at<int>(L.tok), R};
     float *x = ctx->at<float>(L.x), *q = ctx->at<float>(L.q), *att = ctx->at<float>(L.att), *h = ctx->at<float>(L.h);
     const size_t attn_part_floats = R <= ctx->c.max_batch ? L.attn_part_floats : 0;
-    launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
+    if (embed) launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
     if (ctx->use_split(R)) {
         // wide model: every linear layer leaves split-K partials; rotary/cache append and SwiGLU are finished by kernels of their own
         const int ncb = mfma_ncb(R);
@@ -607,8 +607,9 @@ int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slot
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const Layout &L = ctx->lay;
-    launch_setup_rows(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos));
-    const int pending = run_layers(ctx, s, n, max_ctx);
+    launch_setup_rows_embed(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos), ctx->c.dtype,
+                            ctx->tok_emb, ctx->D.d, ctx->at<float>(L.x));
+    const int pending = run_layers(ctx, s, n, max_ctx, false);
     TailArgs t = tail_args(ctx, out, 0, n);
     t.gather = nullptr;
     t.slot = ctx->at<int>(L.slot);
