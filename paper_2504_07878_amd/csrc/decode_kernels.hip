@@ -324,32 +324,41 @@ __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float 
     const int n1 = head * D.dh + j, n2 = n1 + half;
     const WT *const wrow[2] = {W + (size_t)n1 * D.d, W + (size_t)n2 * D.d};
     const int r0 = blockIdx.y * MB;
+    // what the epilogue needs from memory is requested now (position -> rotary pair is a chain of two dependent loads)
+    // and arrives while the weights stream
+    int pos[MB], slot[MB];
+    float2 cs[MB];
+    float b1 = 0.f, b2 = 0.f;
+    if (bias) { b1 = widen(bias, n1); b2 = widen(bias, n2); }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const int r = min(r0 + m, rows.n - 1);
+        pos[m] = rows.pos[r]; slot[m] = rows.slot[r];
+        cs[m] = rope[(size_t)pos[m] * half + j];
+    }
     float acc[2][MB], ss[MB];
     wg_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, rows.n - r0, D.d, xs, acc, ss);
     if ((threadIdx.x & 63) != 0 || pair_raw >= npairs) return;
-    const float b1 = bias ? widen(bias, n1) : 0.f, b2 = bias ? widen(bias, n2) : 0.f;
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
         const int r = r0 + m;
         if (r >= rows.n) break;
         const float rstd = 1.0f / sqrtf(ss[m] / (float)D.d + D.eps);
         float y1 = acc[0][m] * rstd + b1, y2 = acc[1][m] * rstd + b2;
-        const int pos = rows.pos[r];
         if (hh < D.Hq + D.Hkv) {
-            const float2 cs = rope[(size_t)pos * half + j];
-            const float o1 = y1 * cs.x - y2 * cs.y, o2 = y2 * cs.x + y1 * cs.y;
+            const float o1 = y1 * cs[m].x - y2 * cs[m].y, o2 = y2 * cs[m].x + y1 * cs[m].y;
             y1 = o1; y2 = o2;
         }
         if (hh < D.Hq) {
             q[(size_t)r * D.qw + n1] = y1;
             q[(size_t)r * D.qw + n2] = y2;
         } else if (hh < D.Hq + D.Hkv) {
-            KT *dst = kc + (((size_t)rows.slot[r] * D.Hkv + head) * D.max_seq + pos) * D.dh;
+            KT *dst = kc + (((size_t)slot[m] * D.Hkv + head) * D.max_seq + pos[m]) * D.dh;
             store_kv(dst + j, y1);
             store_kv(dst + j + half, y2);
         } else {
-            store_kv(vc + v_offset(D, rows.slot[r], head, pos, j), y1);
-            store_kv(vc + v_offset(D, rows.slot[r], head, pos, j + half), y2);
+            store_kv(vc + v_offset(D, slot[m], head, pos[m], j), y1);
+            store_kv(vc + v_offset(D, slot[m], head, pos[m], j + half), y2);
         }
     }
 }
@@ -734,6 +743,13 @@ __global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, Stage i
     const int n = n_raw < N ? n_raw : 0, n2 = n_raw + 1 < N ? n_raw + 1 : n;
     const WT *const wrow[2] = {W + (size_t)n * K, W + (size_t)n2 * K};
     const int r0 = blockIdx.y * MB;
+    // the old residual values are requested before the weights stream (each is owned by exactly one wavefront)
+    float xa[MB], xb[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const size_t row = (size_t)min(r0 + m, R - 1) * N;
+        xa[m] = x[row + n]; xb[m] = x[row + n2];
+    }
     float acc[2][MB], ss[MB];
     Stage src = in;
     src.advance(r0);
@@ -742,8 +758,8 @@ __global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, Stage i
 #pragma unroll
     for (int m = 0; m < MB; ++m)
         if (r0 + m < R) {
-            x[(size_t)(r0 + m) * N + n_raw] += acc[0][m];
-            if (n_raw + 1 < N) x[(size_t)(r0 + m) * N + n_raw + 1] += acc[1][m];
+            x[(size_t)(r0 + m) * N + n_raw] = xa[m] + acc[0][m];
+            if (n_raw + 1 < N) x[(size_t)(r0 + m) * N + n_raw + 1] = xb[m] + acc[1][m];
         }
 }
 
