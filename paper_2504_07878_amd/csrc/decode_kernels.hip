@@ -114,20 +114,36 @@ struct StageRows {
 struct StageAttn {
     AttnPending a;
     int Hq, dh, r0;
+    // up to 16 chunks (the launcher defers the merge only then); all requests of a phase are issued together, with
+    // indices clamped to the live chunks and weight 0 past them
     __device__ __forceinline__ float4 load(int m, int k) const
     {
         const int r = r0 + m, head = k / dh, d0 = k % dh, ps = dh + 4;
         const int live = min(a.nchunks, (a.pos[r] + a.chunk) / a.chunk);
         const float *pp = a.part + ((size_t)r * Hq + head) * a.nchunks * ps;
+        float mc[16], lc[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const float *pc = pp + min(c, live - 1) * ps + dh;
+            mc[c] = pc[0]; lc[c] = pc[1];
+        }
         float M = -INFINITY;
-        for (int c = 0; c < live; ++c) M = fmaxf(M, pp[c * ps + dh]);
+#pragma unroll
+        for (int c = 0; c < 16; ++c) M = fmaxf(M, mc[c]);   // clamped entries repeat a live chunk
         float L = 0.f;
         float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int c = 0; c < live; ++c) {
-            const float w = __expf(pp[c * ps + dh] - M);
-            const float4 v = *reinterpret_cast<const float4 *>(pp + c * ps + d0);
-            L = fmaf(pp[c * ps + dh + 1], w, L);
-            o.x = fmaf(v.x, w, o.x); o.y = fmaf(v.y, w, o.y); o.z = fmaf(v.z, w, o.z); o.w = fmaf(v.w, w, o.w);
+#pragma unroll
+        for (int c0 = 0; c0 < 16; c0 += 8) {
+            if (c0 >= live) break;
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const float4 *>(pp + min(c0 + u, live - 1) * ps + d0);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float w = c0 + u < live ? __expf(mc[c0 + u] - M) : 0.f;
+                L = fmaf(lc[c0 + u], w, L);
+                o.x = fmaf(v[u].x, w, o.x); o.y = fmaf(v[u].y, w, o.y); o.z = fmaf(v[u].z, w, o.z); o.w = fmaf(v[u].w, w, o.w);
+            }
         }
         const float inv = 1.0f / L;
         return make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
