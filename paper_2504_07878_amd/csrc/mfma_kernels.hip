@@ -565,18 +565,36 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
         __syncthreads();
         if (!s_last) return;
         if (worker) {
+            // four parts at a time, all their loads in flight together (indices clamped to the parts that exist, weight 0 past them)
             const float *pp = part + ((size_t)r * D.Hq + g * G + h) * P * PS;
-            M = -INFINITY;
-            for (int c = 0; c < parts; ++c) M = fmaxf(M, __hip_atomic_load(pp + c * PS + DH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-            L = 0.f;
+            M = -INFINITY; L = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = 0.f;
-            for (int c = 0; c < parts; ++c) {
-                const float *pc = pp + c * PS;
-                const float wgt = __expf(__hip_atomic_load(pc + DH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - M);
-                L = fmaf(__hip_atomic_load(pc + DH + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, L);
+            for (int c0 = 0; c0 < parts; c0 += 4) {
+                float mc[4], lc[4], v[4][8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = fmaf(__hip_atomic_load(pc + d0 + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, o[e]);
+                for (int u = 0; u < 4; ++u) {
+                    const float *pc = pp + min(c0 + u, parts - 1) * PS;
+                    mc[u] = __hip_atomic_load(pc + DH, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    lc[u] = __hip_atomic_load(pc + DH + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) v[u][e] = __hip_atomic_load(pc + d0 + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                float Mn = M;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) Mn = fmaxf(Mn, mc[u]);      // clamped entries repeat an existing part
+                const float corr = __expf(M - Mn);                      // 0 in the first round
+                L *= corr;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] *= corr;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float wgt = c0 + u < parts ? __expf(mc[u] - Mn) : 0.f;
+                    L = fmaf(lc[u], wgt, L);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = fmaf(v[u][e], wgt, o[e]);
+                }
+                M = Mn;
             }
         }
     }
@@ -1045,9 +1063,16 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *pa
     for (int pr = blockIdx.x * blockDim.x + threadIdx.x; pr < npairs; pr += gridDim.x * blockDim.x) {
         const int hh = pr / half, j = pr % half, n1 = hh * D.dh + j, n2 = n1 + half;
         float y1 = bias[n1], y2 = bias[n2];
-        for (int sp = 0; sp < nsplit; ++sp) {   // fixed order
-            const float *src = part + ((size_t)sp * M + m) * N;
-            y1 += src[n1]; y2 += src[n2];
+        for (int s0 = 0; s0 < nsplit; s0 += 4) {   // fixed order, four partials requested at a time
+            float a1[4], a2[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float *src = part + ((size_t)min(s0 + u, nsplit - 1) * M + m) * N;
+                a1[u] = src[n1]; a2[u] = src[n2];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (s0 + u < nsplit) { y1 += a1[u]; y2 += a2[u]; }
         }
         if (hh < D.Hq + D.Hkv) {
             const float2 cs = rope[(size_t)pos * half + j];
