@@ -65,14 +65,23 @@ __device__ __forceinline__ void store_packed(uint4 *pack, int ncb, int row_in_gr
 
 // ------------------------------------------------------------------ one-time weight repack
 
-__global__ void repack_kernel(const bf16_t *W, int N, int K, uint4 *Wt, int KS, int dst_tile0, int dst_tile_stride, int n_tiles)
+// pair_dh > 0 (q, k, v matrices, pair_dh = head dim): the rows of a head are reordered so that tile row 2p holds dim
+// 16*sub + p and tile row 2p + 1 its rotary partner dim 16*sub + p + pair_dh/2 (sub = tile index inside the head): the
+// two features a rotation pairs up then sit next to each other in one thread of the GEMM epilogue.
+__device__ __forceinline__ int paired_row(int t, int i, int pair_dh)
+{
+    const int tph = pair_dh >> 5, head = t / tph, sub = t % tph;
+    return head * pair_dh + sub * 16 + (i >> 1) + (i & 1) * (pair_dh >> 1);
+}
+
+__global__ void repack_kernel(const bf16_t *W, int N, int K, uint4 *Wt, int KS, int dst_tile0, int dst_tile_stride, int n_tiles, int pair_dh)
 {
     const size_t total = (size_t)n_tiles * KS * 64;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int lane = (int)(i & 63);
         const size_t rest = i >> 6;
         const int ks = (int)(rest % KS), t = (int)(rest / KS);
-        const int row = t * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
+        const int row = pair_dh ? paired_row(t, lane & 31, pair_dh) : t * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
         uint32_t h[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) h[e] = (row < N && k + e < K) ? W[(size_t)row * K + k + e] : 0;
@@ -81,13 +90,13 @@ __global__ void repack_kernel(const bf16_t *W, int N, int K, uint4 *Wt, int KS, 
     }
 }
 
-void launch_repack(hipStream_t s, const void *W, int N, int K, void *Wt, int dst_tile0, int dst_tile_stride)
+void launch_repack(hipStream_t s, const void *W, int N, int K, void *Wt, int dst_tile0, int dst_tile_stride, int pair_dh)
 {
     const int KS = (K + 15) / 16, n_tiles = (N + 31) / 32;
     const size_t total = (size_t)n_tiles * KS * 64;
     int blocks = (int)((total + 255) / 256);
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(repack_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t *)W, N, K, (uint4 *)Wt, KS, dst_tile0, dst_tile_stride, n_tiles);
+    hipLaunchKernelGGL(repack_kernel, dim3(blocks), dim3(256), 0, s, (const bf16_t *)W, N, K, (uint4 *)Wt, KS, dst_tile0, dst_tile_stride, n_tiles, pair_dh);
 }
 
 __global__ void widen_bias_kernel(const bf16_t *b, int n, float *out)
@@ -690,99 +699,68 @@ struct EpiPartial {   // split-K partial sums: part[split][m][n]
 };
 
 template <typename KT>
-struct EpiQkv {       // bias, rotary embedding, q out, cache append
+struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold rotary pairs next to each other (see repack_kernel)
     static constexpr bool half_only = true;   // launched with GemmArgs::half = 1: 32-row workgroups only
-    const float *bias;        // concatenated [qw + 2 kvw]
+    const float *bias;        // concatenated [qw + 2 kvw], natural feature order
     const float2 *rope;
     const int *slot, *pos;
     float *q;
     KT *kc, *vc;
     int M, Hq, Hkv, dh, max_seq, qw, vts;
-    float hold0[8], hold1[8];   // first rotary half of the head, kept until its partner tile arrives (two arrays with
-                                // constant indices: a runtime index would move the whole functor out of registers)
     int rpos, rslot;          // position and slot of this thread's batch row, fetched ahead of the weight stream
     __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void row(int m) { rpos = pos[min(m, M - 1)]; rslot = slot[min(m, M - 1)]; }
+    // v: tile rows i0..i0+7 = the pairs (j, j + dh/2), j = 16*sub + i0/2 .. +3, as (first, partner) x 4
     __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
-        const int tph = dh >> 5, halfp = tph >> 1;          // tiles per head, tiles per rotary half
-        const int hh = t / tph, sub = t % tph;
-        float y[8];
-        {
-            const float4 b0 = *reinterpret_cast<const float4 *>(bias + t * 32 + i0), b1 = *reinterpret_cast<const float4 *>(bias + t * 32 + i0 + 4);
-            y[0] = v[0] + b0.x; y[1] = v[1] + b0.y; y[2] = v[2] + b0.z; y[3] = v[3] + b0.w;
-            y[4] = v[4] + b1.x; y[5] = v[5] + b1.y; y[6] = v[6] + b1.z; y[7] = v[7] + b1.w;
-        }
-        if (sub < halfp) {
-            if (sub & 1) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) hold1[e] = y[e];
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) hold0[e] = y[e];
-            }
-            return;
-        }
         if (m >= M) return;
-        const int e0 = (sub - halfp) * 32 + i0;              // index inside the first half of the head
-        const int half = dh >> 1, p = rpos;
-        float lo[8], hi[8], first[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) first[e] = ((sub - halfp) & 1) ? hold1[e] : hold0[e];
+        const int tph = dh >> 5, half = dh >> 1, hh = t / tph, j0 = (t % tph) * 16 + (i0 >> 1), p = rpos;
+        const float4 ba = *reinterpret_cast<const float4 *>(bias + hh * dh + j0), bb = *reinterpret_cast<const float4 *>(bias + hh * dh + half + j0);
+        const float a[4] = {v[0] + ba.x, v[2] + ba.y, v[4] + ba.z, v[6] + ba.w}, b[4] = {v[1] + bb.x, v[3] + bb.y, v[5] + bb.z, v[7] + bb.w};
+        float lo[4], hi[4];
         if (hh < Hq + Hkv) {
-            const float4 *rp = reinterpret_cast<const float4 *>(rope + (size_t)p * half + e0);   // 8 (cos, sin) pairs, 64 bytes, aligned
-            const float4 c4[4] = {rp[0], rp[1], rp[2], rp[3]};
+            const float4 *rp = reinterpret_cast<const float4 *>(rope + (size_t)p * half + j0);   // 4 (cos, sin) pairs, 32 bytes, aligned
+            const float4 c0 = rp[0], c1 = rp[1];
+            const float cx[4] = {c0.x, c0.z, c1.x, c1.z}, sy[4] = {c0.y, c0.w, c1.y, c1.w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float cs_x = (e & 1) ? c4[e >> 1].z : c4[e >> 1].x, cs_y = (e & 1) ? c4[e >> 1].w : c4[e >> 1].y;
-                const float a = first[e], b = y[e];
-                lo[e] = a * cs_x - b * cs_y;
-                hi[e] = b * cs_x + a * cs_y;
+            for (int e = 0; e < 4; ++e) {
+                lo[e] = a[e] * cx[e] - b[e] * sy[e];
+                hi[e] = b[e] * cx[e] + a[e] * sy[e];
             }
         } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) { lo[e] = first[e]; hi[e] = y[e]; }
+            for (int e = 0; e < 4; ++e) { lo[e] = a[e]; hi[e] = b[e]; }
         }
         if (hh < Hq) {
-            float *dst = q + (size_t)m * qw + hh * dh + e0;
+            float *dst = q + (size_t)m * qw + hh * dh + j0;
             *reinterpret_cast<float4 *>(dst) = make_float4(lo[0], lo[1], lo[2], lo[3]);
-            *reinterpret_cast<float4 *>(dst + 4) = make_float4(lo[4], lo[5], lo[6], lo[7]);
             *reinterpret_cast<float4 *>(dst + half) = make_float4(hi[0], hi[1], hi[2], hi[3]);
-            *reinterpret_cast<float4 *>(dst + half + 4) = make_float4(hi[4], hi[5], hi[6], hi[7]);
         } else {
             const int head = hh < Hq + Hkv ? hh - Hq : hh - Hq - Hkv;
             if (hh < Hq + Hkv || vts == 0) {
-                KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)rslot * Hkv + head) * max_seq + p) * dh + e0;
-                store8(dst, lo);
-                store8(dst + half, hi);
-            } else {   // block-transposed V: one position of 16 dim rows
-                KT *dst = vc + ((((size_t)rslot * Hkv + head) * (vts >> 5) + (p >> 5)) * dh + e0) * 32 + (p & 31);
+                KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)rslot * Hkv + head) * max_seq + p) * dh + j0;
+                store4(dst, lo);
+                store4(dst + half, hi);
+            } else {   // block-transposed V: one position of 8 dim rows
+                KT *dst = vc + ((((size_t)rslot * Hkv + head) * (vts >> 5) + (p >> 5)) * dh + j0) * 32 + (p & 31);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) { store1(dst + e * 32, lo[e]); store1(dst + (half + e) * 32, hi[e]); }
+                for (int e = 0; e < 4; ++e) { store1(dst + e * 32, lo[e]); store1(dst + (half + e) * 32, hi[e]); }
             }
         }
+    }
+    __device__ static void store4(float *dst, const float (&v)[4]) { *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]); }
+    __device__ static void store4(bf16_t *dst, const float (&v)[4])
+    {
+        const f32x2 x0 = {v[0], v[1]}, x1 = {v[2], v[3]};
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(__builtin_bit_cast(uint32_t, __builtin_convertvector(x0, bf16x2)),
+                                                     __builtin_bit_cast(uint32_t, __builtin_convertvector(x1, bf16x2)));
     }
     __device__ static void store1(float *dst, float v) { *dst = v; }
     __device__ static void store1(bf16_t *dst, float v)
     {
         const f32x2 x = {v, 0.f};
         *dst = (bf16_t)__builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-    }
-    __device__ static void store8(float *dst, const float (&v)[8])
-    {
-        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-        *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
-    }
-    __device__ static void store8(bf16_t *dst, const float (&v)[8])
-    {
-        uint32_t h[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const f32x2 x = {v[2 * e], v[2 * e + 1]};
-            h[e] = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
-        }
-        *reinterpret_cast<uint4 *>(dst) = make_uint4(h[0], h[1], h[2], h[3]);
     }
     __device__ void end(float *) {}
 };
@@ -1062,13 +1040,14 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *pa
     const int pos = rows.pos[m], slot = rows.slot[m];
     for (int pr = blockIdx.x * blockDim.x + threadIdx.x; pr < npairs; pr += gridDim.x * blockDim.x) {
         const int hh = pr / half, j = pr % half, n1 = hh * D.dh + j, n2 = n1 + half;
+        const int c1 = hh * D.dh + (j >> 4) * 32 + 2 * (j & 15), c2 = c1 + 1;   // columns of the pair in the interleaved tile order
         float y1 = bias[n1], y2 = bias[n2];
         for (int s0 = 0; s0 < nsplit; s0 += 4) {   // fixed order, four partials requested at a time
             float a1[4], a2[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float *src = part + ((size_t)min(s0 + u, nsplit - 1) * M + m) * N;
-                a1[u] = src[n1]; a2[u] = src[n2];
+                a1[u] = src[c1]; a2[u] = src[c2];
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
@@ -1224,13 +1203,13 @@ void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, cons
 {
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.qw + 2 * D.kvw) / 32; a.M = rows.n;
-    a.tiles_per_wg = D.dh / 32;   // one head per workgroup
+    a.tiles_per_wg = 1;
     a.half = 1;
     if (kdt == DT_F32) {
-        EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, {}};
+        EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, 0, 0};
         launch_gemm(s, a, 1, e);
     } else {
-        EpiQkv<bf16_t> e{bias, rope, rows.slot, rows.pos, q, (bf16_t *)kc, (bf16_t *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, {}};
+        EpiQkv<bf16_t> e{bias, rope, rows.slot, rows.pos, q, (bf16_t *)kc, (bf16_t *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, 0, 0};
         launch_gemm(s, a, 1, e);
     }
 }

@@ -39,14 +39,14 @@ constexpr int GEMV_MAX_ROWS = 8;   // up to this many rows the streaming GEMV ke
 // epilogue (rotary, SwiGLU, softmax statistics) cannot split K across workgroups.
 bool mfma_supported(const tr_config *c)
 {
-    return c->dtype == TR_BF16 && c->d_model % 16 == 0 && c->d_model <= 896 && c->d_ffn % 16 == 0 && (c->n_q_heads * c->head_dim) % 32 == 0 &&
+    return c->dtype == TR_BF16 && c->d_model % 16 == 0 && c->d_model <= 896 && c->d_ffn % 16 == 0 && c->head_dim % 32 == 0 &&
            (c->max_batch > GEMV_MAX_ROWS || c->max_seq > GEMV_MAX_ROWS);
 }
 
 bool split_supported(const tr_config *c)
 {
     return c->dtype == TR_BF16 && c->d_model % 16 == 0 && c->d_model > 896 && c->d_model <= 4096 && c->d_ffn % 32 == 0 &&
-           (c->n_q_heads * c->head_dim) % 32 == 0 && (c->max_batch > 4 || c->max_seq > 4);
+           c->head_dim % 32 == 0 && (c->max_batch > 4 || c->max_seq > 4);
 }
 
 size_t elem_size(int dt) { return dt == TR_F32 ? 4 : 2; }
@@ -471,18 +471,18 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
         // one-time repack of the bf16 matrices into matrix-core tiles; q|k|v are concatenated, gate/up interleaved
         for (int l = 0; l < D.L; ++l) {
             const LayerW &lw = ctx->layers[(size_t)l];
-            launch_repack(nullptr, lw.wq, D.qw, D.d, ctx->wt(l, lay.wt_qkv), 0, 1);
-            launch_repack(nullptr, lw.wk, D.kvw, D.d, ctx->wt(l, lay.wt_qkv), D.qw / 32, 1);
-            launch_repack(nullptr, lw.wv, D.kvw, D.d, ctx->wt(l, lay.wt_qkv), (D.qw + D.kvw) / 32, 1);
-            launch_repack(nullptr, lw.wo, D.d, D.qw, ctx->wt(l, lay.wt_o), 0, 1);
-            launch_repack(nullptr, lw.wg, D.F, D.d, ctx->wt(l, lay.wt_gu), 0, 2);
-            launch_repack(nullptr, lw.wu, D.F, D.d, ctx->wt(l, lay.wt_gu), 1, 2);
-            launch_repack(nullptr, lw.wd, D.d, D.F, ctx->wt(l, lay.wt_d), 0, 1);
+            launch_repack(nullptr, lw.wq, D.qw, D.d, ctx->wt(l, lay.wt_qkv), 0, 1, D.dh);
+            launch_repack(nullptr, lw.wk, D.kvw, D.d, ctx->wt(l, lay.wt_qkv), D.qw / 32, 1, D.dh);
+            launch_repack(nullptr, lw.wv, D.kvw, D.d, ctx->wt(l, lay.wt_qkv), (D.qw + D.kvw) / 32, 1, D.dh);
+            launch_repack(nullptr, lw.wo, D.d, D.qw, ctx->wt(l, lay.wt_o), 0, 1, 0);
+            launch_repack(nullptr, lw.wg, D.F, D.d, ctx->wt(l, lay.wt_gu), 0, 2, 0);
+            launch_repack(nullptr, lw.wu, D.F, D.d, ctx->wt(l, lay.wt_gu), 1, 2, 0);
+            launch_repack(nullptr, lw.wd, D.d, D.F, ctx->wt(l, lay.wt_d), 0, 1, 0);
             launch_widen_bias(nullptr, lw.bq, D.qw, ctx->bias(l));
             launch_widen_bias(nullptr, lw.bk, D.kvw, ctx->bias(l) + D.qw);
             launch_widen_bias(nullptr, lw.bv, D.kvw, ctx->bias(l) + D.qw + D.kvw);
         }
-        if (lay.mfma || lay.split_head) launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1);
+        if (lay.mfma || lay.split_head) launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1, 0);
         e = hipMemset(ctx->ws + lay.pack_d, 0, lay.part - lay.pack_d);   // padding rows of the packed activations stay zero
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess) e = hipGetLastError();

@@ -108,7 +108,8 @@ void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
 void launch_lmhead_gemv(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);
 
 // matrix-core path (bf16 weights, more than a few rows)
-void launch_repack(hipStream_t s, const void *W, int N, int K, void *Wt, int dst_tile0, int dst_tile_stride);
+// pair_dh > 0: rows of each head reordered so that rotary partners are adjacent (q, k, v matrices), see repack_kernel
+void launch_repack(hipStream_t s, const void *W, int N, int K, void *Wt, int dst_tile0, int dst_tile_stride, int pair_dh);
 void launch_widen_bias(hipStream_t s, const void *b, int n, float *out);
 void launch_prep(hipStream_t s, const PrepArgs &p);
 void launch_pack(hipStream_t s, const float *in, int M, int K, void *pack, int ncb);
