@@ -114,12 +114,84 @@ def counters_workload(s):
     log("counters workload done: 1 copy of 1 GiB, 5 tail calls at 64 rows, 3 tail calls at 256 rows")
 
 
-def joint_workload(s, new_tokens=32, B=64):
+def gpu_drawn_weights(L, seed):
+    """Weights of a large model drawn on the GPU (N(0, 0.02), seeded): drawing 7.6 G values on the host takes minutes."""
+    import torch
+    from paper_2504_07878_amd import synth, tokroute
+    torch.manual_seed(seed)
+    one = synth.make_weights(L.with_(n_layers=1, vocab=64), seed)
+    draw = lambda shape: torch.randn(shape, device="cuda").mul_(0.02).to(torch.bfloat16)
+    lw = {}
+    for k, v in one.items():
+        if k.startswith("l0."):
+            for l in range(L.n_layers):
+                lw[f"l{l}." + k[3:]] = draw(v.shape) if v.ndim == 2 else tokroute.to_device(v, L.dtype)
+        elif k in ("tok_emb", "lm_head"):
+            lw[k] = draw((L.vocab, L.d_model))
+        else:
+            lw[k] = draw(v.shape) if v.ndim == 2 else tokroute.to_device(v, L.dtype)
+    return lw
+
+
+def llm7b_workload(steps, warmup):
+    """Large-model decode on the routed subset: 32 sequences with 2048 cached positions, each flagged with probability 0.07 per step.
+
+    The caches hold synthetic N(0, 1) values (one seeded fill, loaded into every slot). A step with no flagged sequence
+    costs nothing and produces nothing. Prints one JSON line of its own.
+    """
+    import numpy as np
+    import torch
+    from paper_2504_07878_amd import synth, tokroute
+    L = synth.LLM_7B
+    B, CTX = 32, 2048
+    llm = tokroute.Model(L.asdict(), gpu_drawn_weights(L, SEED), B, CTX + steps + warmup + 8)
+    k, v = synth.kv_fill(SEED, "cfg5.kv", L, CTX)
+    k, v = tokroute.to_device(k, L.kv_dtype), tokroute.to_device(v, L.kv_dtype)
+    for b in range(B):
+        llm.load_kv(b, k, v)
+    del k, v
+    flags = synth.bernoulli_flags(SEED, "cfg5.flags", (warmup + steps, B), 0.07)
+    toks = synth.prompt_tokens(SEED, "cfg5.toks", (warmup + steps) * B, L.vocab).reshape(-1, B)
+    outs = {n: llm.outputs(n) for n in range(1, B + 1)}
+    lens = np.full(B, CTX, np.int64)
+    wb = 2 * (L.n_layers * (2 * L.d_model * L.n_q_heads * L.head_dim + 2 * L.d_model * L.n_kv_heads * L.head_dim + 3 * L.d_model * L.d_ffn)
+              + L.vocab * L.d_model)
+    kvb = 2 * L.n_layers * L.n_kv_heads * L.head_dim * 2
+    routed = nbytes = 0
+    hist = {}
+    t0 = 0.0
+    for i in range(warmup + steps):
+        if i == warmup:
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+        act = [b for b in range(B) if flags[i, b]]
+        if not act:
+            if i >= warmup:
+                hist[0] = hist.get(0, 0) + 1
+            continue
+        llm.decode_step(act, toks[i, act], outs[len(act)])
+        if i >= warmup:
+            routed += len(act)
+            nbytes += wb + int(lens[act].sum() + len(act)) * kvb
+            hist[len(act)] = hist.get(len(act), 0) + 1
+        lens[act] += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    print(json.dumps({"metric": "large-model decode on the routed subset, routed tokens/s", "value": routed / dt, "unit": "tokens/s", "n_gpus": 1,
+                      "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "7B-class bf16 decoder, 32 sequences with 2048 cached positions (synthetic cache), each flagged with "
+                                             "probability 0.07 per step, decode on the flagged ones (BASELINE configs[4])",
+                                 "routed_tokens": routed, "steps_by_rows": {str(n): c for n, c in sorted(hist.items())},
+                                 "ms_per_nonempty_step": dt / max(1, steps - hist.get(0, 0)) * 1e3,
+                                 "algorithmic_GB_per_s": nbytes / dt / 1e9, "fraction_of_hbm_roofline": nbytes / dt / 1e9 / HBM_PEAK_GBPS}}), flush=True)
+
+
+def joint_workload(s, new_tokens=32, B=64, quantiles=(0.0, 0.02, 0.07, 0.2)):
     """Joint decoding of B sequences: 0.5B-class small model + router, 7B-class large model called on the flagged positions.
 
-    The router of a random-weight model knows nothing, so the threshold is set to the quantile of its scores that routes
-    about 7 % of the positions (the paper's operating point, abstract). The large model's weights are drawn on the GPU
-    (N(0, 0.02), seeded) because drawing 7.6 G values on the host takes minutes. Prints one JSON line of its own.
+    The router of a random-weight model knows nothing, so each threshold is a quantile of its scores on a plain
+    small-model run: 0.07 routes about 7 % of the positions (the paper's operating point, abstract), the others show how
+    the rate moves with the routed share (the shape of the paper's Table 1). Prints one JSON line per threshold.
     """
     import numpy as np
     import torch
@@ -128,37 +200,39 @@ def joint_workload(s, new_tokens=32, B=64):
     max_seq = 128
     weights = synth.make_weights(s, SEED, workers=8)
     slm = tokroute.Model(s.asdict(), weights, B, max_seq)
-    torch.manual_seed(SEED)
-    one = synth.make_weights(L.with_(n_layers=1), SEED)
-    lw = {}
-    for k, v in one.items():
-        if k.startswith("l0."):
-            for l in range(L.n_layers):
-                lw[f"l{l}." + k[3:]] = (torch.randn(v.shape, device="cuda").mul_(0.02).to(torch.bfloat16) if v.ndim == 2 else tokroute.to_device(v, L.dtype))
-        else:
-            lw[k] = torch.randn(v.shape, device="cuda").mul_(0.02).to(torch.bfloat16) if v.ndim == 2 else tokroute.to_device(v, L.dtype)
-    llm = tokroute.Model(L.asdict(), lw, B, max_seq)
+    llm = tokroute.Model(L.asdict(), gpu_drawn_weights(L, SEED), B, max_seq)
     prompts = [synth.prompt_tokens(SEED, f"joint.p{b}", 32, s.vocab) for b in range(B)]
-    # scores of a plain small-model run fix the threshold
+    # scores of a plain small-model run fix the thresholds
     slm.set_mode(1)
     out = slm.prefill(list(range(B)), prompts).cpu()
     scores = [out.score.copy()]
     for _ in range(8):
         out = slm.decode_step(list(range(B)), out.token).cpu()
         scores.append(out.score.copy())
-    tau = float(np.quantile(np.concatenate(scores), 0.07))
-    slm.set_mode(0); slm.set_threshold(tau)
-    joint.generate(slm, llm, prompts, 4)              # warm-up (every run starts with a prefill, which overwrites the caches)
+    scores = np.concatenate(scores)
+    slm.set_mode(0)
+    # cost of the one host round trip per step (synchronise + copy tokens, scores and flags back), for comparison with the step time
+    dev_out = slm.decode_step(list(range(B)), out.token)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    tokens, routed = joint.generate(slm, llm, prompts, new_tokens)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    print(json.dumps({"metric": "joint decoding tokens/s (0.5B-class small model + router, 7B-class large model on the routed positions)",
-                      "value": B * new_tokens / dt, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
-                      "config": {"workload": f"{B} sequences, 32-token prompts, {new_tokens} new tokens each, threshold at the 7 % quantile of the router scores",
-                                 "threshold": tau, "routed_fraction": float(routed.mean()), "seconds": dt,
-                                 "note": "prefill of both models is inside the timed region"}}), flush=True)
+    for _ in range(20):
+        dev_out.cpu(joint.NEEDED)
+    round_trip_us = (time.perf_counter() - t0) / 20 * 1e6
+    for q in quantiles:
+        tau = float(np.quantile(scores, q)) if q > 0 else 0.0
+        slm.set_threshold(tau)
+        joint.generate(slm, llm, prompts, 4)              # warm-up (every run starts with a prefill, which overwrites the caches)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        tokens, routed = joint.generate(slm, llm, prompts, new_tokens)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        print(json.dumps({"metric": "joint decoding tokens/s (0.5B-class small model + router, 7B-class large model on the routed positions)",
+                          "value": B * new_tokens / dt, "unit": "tokens/s", "n_gpus": 1, "data": "synthetic", "dtype": "bf16",
+                          "config": {"workload": f"{B} sequences, 32-token prompts, {new_tokens} new tokens each, threshold at the {q:g} quantile of the router scores",
+                                     "threshold": tau, "routed_fraction": float(routed.mean()), "seconds": dt,
+                                     "host_round_trip_us_per_step": round_trip_us,
+                                     "note": "prefill of both models is inside the timed region"}}), flush=True)
 
 
 def measured_traffic():
@@ -180,9 +254,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=512)
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="b64", choices=["b64", "counters", "joint"],
+    ap.add_argument("--workload", default="b64", choices=["b64", "counters", "joint", "llm7b"],
                     help="b64: the benchmark; counters: one 1 GiB device copy (calibration) and a few routing-tail calls at 64 rows, "
-                         "short enough for a hardware-counter pass of rocprofv3; joint: the two-model routing loop end to end")
+                         "short enough for a hardware-counter pass of rocprofv3; joint: the two-model routing loop end to end at several routed shares; "
+                         "llm7b: the large model's decode steps on a randomly flagged subset of 32 sequences")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
@@ -203,6 +278,9 @@ def main():
         return
     if args.workload == "joint":
         joint_workload(s)
+        return
+    if args.workload == "llm7b":
+        llm7b_workload(min(args.steps, 256), args.warmup)
         return
     t0 = time.perf_counter()
     weights = synth.make_weights(s, SEED, workers=8)

@@ -12,6 +12,8 @@ from __future__ import annotations
 
 import numpy as np
 
+NEEDED = ("token", "flag")     # all the host loop reads back per step: 8 bytes per sequence
+
 
 def generate(slm, llm, prompts, max_new: int):
     """Greedy joint decoding of len(prompts) sequences (slot b of both models serves sequence b).
@@ -26,18 +28,18 @@ def generate(slm, llm, prompts, max_new: int):
     llm_len = [0] * B                      # tokens of seq[b] the large model's cache holds
     tokens = np.zeros((B, max_new), np.int32)
     routed = np.zeros((B, max_new), bool)
-    out = slm.prefill(slots, prompts).cpu()
+    out = slm.prefill(slots, prompts).cpu(NEEDED)
     for t in range(max_new):
         tok = out.token.astype(np.int32).copy()
         flagged = [b for b in slots if out.flag[b]]
         first = [b for b in flagged if llm_len[b] == 0]
         later = [b for b in flagged if llm_len[b] > 0]
         if first:
-            lo = llm.prefill(first, [seq[b] for b in first]).cpu()
+            lo = llm.prefill(first, [seq[b] for b in first]).cpu(("token",))
             for i, b in enumerate(first):
                 tok[b] = lo.token[i]
         if later:
-            lo = llm.extend(later, [seq[b][llm_len[b]:] for b in later]).cpu()
+            lo = llm.extend(later, [seq[b][llm_len[b]:] for b in later]).cpu(("token",))
             for i, b in enumerate(later):
                 tok[b] = lo.token[i]
         for b in flagged:
@@ -47,5 +49,5 @@ def generate(slm, llm, prompts, max_new: int):
             seq[b].append(int(tok[b]))
         tokens[:, t] = tok
         if t + 1 < max_new:
-            out = slm.decode_step(slots, tok).cpu()
+            out = slm.decode_step(slots, tok).cpu(NEEDED)
     return tokens, routed

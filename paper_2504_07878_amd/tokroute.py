@@ -107,12 +107,14 @@ class Outputs:
         self.struct = tr_out(self.token.data_ptr(), self.conf.data_ptr(), self.score.data_ptr(), self.flag.data_ptr(),
                              self.hidden.data_ptr() if want_hidden else None, self.logits.data_ptr() if want_logits else None)
 
-    def cpu(self):
-        """Synchronise and copy everything to numpy."""
+    FIELDS = ("token", "conf", "score", "flag", "hidden", "logits")
+
+    def cpu(self, fields=FIELDS):
+        """Synchronise and copy the named outputs (default: all) to numpy; the others are None."""
         torch.cuda.synchronize()
         o = type("HostOutputs", (), {})()
-        for k in ("token", "conf", "score", "flag", "hidden", "logits"):
-            v = getattr(self, k)
+        for k in self.FIELDS:
+            v = getattr(self, k) if k in fields else None
             setattr(o, k, None if v is None else v.cpu().numpy())
         return o
 

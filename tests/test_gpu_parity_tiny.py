@@ -282,6 +282,35 @@ def test_catch_up_step_over_an_existing_cache(tr, tro, dtype):
     assert compare_outputs(go, oo, s.dtype, s.threshold, "extend to the end of the cache") == 0 and g.seq_len(3) == max_seq
 
 
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_one_call_mixes_new_prompts_decode_steps_and_catch_up(tr, tro, dtype):
+    """One tr_extend call whose segments are a new prompt for an emptied slot (a prefill), single tokens (decode steps) and
+    catch-up segments, in the same passes over the weights, against the oracle; then an ordinary decode step of everyone."""
+    s = synth.TINY.with_(dtype=dtype, kv_dtype=dtype)
+    w = synth.make_weights(s, SEED + 9, std=0.05, bias_std=0.05, gain_std=0.1)
+    B, max_seq = 6, 400
+    g = tr.Model(s.asdict(), w, B, max_seq); o = tro.Model(s.asdict(), w, B, max_seq)
+    lens = [40, 7, 130, 64, 9, 250]
+    slots = list(range(B))
+    prompts = [synth.prompt_tokens(SEED, f"mx.p{i}", n, s.vocab) for i, n in enumerate(lens)]
+    g.prefill(slots, prompts); o.prefill(slots, prompts)
+    for m in (g, o):
+        m.seq_truncate(0, 0); m.seq_truncate(3, 0)            # two requests ended; their slots take new prompts
+    seg_lens = [90, 1, 14, 33, 1, 6]
+    segs = [synth.prompt_tokens(SEED, f"mx.s{i}", n, s.vocab) for i, n in enumerate(seg_lens)]
+    go = g.extend(slots, segs, want_logits=True).cpu()
+    oo = o.extend(slots, segs, want_logits=True)
+    ex = compare_outputs(go, oo, s.dtype, s.threshold, "mixed call")
+    go = g.decode_step(slots, oo.token, want_logits=True).cpu()
+    oo = o.decode_step(slots, oo.token, want_logits=True)
+    ex += compare_outputs(go, oo, s.dtype, s.threshold, "decode after the mixed call")
+    assert ex <= 1
+    want = [90, 8, 144, 33, 10, 256]
+    cnt = g.counters()
+    for b in range(B):
+        assert g.seq_len(b) == o.seq_len(b) == want[b] + 1 and tuple(cnt[b]) == o.counters(b)
+
+
 @pytest.mark.parametrize("dtype,B", [(synth.F32, 3), (synth.BF16, 20)])
 def test_other_routing_scores(tr, tro, dtype, B):
     """The softmax-confidence score (Figure 1) and the linear deferral head compared with '>' (Section 2.2) in the fused tail,
@@ -368,3 +397,43 @@ def test_fork_of_a_sequence(tr, tro, dtype):
     fresh = tr.Model(s.asdict(), w, 2, 16)
     with pytest.raises(tr.TokrouteError):
         fresh.seq_fork(0, 1)
+
+
+ODD_SHAPES = {
+    # fp32 everywhere, GEMV + FMA attention kernels: nothing a multiple of 16 or 32, one query head per kv head
+    "f32_g1": dict(d_model=72, n_q_heads=3, n_kv_heads=3, head_dim=64, d_ffn=200, vocab=1003, router_hidden=40, dtype=synth.F32, kv_dtype=synth.F32),
+    # bf16 on the fused matrix-core path: ragged last tiles of the FFN, the residual stream and the vocabulary, 8 query heads on one kv head
+    "bf16_g8": dict(d_model=272, n_q_heads=8, n_kv_heads=1, head_dim=64, d_ffn=1040, vocab=5003, router_hidden=72, dtype=synth.BF16, kv_dtype=synth.BF16),
+    # bf16 weights over an fp32 cache
+    "bf16_f32kv": dict(d_model=272, n_q_heads=6, n_kv_heads=2, head_dim=64, d_ffn=1040, vocab=5003, router_hidden=72, dtype=synth.BF16, kv_dtype=synth.F32),
+    # wide model on the split-K path: 65 k-steps, 5 query heads per kv head, ragged vocabulary, no router, untied head
+    "wide_g5": dict(d_model=1040, n_q_heads=10, n_kv_heads=2, head_dim=128, d_ffn=2080, vocab=4099, router_hidden=0, tie_lm_head=0,
+                    dtype=synth.BF16, kv_dtype=synth.BF16),
+}
+
+
+@pytest.mark.parametrize("name,B", [("f32_g1", 5), ("bf16_g8", 3), ("bf16_g8", 21), ("bf16_f32kv", 21), ("wide_g5", 3), ("wide_g5", 12)])
+def test_shapes_that_fill_no_tile_exactly(tr, tro, name, B):
+    """Model shapes whose widths are not multiples of the kernels' tiles (reduction length, FFN width, vocabulary, router
+    width, heads per group), on every kernel family: prefill, decode steps and a catch-up step against the oracle."""
+    s = synth.TINY.with_(name=name, **ODD_SHAPES[name])
+    w = synth.make_weights(s, SEED + 11, std=0.05, bias_std=0.05, gain_std=0.1)
+    max_seq = 160
+    g = tr.Model(s.asdict(), w, B, max_seq); o = tro.Model(s.asdict(), w, B, max_seq)
+    lens = synth.prompt_lengths(SEED, f"odd.{name}.{B}", B, 1, 120)
+    lens[0] = 1
+    prompts = [synth.prompt_tokens(SEED, f"odd.{name}.{i}", int(n), s.vocab) for i, n in enumerate(lens)]
+    slots = list(range(B))
+    go = g.prefill(slots, prompts, want_logits=True).cpu(); oo = o.prefill(slots, prompts, want_logits=True)
+    ex = compare_outputs(go, oo, s.dtype, s.threshold, f"{name} B={B} prefill")
+    for step in range(3):
+        toks = oo.token.copy()
+        go = g.decode_step(slots, toks, want_logits=True).cpu(); oo = o.decode_step(slots, toks, want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"{name} B={B} step {step}")
+    segs = [synth.prompt_tokens(SEED, f"odd.{name}.seg{i}", 1 + 3 * (i % 5), s.vocab) for i in range(B)]
+    go = g.extend(slots, segs, want_logits=True).cpu(); oo = o.extend(slots, segs, want_logits=True)
+    ex += compare_outputs(go, oo, s.dtype, s.threshold, f"{name} B={B} catch-up")
+    assert ex <= 2
+    cnt = g.counters()
+    for b in range(B):
+        assert g.seq_len(b) == o.seq_len(b) and tuple(cnt[b]) == o.counters(b)

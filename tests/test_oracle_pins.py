@@ -531,6 +531,24 @@ def test_extend_bookkeeping_and_errors(tro):
     assert o.flag[0] == 0 and m.counters(0)[0] == 3
 
 
+def test_extend_of_an_emptied_slot_is_a_prefill(tro):
+    """A slot rolled back to length 0 that ingests a prompt through the catch-up step must return what a prefill of that
+    prompt returns (same logits, token, score), while a neighbour in the same call takes a single decode step: one call
+    mixes a new request with running ones (the alternating stages of Figure 2)."""
+    s = small_shape()
+    m, _ = build(tro, s, max_batch=3, max_seq=32)
+    ref, _ = build(tro, s, max_batch=3, max_seq=32)
+    toks = synth.prompt_tokens(SEED, "mix", 30, s.vocab)
+    m.prefill([0, 1], [toks[:5], toks[5:9]])
+    m.seq_truncate(0, 0)
+    a = m.extend([1, 0], [toks[9:10], toks[10:21]], want_logits=True)        # slot 1: decode step; slot 0: a new prompt of 11 tokens
+    p = ref.prefill([0], [toks[10:21]], want_logits=True)
+    assert np.array_equal(a.logits[1], p.logits[0]) and a.token[1] == p.token[0] and a.score[1] == p.score[0]
+    ref.prefill([1], [toks[5:9]])
+    d = ref.decode_step([1], [toks[9]], want_logits=True)
+    assert np.array_equal(a.logits[0], d.logits[0]) and m.seq_len(0) == 11 and m.seq_len(1) == 5
+
+
 # ------------------------------------------------------------------ other routing scores (Figure 1 caption; Section 2.2)
 
 def test_confidence_policy_routes_on_the_maximum_softmax_probability(tro):
