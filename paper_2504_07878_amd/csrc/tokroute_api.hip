@@ -23,6 +23,7 @@ struct Layout {
     size_t kc, vc, rope, counters, slot, tok, pos, gather, out_slot, x, q, att, h, hn, attn_part, tail_part, total;
     size_t attn_part_floats;
     size_t attn_cnt;
+    size_t tail_rpart, tail_rcnt;
     int max_rows, nslices;
     // matrix-core paths: repacked weights, packed activations, split-K partials.
     // mfma: K of the layers with a non-linear epilogue fits one workgroup (d <= 896), those layers are fused GEMMs and the
@@ -92,6 +93,7 @@ Layout make_layout(const tr_config *c)
     L.hn = take((size_t)c->max_batch * c->d_model * 4);
     L.attn_part = take(L.attn_part_floats * 4);
     L.attn_cnt = take(R * c->n_kv_heads * 4);
+    L.tail_rpart = take((size_t)c->max_batch * TAIL_ROUTER_PARTS * 4); L.tail_rcnt = take((size_t)c->max_batch * 4);
     L.mfma = mfma_supported(c);
     L.split = split_supported(c);
     const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab) : 0;
@@ -355,6 +357,7 @@ TailArgs tail_args(tr_ctx *ctx, const tr_out *out, int out_offset, int n)
     t.counters = ctx->at<long long>(L.counters);
     t.threshold = ctx->threshold; t.route_dir = ctx->c.route_dir; t.mode = ctx->mode; t.hidden_tap = ctx->c.hidden_tap;
     t.policy = ctx->c.route_policy;
+    t.rpart = ctx->at<float>(L.tail_rpart); t.rcnt = ctx->at<int>(L.tail_rcnt);
     return t;
 }
 
@@ -467,6 +470,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     // the attention kernels read whole 32-key blocks and mask afterwards: cache positions never written must hold finite values
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.kc, 0, lay.rope - lay.kc);
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.attn_cnt, 0, (size_t)lay.max_rows * cfg->n_kv_heads * 4);
+    if (e == hipSuccess) e = hipMemset(ctx->ws + lay.tail_rcnt, 0, (size_t)cfg->max_batch * 4);
     if (e == hipSuccess && (lay.mfma || lay.split)) {
         // one-time repack of the bf16 matrices into matrix-core tiles; q|k|v are concatenated, gate/up interleaved
         for (int l = 0; l < D.L; ++l) {

@@ -77,7 +77,10 @@ struct TailArgs {
     int counter_mode;        // 0 none, 1 add (decode), 2 set (prefill)
     float threshold; int route_dir, mode, hidden_tap;
     int policy;              // TR_POLICY_*
+    float *rpart;            // [n][TAIL_ROUTER_PARTS]: partial pre-activations of the router's output unit, one per workgroup of a row
+    int *rcnt;               // [n]: arrival counters of those workgroups, zero before and after every launch (NULL: one workgroup per row)
 };
+constexpr int TAIL_ROUTER_PARTS = 4;
 
 // ---- launchers (enqueue only) ----
 // rows 0..n-1 of one slot at positions base..base+n-1
