@@ -196,9 +196,8 @@ __device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *g
                 dots_step<WT, NR, MB>(rw[SET][u], xr, (K0) - (KC0) + u * 512 + lane * 8, acc);    \
     }
 
-    TR_ISSUE(0, 0)
-    for (int kc0 = 0; kc0 < K; kc0 += KC) {
-        const int kc = min(KC, K - kc0);
+    // stages columns kc0 .. kc0+kc-1 of the MB rows (gain applied, sums of squares taken); barriers on both sides
+    auto stage = [&](int kc0, int kc) {
         __syncthreads();
         for (int c = threadIdx.x * 4; c < kc; c += 1024) {
             float4 g = make_float4(1.f, 1.f, 1.f, 1.f);
@@ -215,10 +214,29 @@ __device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *g
             }
         }
         __syncthreads();
-        TR_ISSUE(1, kc0 + BATCH)
-        TR_CONSUME(0, kc0, kc0)
-        TR_ISSUE(0, kc0 + KC)
-        TR_CONSUME(1, kc0 + BATCH, kc0)
+    };
+    if (K <= 1024) {
+        // short rows (the 0.5B-class model's d = 896): two steps cover a row, so there is nothing to run ahead of and
+        // no request is made that is not used
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int kk = min(u * 512 + lane * 8, K - 8);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rw[0][u][r].load(wrow[r] + kk);
+        }
+        stage(0, K);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (u * 512 + lane * 8 < K) dots_step<WT, NR, MB>(rw[0][u], xr, u * 512 + lane * 8, acc);
+    } else {
+        TR_ISSUE(0, 0)
+        for (int kc0 = 0; kc0 < K; kc0 += KC) {
+            stage(kc0, min(KC, K - kc0));
+            TR_ISSUE(1, kc0 + BATCH)
+            TR_CONSUME(0, kc0, kc0)
+            TR_ISSUE(0, kc0 + KC)
+            TR_CONSUME(1, kc0 + BATCH, kc0)
+        }
     }
 #undef TR_ISSUE
 #undef TR_CONSUME
