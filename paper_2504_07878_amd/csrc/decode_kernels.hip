@@ -797,6 +797,62 @@ __global__ __launch_bounds__(256) void residual_gemv_kernel(const WT *W, Stage i
         }
 }
 
+// One activation row and weight rows of 1025 to 8192 columns (the 0.5B-class FFN output: 896 rows of 4864): the four
+// wavefronts of a workgroup share two output rows and split their columns (wavefront w takes the 512-column steps
+// w, w + 4, ...), so that a row is ONE round of requests instead of several dependent ones and four times as many
+// wavefronts stream. Each wavefront reads the activations of its own columns straight from memory, together with the
+// weights. The partial sums meet in LDS and are added in wavefront order. SPW: steps per wavefront.
+template <typename WT, int SPW>
+__global__ __launch_bounds__(256) void residual_splitk_kernel(const WT *W, const float *in, int N, int K, float *x)
+{
+    __shared__ float s_p[4][2];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 2, n2 = min(n + 1, N - 1);
+    const WT *const wrow[2] = {W + (size_t)n * K, W + (size_t)n2 * K};
+    float xold = 0.f;
+    if (threadIdx.x < 2) xold = x[min(n + (int)threadIdx.x, N - 1)];
+    Raw8<WT> rw[SPW][2];
+    float4 xv[SPW][2];
+#pragma unroll
+    for (int i = 0; i < SPW; ++i) {
+        const int k = min((wave + 4 * i) * 512 + lane * 8, K - 8);   // requests past the end of the row are redirected and unused
+        rw[i][0].load(wrow[0] + k); rw[i][1].load(wrow[1] + k);
+        xv[i][0] = *reinterpret_cast<const float4 *>(in + k); xv[i][1] = *reinterpret_cast<const float4 *>(in + k + 4);
+    }
+    float acc[2] = {0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < SPW; ++i)
+        if ((wave + 4 * i) * 512 + lane * 8 < K) {
+            const float xe[8] = {xv[i][0].x, xv[i][0].y, xv[i][0].z, xv[i][0].w, xv[i][1].x, xv[i][1].y, xv[i][1].z, xv[i][1].w};
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                float w[8];
+                rw[i][r].get(w);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[r] = fmaf(w[e], xe[e], acc[r]);
+            }
+        }
+    acc[0] = wave_sum(acc[0]); acc[1] = wave_sum(acc[1]);
+    if (lane == 0) { s_p[wave][0] = acc[0]; s_p[wave][1] = acc[1]; }
+    __syncthreads();
+    const int t = threadIdx.x;
+    if (t < 2 && n + t < N) x[n + t] = xold + ((s_p[0][t] + s_p[1][t]) + (s_p[2][t] + s_p[3][t]));
+}
+
+template <typename WT>
+static bool launch_residual_splitk(hipStream_t s, const void *W, const float *in, int R, int N, int K, float *x)
+{
+    if (R != 1 || K <= 1024 || K > 8192) return false;
+    const int spw = ((K + 511) / 512 + 3) / 4;
+    const dim3 grid((N + 1) / 2), block(256);
+    const WT *w = (const WT *)W;
+    if (spw == 1) hipLaunchKernelGGL((residual_splitk_kernel<WT, 1>), grid, block, 0, s, w, in, N, K, x);
+    else if (spw == 2) hipLaunchKernelGGL((residual_splitk_kernel<WT, 2>), grid, block, 0, s, w, in, N, K, x);
+    else if (spw == 3) hipLaunchKernelGGL((residual_splitk_kernel<WT, 3>), grid, block, 0, s, w, in, N, K, x);
+    else hipLaunchKernelGGL((residual_splitk_kernel<WT, 4>), grid, block, 0, s, w, in, N, K, x);
+    return true;
+}
+
 template <typename WT, class Stage>
 static void launch_residual_gemv(hipStream_t s, const void *W, const Stage &in, int R, int N, int K, float *x)
 {
@@ -815,15 +871,15 @@ void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const f
         return;
     }
     const StageRows st{att, (size_t)D.qw};
-    if (wdt == DT_F32) launch_residual_gemv<float>(s, wo, st, R, D.d, D.qw, x);
-    else launch_residual_gemv<bf16_t>(s, wo, st, R, D.d, D.qw, x);
+    if (wdt == DT_F32) { if (!launch_residual_splitk<float>(s, wo, att, R, D.d, D.qw, x)) launch_residual_gemv<float>(s, wo, st, R, D.d, D.qw, x); }
+    else if (!launch_residual_splitk<bf16_t>(s, wo, att, R, D.d, D.qw, x)) launch_residual_gemv<bf16_t>(s, wo, st, R, D.d, D.qw, x);
 }
 
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x)
 {
     const StageRows st{h, (size_t)D.F};
-    if (wdt == DT_F32) launch_residual_gemv<float>(s, wd, st, R, D.d, D.F, x);
-    else launch_residual_gemv<bf16_t>(s, wd, st, R, D.d, D.F, x);
+    if (wdt == DT_F32) { if (!launch_residual_splitk<float>(s, wd, h, R, D.d, D.F, x)) launch_residual_gemv<float>(s, wd, st, R, D.d, D.F, x); }
+    else if (!launch_residual_splitk<bf16_t>(s, wd, h, R, D.d, D.F, x)) launch_residual_gemv<bf16_t>(s, wd, st, R, D.d, D.F, x);
 }
 
 // ------------------------------------------------------------------ FFN input: h = silu(Wg n) * (Wu n), n = RMSNorm(x; ln2)

@@ -409,10 +409,16 @@ ODD_SHAPES = {
     # wide model on the split-K path: 65 k-steps, 5 query heads per kv head, ragged vocabulary, no router, untied head
     "wide_g5": dict(d_model=1040, n_q_heads=10, n_kv_heads=2, head_dim=128, d_ffn=2080, vocab=4099, router_hidden=0, tie_lm_head=0,
                     dtype=synth.BF16, kv_dtype=synth.BF16),
+    # a single sequence with FFN widths of 1025 to 8192: the output projection splits each weight row over the four wavefronts
+    # of a workgroup, 1, 2 or 4 steps of 512 columns each (the 0.5B-class model's 4864 gives 3)
+    "ffn_1544": dict(d_ffn=1544, dtype=synth.F32, kv_dtype=synth.F32),
+    "ffn_3000": dict(d_ffn=3000, dtype=synth.BF16, kv_dtype=synth.BF16),
+    "ffn_6152": dict(d_ffn=6152, dtype=synth.BF16, kv_dtype=synth.F32),
 }
 
 
-@pytest.mark.parametrize("name,B", [("f32_g1", 5), ("bf16_g8", 3), ("bf16_g8", 21), ("bf16_f32kv", 21), ("wide_g5", 3), ("wide_g5", 12)])
+@pytest.mark.parametrize("name,B", [("f32_g1", 5), ("bf16_g8", 3), ("bf16_g8", 21), ("bf16_f32kv", 21), ("wide_g5", 3), ("wide_g5", 12),
+                                    ("wide_g5", 1), ("ffn_1544", 1), ("ffn_3000", 1), ("ffn_6152", 1)])
 def test_shapes_that_fill_no_tile_exactly(tr, tro, name, B):
     """Model shapes whose widths are not multiples of the kernels' tiles (reduction length, FFN width, vocabulary, router
     width, heads per group), on every kernel family: prefill, decode steps and a catch-up step against the oracle."""
@@ -421,7 +427,7 @@ def test_shapes_that_fill_no_tile_exactly(tr, tro, name, B):
     max_seq = 160
     g = tr.Model(s.asdict(), w, B, max_seq); o = tro.Model(s.asdict(), w, B, max_seq)
     lens = synth.prompt_lengths(SEED, f"odd.{name}.{B}", B, 1, 120)
-    lens[0] = 1
+    lens[0] = 1 if B > 1 else 37
     prompts = [synth.prompt_tokens(SEED, f"odd.{name}.{i}", int(n), s.vocab) for i, n in enumerate(lens)]
     slots = list(range(B))
     go = g.prefill(slots, prompts, want_logits=True).cpu(); oo = o.prefill(slots, prompts, want_logits=True)
