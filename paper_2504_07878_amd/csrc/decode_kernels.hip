@@ -105,6 +105,7 @@ template <int MB> struct DotsCfg {
 
 // Where the staged activations come from: plain fp32 rows ...
 struct StageRows {
+    static constexpr bool direct = true;    // plain rows in memory: lanes may fetch their own columns
     const float *x;
     size_t stride;
     __device__ __forceinline__ float4 load(int m, int k) const { return *reinterpret_cast<const float4 *>(x + (size_t)m * stride + k); }
@@ -112,6 +113,7 @@ struct StageRows {
 };
 // ... or attention partials merged on the fly (fixed order over the chunks)
 struct StageAttn {
+    static constexpr bool direct = false;   // a staged value costs a merge over the chunks: stage once per workgroup
     AttnPending a;
     int Hq, dh, r0;
     // up to 16 chunks (the launcher defers the merge only then); all requests of a phase are issued together, with
@@ -223,6 +225,40 @@ __device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *g
             const int kk = min(u * 512 + lane * 8, K - 8);
 #pragma unroll
             for (int r = 0; r < NR; ++r) rw[0][u][r].load(wrow[r] + kk);
+        }
+        if constexpr (MB == 1 && Stage::direct) {
+            // one plain activation row: every lane fetches the 16 columns it multiplies (and their gains) together with
+            // the weights, each wavefront sees the whole row, so nothing goes through LDS and no barrier is needed
+            float4 xa[2][2];
+            Raw8<WT> gr[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int kk = min(u * 512 + lane * 8, K - 8);
+                xa[u][0] = src.load(0, kk); xa[u][1] = src.load(0, kk + 4);
+                if (NORM) gr[u].load(gain + kk);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (u * 512 + lane * 8 < K) {
+                    float xe[8] = {xa[u][0].x, xa[u][0].y, xa[u][0].z, xa[u][0].w, xa[u][1].x, xa[u][1].y, xa[u][1].z, xa[u][1].w};
+                    if (NORM) {
+                        float g[8];
+                        gr[u].get(g);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) { ss[0] = fmaf(xe[e], xe[e], ss[0]); xe[e] *= g[e]; }
+                    }
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        float w[8];
+                        rw[0][u][r].get(w);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) acc[r][0] = fmaf(w[e], xe[e], acc[r][0]);
+                    }
+                }
+#pragma unroll
+            for (int r = 0; r < NR; ++r) acc[r][0] = wave_sum(acc[r][0]);
+            if (NORM) ss[0] = wave_sum(ss[0]);
+            return;
         }
         stage(0, K);
 #pragma unroll
