@@ -266,12 +266,21 @@ __device__ __forceinline__ void wg_dots(const WT *const (&wrow)[NR], const WT *g
             if (u * 512 + lane * 8 < K) dots_step<WT, NR, MB>(rw[0][u], xr, u * 512 + lane * 8, acc);
     } else {
         TR_ISSUE(0, 0)
-        for (int kc0 = 0; kc0 < K; kc0 += KC) {
-            stage(kc0, min(KC, K - kc0));
+        int kc0 = 0;
+        for (; kc0 + KC < K; kc0 += KC) {   // chunks with a successor: every request of the steady state is unconditional
+            stage(kc0, KC);
             TR_ISSUE(1, kc0 + BATCH)
             TR_CONSUME(0, kc0, kc0)
             TR_ISSUE(0, kc0 + KC)
             TR_CONSUME(1, kc0 + BATCH, kc0)
+        }
+        stage(kc0, K - kc0);                // last chunk: nothing is requested beyond the row
+        if (kc0 + BATCH < K) {
+            TR_ISSUE(1, kc0 + BATCH)
+            TR_CONSUME(0, kc0, kc0)
+            TR_CONSUME(1, kc0 + BATCH, kc0)
+        } else {
+            TR_CONSUME(0, kc0, kc0)
         }
     }
 #undef TR_ISSUE
