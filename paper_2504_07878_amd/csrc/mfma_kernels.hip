@@ -876,7 +876,7 @@ template <int NCB, int KW, class Epi>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_kernel(GemmArgs a, Epi epi_in)
 {
     constexpr int NCO = NCB / 2;
-    __shared__ __attribute__((aligned(16))) float red[RED_FLOATS];
+    __shared__ __attribute__((aligned(16))) float red[2 * RED_FLOATS];
     Epi epi = epi_in;   // per-thread epilogue state lives in registers
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ks0 = blockIdx.y * a.ksw, ks1 = min(a.KS, ks0 + a.ksw);
@@ -926,35 +926,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
             for (int co = 0; co < NCO; ++co) acc[co] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][hl * NCO + co], acc[co], 0, 0, 0);
     };
-    // the three slices of a tile's reduction + epilogue
-    auto put = [&]() {
-        __syncthreads();   // the previous tile has been read
+    // The cross-wavefront sum of a tile goes through one of two LDS buffers, so a tile costs ONE barrier, and the sum and
+    // epilogue of tile t sit in the same straight-line stretch as the MFMAs of tile t + 1 (independent work that can
+    // fill the matrix pipe's shadow): put(t) | barrier | MFMAs(t + 1), refill, get(t), epilogue(t) | put(t + 1) | ...
+    // A buffer is rewritten two barriers after it was read, and every wavefront reads before it reaches the next barrier.
+    auto put = [&](float *rb) {
 #pragma unroll
         for (int co = 0; co < NCO; ++co)
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd)   // registers 4qd..4qd+3 are 4 consecutive feature rows of one batch column
-                *reinterpret_cast<float4 *>(&red[(wave * 64 + co * 32 + (lane & 31)) * 36 + qd * 8 + (lane >> 5) * 4]) =
+                *reinterpret_cast<float4 *>(&rb[(wave * 64 + co * 32 + (lane & 31)) * 36 + qd * 8 + (lane >> 5) * 4]) =
                     make_float4(acc[co][4 * qd], acc[co][4 * qd + 1], acc[co][4 * qd + 2], acc[co][4 * qd + 3]);
     };
-    auto get = [&](float (&v)[8]) {
-        __syncthreads();
+    auto finish = [&](int t, const float *rb) {
+        float v[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) v[r] = 0.f;
-        if (j < 32 * NCO) {
+        if (j < 32 * NCO) {   // lanes past the column blocks of this workgroup hold nothing
 #pragma unroll
             for (int ww = 0; ww < NWAVES; ++ww) {
-                const float4 lo4 = *reinterpret_cast<const float4 *>(&red[(ww * 64 + j) * 36 + i0]);
-                const float4 hi4 = *reinterpret_cast<const float4 *>(&red[(ww * 64 + j) * 36 + i0 + 4]);
+                const float4 lo4 = *reinterpret_cast<const float4 *>(&rb[(ww * 64 + j) * 36 + i0]);
+                const float4 hi4 = *reinterpret_cast<const float4 *>(&rb[(ww * 64 + j) * 36 + i0 + 4]);
                 v[0] += lo4.x; v[1] += lo4.y; v[2] += lo4.z; v[3] += lo4.w;
                 v[4] += hi4.x; v[5] += hi4.y; v[6] += hi4.z; v[7] += hi4.w;
             }
+            epi.tile(t, row0 + j, i0, v);
         }
-    };
-    auto post_tile = [&](int t) {
-        float v[8];
-        put();
-        get(v);
-        if (j < 32 * NCO) epi.tile(t, row0 + j, i0, v);   // lanes past the column blocks of this workgroup hold nothing
     };
     auto mfma_tile = [&](const uint4 (&ws)[KW]) {
 #pragma unroll
@@ -964,34 +961,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int kk = 0; kk < KW; ++kk) mfma_step(ws[kk], kk);
     };
+    float *const red0 = red, *const red1 = red + RED_FLOATS;
 
     epi.begin();
     epi.row(row0 + j);
     int t = t0;
-    if (t1 - t0 >= 4) {
-        // long tile ranges: nothing conditional between the first load and the end of the steady state, so the
-        // compiler can wait for exactly the registers it needs and leave the younger loads in flight
+    if (t0 < t1) {
         load_tile(t0, w[0]);
-        load_tile(t0 + 1, w[1]);
-        for (; t + 3 < t1; t += 2) {
-            mfma_tile(w[0]);
-            load_tile(t + 2, w[0]);
-            post_tile(t);
+        if (t0 + 1 < t1) load_tile(t0 + 1, w[1]);
+        mfma_tile(w[0]);
+        if (t0 + 2 < t1) load_tile(t0 + 2, w[0]);
+        // from here on: acc = sums of tile t, w[1] = tile t + 1, w[0] = tile t + 2 (where they exist).
+        // Long tile ranges: nothing conditional inside, so the compiler can wait for exactly the registers it needs
+        // and leave the younger loads in flight.
+        for (; t + 4 < t1; t += 2) {
+            put(red0);
+            __syncthreads();
             mfma_tile(w[1]);
             load_tile(t + 3, w[1]);
-            post_tile(t + 1);
+            finish(t, red0);
+            put(red1);
+            __syncthreads();
+            mfma_tile(w[0]);
+            load_tile(t + 4, w[0]);
+            finish(t + 1, red1);
         }
-    } else {
-        if (t < t1) load_tile(t, w[0]);
-        if (t + 1 < t1) load_tile(t + 1, w[1]);
-    }
-    // up to three tiles are left; w[0] holds tile t, w[1] tile t + 1
+        // up to four tiles are left
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-        if (t + i < t1) {
-            mfma_tile(w[i & 1]);
-            if (i == 0 && t + 2 < t1) load_tile(t + 2, w[0]);
-            post_tile(t + i);
+        for (int i = 0; i < 4; ++i) {
+            if (t + i < t1) {
+                put(i & 1 ? red1 : red0);
+                __syncthreads();
+                if (t + i + 1 < t1) {
+                    mfma_tile(w[(i + 1) & 1]);
+                    if (t + i + 3 < t1) load_tile(t + i + 3, w[(i + 1) & 1]);
+                }
+                finish(t + i, i & 1 ? red1 : red0);
+            }
         }
     }
     epi.end(red);
@@ -1164,10 +1170,22 @@ void launch_swiglu_finish(hipStream_t s, const Dims &D, const float *part, int n
     hipLaunchKernelGGL(swiglu_finish_kernel, dim3((D.F / 8 + 255) / 256, M), dim3(256), 0, s, part, nsplit, M, D.F, (uint4 *)hpack, mfma_ncb(M));
 }
 
-void plan_partial(int KS, int n_tiles, int *nsplit, int *ksw, int *tiles_per_wg)
+// Tiles per workgroup, in units of `unit` tiles, for a launch that runs `copies` workgroups over every tile (row groups x
+// splits): as few as possible while the whole launch is one round of at most 256 workgroups, all with the same share.
+// With many 64-row groups (prefill, long catch-up segments) a workgroup therefore takes many tiles, and the activations
+// it keeps in registers (229 KB for 64 rows of 896 columns) are fetched once for all of them.
+static int tiles_per_workgroup(int n_tiles, int copies, int unit)
+{
+    const int units = (n_tiles + unit - 1) / unit;
+    const int wgs_per_copy = copies >= 256 ? 1 : 256 / copies;
+    return (units + wgs_per_copy - 1) / wgs_per_copy * unit;
+}
+
+// groups: 64-row groups of the launch (more of them: fewer splits are needed to fill the chip)
+void plan_partial(int KS, int n_tiles, int groups, int *nsplit, int *ksw, int *tiles_per_wg)
 {
     int S = (KS + NWAVES * MAXKW - 1) / (NWAVES * MAXKW);
-    const int want = 256 / (n_tiles > 0 ? n_tiles : 1);
+    const int want = 256 / (n_tiles > 0 ? n_tiles * groups : 1);
     if (want > S) S = want;
     if (S > MAX_SPLITS) S = MAX_SPLITS;
     if (S > KS) S = KS;
@@ -1175,14 +1193,13 @@ void plan_partial(int KS, int n_tiles, int *nsplit, int *ksw, int *tiles_per_wg)
     S = (KS + w - 1) / w;
     *nsplit = S;
     *ksw = w;
-    int tpw = (n_tiles * S + 255) / 256;
-    *tiles_per_wg = tpw < 1 ? 1 : tpw;
+    *tiles_per_wg = tiles_per_workgroup(n_tiles, S * groups, 1);
 }
 
 int gemm_partial_splits(int K, int N)
 {
     int S, ksw, tpw;
-    plan_partial(K / 16, (N + 31) / 32, &S, &ksw, &tpw);
+    plan_partial(K / 16, (N + 31) / 32, 1, &S, &ksw, &tpw);   // one row group: the most splits any launch makes
     return S;
 }
 
@@ -1191,7 +1208,7 @@ void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K,
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = K / 16; a.n_tiles = (N + 31) / 32; a.M = M;
     int S, ksw, tpw;
-    plan_partial(a.KS, a.n_tiles, &S, &ksw, &tpw);
+    plan_partial(a.KS, a.n_tiles, (M + 63) / 64, &S, &ksw, &tpw);
     a.ksw = ksw; a.tiles_per_wg = tpw;
     EpiPartial e{part, N, M};
     launch_gemm(s, a, S, e);
@@ -1203,7 +1220,7 @@ void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, cons
 {
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.qw + 2 * D.kvw) / 32; a.M = rows.n;
-    a.tiles_per_wg = 1;
+    a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, rows.n > 32 ? 2 * ((rows.n + 63) / 64) : 1, 1);
     a.half = 1;
     if (kdt == DT_F32) {
         EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, 0, 0};
@@ -1218,7 +1235,7 @@ void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void
 {
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = 2 * ((D.F + 31) / 32); a.M = M;
-    a.tiles_per_wg = 2 * ((a.n_tiles / 2 + 255) / 256);
+    a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, (M + 63) / 64, 2);   // whole gate/up pairs
     EpiSwiglu e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}};
     launch_gemm(s, a, 1, e);
 }
