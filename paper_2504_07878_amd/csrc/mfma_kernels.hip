@@ -15,6 +15,7 @@
 //     then an epilogue functor consumes the 32x64 tile (rotary + cache append, SwiGLU, split-K partials, or the
 //     running softmax statistics of the LM head). Everything is deterministic.
 #include "tr_internal.h"
+#include <type_traits>
 
 namespace tr {
 
@@ -677,7 +678,10 @@ struct GemmArgs {
     int remap_groups;   // > 0: 1-D grid; the row groups of one tile range are placed on the same XCD, next to each other in time
 };
 
-// Epilogues receive, per thread, 8 consecutive output features (rows i0..i0+7 of tile t) of one batch row.
+// Epilogues receive, per thread, 8 consecutive output features (rows i0..i0+7 of tile t) of one batch row. PAR is the
+// parity of the tile's index inside its workgroup's range, known at compile time. An epilogue does its arithmetic
+// unconditionally and keeps conditions to its stores at the very end: the arithmetic then shares a basic block with the
+// MFMAs of the next tile, which the matrix pipe executes while the vector ALUs do the epilogue.
 
 struct EpiPartial {   // split-K partial sums: part[split][m][n]
     static constexpr bool half_only = false;
@@ -686,7 +690,7 @@ struct EpiPartial {   // split-K partial sums: part[split][m][n]
     __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void row(int) {}
-    __device__ void tile(int t, int m, int i0, const float (&v)[8])
+    template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         const int n = t * 32 + i0;
         if (m < M && n < N) {
@@ -712,7 +716,7 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
     __device__ void begin() {}
     __device__ void row(int m) { rpos = pos[min(m, M - 1)]; rslot = slot[min(m, M - 1)]; }
     // v: tile rows i0..i0+7 = the pairs (j, j + dh/2), j = 16*sub + i0/2 .. +3, as (first, partner) x 4
-    __device__ void tile(int t, int m, int i0, const float (&v)[8])
+    template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         if (m >= M) return;
         const int tph = dh >> 5, half = dh >> 1, hh = t / tph, j0 = (t % tph) * 16 + (i0 >> 1), p = rpos;
@@ -765,6 +769,8 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
     __device__ void end(float *) {}
 };
 
+// RAGGED: F is not a multiple of 32, the last tile pair is partly empty
+template <bool RAGGED>
 struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written as packed activations of the down projection
     static constexpr bool half_only = false;
     uint4 *hpack;     // [group][F/16][NCB][64]
@@ -773,25 +779,27 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
     __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void row(int) {}
-    __device__ void tile(int t, int m, int i0, const float (&v)[8])
+    // a workgroup's tile range starts at a gate tile (even index), so PAR = 0 is a gate tile, PAR = 1 its up tile
+    template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
-        if ((t & 1) == 0) {
+        if (PAR == 0) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) hold[e] = v[e];
             return;
         }
-        if (m >= M) return;
         float h[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) h[e] = hold[e] * __frcp_rn(1.0f + __expf(-hold[e])) * v[e];   // hardware exp2 and reciprocal (1 ulp each)
         const int f0 = (t >> 1) * 32 + i0;
-        if (f0 < F) store_packed(hpack + (size_t)(m >> 6) * (F / 16) * ncb * 64, ncb, m & 63, f0 >> 3, h);
+        // rows past M are written too: they lie inside the padded 64-row group and are never read back as valid rows
+        if (!RAGGED || f0 < F) store_packed(hpack + (size_t)(m >> 6) * (F / 16) * ncb * 64, ncb, m & 63, f0 >> 3, h);
     }
     __device__ void end(float *) {}
 };
 
-// DUMP = false keeps every vector-memory store out of the tile loop, so that the wait counters of the weight stream stay exact
-template <bool DUMP>
+// DUMP = false keeps every vector-memory store out of the tile loop, so that the wait counters of the weight stream stay exact.
+// RAGGED: the vocabulary is not a multiple of 32.
+template <bool DUMP, bool RAGGED>
 struct EpiLmHead {    // running softmax statistics per batch row; logits optionally dumped
     static constexpr bool half_only = false;
     float4 *part;     // [gridDim.x][M]
@@ -802,42 +810,30 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     __device__ void block(int b, int g) { bx = b; grp = g; }
     __device__ void begin() { mx = -INFINITY; sum = 0.f; idx = 0x7fffffff; }
     __device__ void row(int) {}
-    __device__ void tile(int t, int m, int i0, const float (&v)[8])
+    // Branch-free: rows past M have all-zero activations, so their statistics are finite and simply never written.
+    template <int PAR> __device__ void tile(int t, int m, int i0, const float (&vin)[8])
     {
-        if (m >= M) return;
         const int n0 = t * 32 + i0;
         if (DUMP) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                if (n0 + e < V) logits[(size_t)m * V + n0 + e] = v[e];
+                if (m < M && n0 + e < V) logits[(size_t)m * V + n0 + e] = vin[e];
         }
-        float lm = -INFINITY, add = 0.f;
-        int li = 0;
-        if (n0 + 8 <= V) {   // all but the ragged end of the vocabulary
+        float v[8];
 #pragma unroll
-            for (int e = 7; e >= 0; --e)
-                if (v[e] >= lm) { lm = v[e]; li = e; }              // descending scan: the lowest index wins ties
-            if (lm > mx) {                                          // strict: earlier tiles win ties
-                sum *= __expf(mx - lm);
-                mx = lm;
-                idx = n0 + li;
-            }
+        for (int e = 0; e < 8; ++e) v[e] = (!RAGGED || n0 + e < V) ? vin[e] : -INFINITY;   // a tile always holds at least one real row
+        float lm = v[7];
+        int li = 7;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) add += __expf(v[e] - mx);
-        } else {
+        for (int e = 6; e >= 0; --e)
+            if (v[e] >= lm) { lm = v[e]; li = e; }                  // descending scan: the lowest index wins ties
+        const float nm = fmaxf(mx, lm);
+        idx = lm > mx ? n0 + li : idx;                              // strict: earlier tiles win ties
+        float add = 0.f;
 #pragma unroll
-            for (int e = 7; e >= 0; --e)
-                if (n0 + e < V && v[e] >= lm) { lm = v[e]; li = e; }
-            if (lm > mx) {
-                sum *= __expf(mx - lm);
-                mx = lm;
-                idx = n0 + li;
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (n0 + e < V) add += __expf(v[e] - mx);
-        }
-        sum += add;
+        for (int e = 0; e < 8; ++e) add += __expf(v[e] - nm);       // exp(-inf) = 0 for the rows past the vocabulary
+        sum = fmaf(sum, __expf(mx - nm), add);                      // mx = -inf before the first tile: factor 0 on a zero sum
+        mx = nm;
     }
     // the four threads that share a batch row (one per 8-row band) merge through LDS
     __device__ void end(float *lds)
@@ -938,7 +934,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 *reinterpret_cast<float4 *>(&rb[(wave * 64 + co * 32 + (lane & 31)) * 36 + qd * 8 + (lane >> 5) * 4]) =
                     make_float4(acc[co][4 * qd], acc[co][4 * qd + 1], acc[co][4 * qd + 2], acc[co][4 * qd + 3]);
     };
-    auto finish = [&](int t, const float *rb) {
+    auto finish = [&](auto par, int t, const float *rb) {
         float v[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) v[r] = 0.f;
@@ -950,9 +946,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 v[0] += lo4.x; v[1] += lo4.y; v[2] += lo4.z; v[3] += lo4.w;
                 v[4] += hi4.x; v[5] += hi4.y; v[6] += hi4.z; v[7] += hi4.w;
             }
-            epi.tile(t, row0 + j, i0, v);
+            epi.template tile<decltype(par)::value>(t, row0 + j, i0, v);
         }
     };
+    using Par0 = std::integral_constant<int, 0>;
+    using Par1 = std::integral_constant<int, 1>;
     auto mfma_tile = [&](const uint4 (&ws)[KW]) {
 #pragma unroll
         for (int co = 0; co < NCO; ++co)
@@ -962,7 +960,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int kk = 0; kk < KW; ++kk) mfma_step(ws[kk], kk);
     };
     float *const red0 = red, *const red1 = red + RED_FLOATS;
-
     epi.begin();
     epi.row(row0 + j);
     int t = t0;
@@ -979,16 +976,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             __syncthreads();
             mfma_tile(w[1]);
             load_tile(t + 3, w[1]);
-            finish(t, red0);
+            finish(Par0{}, t, red0);
             put(red1);
             __syncthreads();
             mfma_tile(w[0]);
             load_tile(t + 4, w[0]);
-            finish(t + 1, red1);
+            finish(Par1{}, t + 1, red1);
         }
         // up to four tiles are left
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        auto tail_step = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
             if (t + i < t1) {
                 put(i & 1 ? red1 : red0);
                 __syncthreads();
@@ -996,9 +993,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                     mfma_tile(w[(i + 1) & 1]);
                     if (t + i + 3 < t1) load_tile(t + i + 3, w[(i + 1) & 1]);
                 }
-                finish(t + i, i & 1 ? red1 : red0);
+                finish(std::integral_constant<int, (i & 1)>{}, t + i, i & 1 ? red1 : red0);
             }
-        }
+        };
+        tail_step(std::integral_constant<int, 0>{});
+        tail_step(std::integral_constant<int, 1>{});
+        tail_step(std::integral_constant<int, 2>{});
+        tail_step(std::integral_constant<int, 3>{});
     }
     epi.end(red);
 }
@@ -1236,8 +1237,13 @@ void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = 2 * ((D.F + 31) / 32); a.M = M;
     a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, (M + 63) / 64, 2);   // whole gate/up pairs
-    EpiSwiglu e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}};
-    launch_gemm(s, a, 1, e);
+    if (D.F % 32) {
+        EpiSwiglu<true> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}};
+        launch_gemm(s, a, 1, e);
+    } else {
+        EpiSwiglu<false> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}};
+        launch_gemm(s, a, 1, e);
+    }
 }
 
 int lmhead_mfma_wgs(int V)
@@ -1253,13 +1259,12 @@ void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.V + 31) / 32; a.M = M;
     a.tiles_per_wg = (a.n_tiles + 255) / 256;
     a.remap_groups = M > 64 ? (M + 63) / 64 : 0;
-    if (logits) {
-        EpiLmHead<true> e{(float4 *)part, logits, M, D.V, 0.f, 0.f, 0, 0, 0, lmhead_mfma_wgs(D.V)};
+    auto go = [&](auto e) {
+        e.part = (float4 *)part; e.logits = logits; e.M = M; e.V = D.V; e.nwg = lmhead_mfma_wgs(D.V);
         launch_gemm(s, a, 1, e);
-    } else {
-        EpiLmHead<false> e{(float4 *)part, nullptr, M, D.V, 0.f, 0.f, 0, 0, 0, lmhead_mfma_wgs(D.V)};
-        launch_gemm(s, a, 1, e);
-    }
+    };
+    if (logits) { if (D.V % 32) go(EpiLmHead<true, true>{}); else go(EpiLmHead<true, false>{}); }
+    else { if (D.V % 32) go(EpiLmHead<false, true>{}); else go(EpiLmHead<false, false>{}); }
 }
 
 }  // namespace tr
