@@ -1186,7 +1186,7 @@ static int tiles_per_workgroup(int n_tiles, int copies, int unit)
 void plan_partial(int KS, int n_tiles, int groups, int *nsplit, int *ksw, int *tiles_per_wg)
 {
     int S = (KS + NWAVES * MAXKW - 1) / (NWAVES * MAXKW);
-    const int want = 256 / (n_tiles > 0 ? n_tiles * groups : 1);
+    const int want = 128 / (n_tiles > 0 ? n_tiles * groups : 1);   // half the chip: every extra split is one more partial for the next kernel to add
     if (want > S) S = want;
     if (S > MAX_SPLITS) S = MAX_SPLITS;
     if (S > KS) S = KS;
