@@ -246,7 +246,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "ed1ef2fa6c6bed1ac51d1832d9c5dba1743a5bf68e0056429f28950db663a783", "fetch_bytes": 274391619, "write_bytes": 256000}
+LMHEAD_TRAFFIC = {"source_sha256": "c064040d56b0ba9bd2659dbb730cf8d692e284f0d15dd279e06bbbf092759d46", "fetch_bytes": 274353814, "write_bytes": 256000}
 
 
 def main():
