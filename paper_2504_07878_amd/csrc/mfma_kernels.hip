@@ -75,6 +75,16 @@ __device__ __forceinline__ int paired_row(int t, int i, int pair_dh)
     return head * pair_dh + sub * 16 + (i >> 1) + (i & 1) * (pair_dh >> 1);
 }
 
+// MFMA row rho of a tile (the accumulator holds rows 8*qd + 4*hf + e in register 4*qd + e of the lanes with lane/32 = hf)
+// carries the tile's feature tile_feature(rho): features are placed so that the accumulator registers {8a .. 8a+7} of
+// one lane, a = 0 or 1, are 8 CONSECUTIVE features 16a + 8hf .. + 7. A wavefront can then hand half of its accumulator
+// to another wavefront and keep, per lane, whole runs of 8 features.
+__host__ __device__ __forceinline__ int tile_feature(int rho)
+{
+    const int qd = rho >> 3, hf = (rho >> 2) & 1, e = rho & 3;
+    return 16 * (qd >> 1) + 8 * hf + 4 * (qd & 1) + e;
+}
+
 __global__ void repack_kernel(const bf16_t *W, int N, int K, uint4 *Wt, int KS, int dst_tile0, int dst_tile_stride, int n_tiles, int pair_dh)
 {
     const size_t total = (size_t)n_tiles * KS * 64;
@@ -82,7 +92,8 @@ __global__ void repack_kernel(const bf16_t *W, int N, int K, uint4 *Wt, int KS, 
         const int lane = (int)(i & 63);
         const size_t rest = i >> 6;
         const int ks = (int)(rest % KS), t = (int)(rest / KS);
-        const int row = pair_dh ? paired_row(t, lane & 31, pair_dh) : t * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
+        const int feat = tile_feature(lane & 31);
+        const int row = pair_dh ? paired_row(t, feat, pair_dh) : t * 32 + feat, k = ks * 16 + (lane >> 5) * 8;
         uint32_t h[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) h[e] = (row < N && k + e < K) ? W[(size_t)row * K + k + e] : 0;
@@ -699,7 +710,7 @@ struct EpiPartial {   // split-K partial sums: part[split][m][n]
             *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
         }
     }
-    __device__ void end(float *) {}
+    __device__ void end(float *, int, int) {}
 };
 
 template <typename KT>
@@ -766,7 +777,7 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
         const f32x2 x = {v, 0.f};
         *dst = (bf16_t)__builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2));
     }
-    __device__ void end(float *) {}
+    __device__ void end(float *, int, int) {}
 };
 
 // RAGGED: F is not a multiple of 32, the last tile pair is partly empty
@@ -794,7 +805,7 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
         // rows past M are written too: they lie inside the padded 64-row group and are never read back as valid rows
         if (!RAGGED || f0 < F) store_packed(hpack + (size_t)(m >> 6) * (F / 16) * ncb * 64, ncb, m & 63, f0 >> 3, h);
     }
-    __device__ void end(float *) {}
+    __device__ void end(float *, int, int) {}
 };
 
 // DUMP = false keeps every vector-memory store out of the tile loop, so that the wait counters of the weight stream stay exact.
@@ -835,12 +846,13 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
         sum = fmaf(sum, __expf(mx - nm), add);                      // mx = -inf before the first tile: factor 0 on a zero sum
         mx = nm;
     }
-    // the four threads that share a batch row (one per 8-row band) merge through LDS
-    __device__ void end(float *lds)
+    // the four threads that share a batch row (one per band of 8 features) merge through LDS; row_local: the thread's
+    // batch row inside its 64-row group, band: which 8 features of every tile it held
+    __device__ void end(float *lds, int row_local, int band)
     {
         float4 *s = reinterpret_cast<float4 *>(lds);
         __syncthreads();
-        s[threadIdx.x] = make_float4(mx, __int_as_float(idx), sum, 0.f);
+        s[band * 64 + row_local] = make_float4(mx, __int_as_float(idx), sum, 0.f);
         __syncthreads();
         const int j = threadIdx.x;
         const int m = grp * 64 + j;
@@ -908,7 +920,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const size_t tile_stride = (size_t)a.KS * 64;
     uint4 w[2][KW];
     f32x16 acc[NCO];
-    const int j = threadIdx.x & 63, i0 = (threadIdx.x >> 6) * 8;
+    const int j = threadIdx.x & 63, i0 = (threadIdx.x >> 6) * 8, rho0 = (i0 >> 4) * 16 + ((i0 >> 3) & 1) * 4;
 
     auto load_tile = [&](int t, uint4 (&ws)[KW]) {   // unconditional: t must be a valid tile
         const uint4 *wp = a.Wt + (size_t)t * tile_stride + lane;
@@ -930,7 +942,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
         for (int co = 0; co < NCO; ++co)
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd)   // registers 4qd..4qd+3 are 4 consecutive feature rows of one batch column
+            for (int qd = 0; qd < 4; ++qd)   // registers 4qd..4qd+3 are the 4 consecutive MFMA rows 8qd + 4(lane/32) .. of one batch column
                 *reinterpret_cast<float4 *>(&rb[(wave * 64 + co * 32 + (lane & 31)) * 36 + qd * 8 + (lane >> 5) * 4]) =
                     make_float4(acc[co][4 * qd], acc[co][4 * qd + 1], acc[co][4 * qd + 2], acc[co][4 * qd + 3]);
     };
@@ -941,8 +953,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         if (j < 32 * NCO) {   // lanes past the column blocks of this workgroup hold nothing
 #pragma unroll
             for (int ww = 0; ww < NWAVES; ++ww) {
-                const float4 lo4 = *reinterpret_cast<const float4 *>(&rb[(ww * 64 + j) * 36 + i0]);
-                const float4 hi4 = *reinterpret_cast<const float4 *>(&rb[(ww * 64 + j) * 36 + i0 + 4]);
+                // features i0..i0+3 and i0+4..i0+7 sit in MFMA rows rho0.. and rho0+8.. (see tile_feature)
+                const float4 lo4 = *reinterpret_cast<const float4 *>(&rb[(ww * 64 + j) * 36 + rho0]);
+                const float4 hi4 = *reinterpret_cast<const float4 *>(&rb[(ww * 64 + j) * 36 + rho0 + 8]);
                 v[0] += lo4.x; v[1] += lo4.y; v[2] += lo4.z; v[3] += lo4.w;
                 v[4] += hi4.x; v[5] += hi4.y; v[6] += hi4.z; v[7] += hi4.w;
             }
@@ -1001,13 +1014,147 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         tail_step(std::integral_constant<int, 2>{});
         tail_step(std::integral_constant<int, 3>{});
     }
-    epi.end(red);
+    epi.end(red, threadIdx.x & 63, threadIdx.x >> 6);
 }
 
 template <int NCB, int KW, class Epi>
 static void launch_gemm_one(hipStream_t s, const GemmArgs &a, dim3 grid, const Epi &epi)
 {
     hipLaunchKernelGGL((gemm_kernel<NCB, KW, Epi>), grid, dim3(256), 0, s, a, epi);
+}
+
+// 64-row groups: the wavefronts split K in two and the rows in two (wavefront = (K half kh, row half rh)), so only TWO
+// partial tiles have to be added per output instead of four, and each wavefront hands over just half of its
+// accumulator: of the MFMA rows it computed, those of runs 8a..8a+7, a != kh, go to its partner (same rows, other
+// K half) through LDS, the others stay in registers. 16 KB of LDS traffic per tile instead of 64 KB, which was the
+// largest item of a tile after the MFMAs. Thanks to tile_feature() a lane ends up with 8 consecutive features
+// 16 kh + 8 (lane / 32) .. of batch row 32 rh + lane % 32: the epilogues see what they saw before.
+// The weights of a wavefront's K half (up to 28 k-steps) live in ONE register ring: entry kk is refilled with the
+// next tile's k-step right after the two MFMAs that read it have been issued, so a whole tile is in flight ahead of
+// the arithmetic. The hi and lo products accumulate separately (two dependent MFMAs on one accumulator run at half
+// rate) and are added once per tile. Exchange buffers alternate, so a tile costs one barrier, and the partner's half
+// and the epilogue of tile t follow the MFMAs of tile t + 1 in the same straight-line stretch.
+template <int KW2, class Epi>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm22_kernel(GemmArgs a, Epi epi_in)
+{
+    __shared__ float4 xb[2][NWAVES][2][64];
+    Epi epi = epi_in;   // per-thread epilogue state lives in registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: everything derived from it stays in scalar registers
+    const int lane = threadIdx.x & 63, kh = wave & 1, rh = wave >> 1, hf = lane >> 5;
+    const int ks0 = blockIdx.y * a.ksw, ks1 = min(a.KS, ks0 + a.ksw);
+    const int per = (ks1 - ks0 + 1) / 2;   // <= KW2
+    const int wk0 = ks0 + kh * per;
+    const int nk = max(0, min(ks1, wk0 + per) - wk0);
+    int bx = blockIdx.x, group = blockIdx.z;
+    if (a.remap_groups > 0) {   // workgroups are dealt to the 8 XCDs round-robin: keep the groups of a tile range on one XCD
+        const int xcd = bx & 7, slot = bx >> 3;
+        group = slot % a.remap_groups;
+        bx = (slot / a.remap_groups) * 8 + xcd;
+    }
+    epi.block(bx, group);
+    const int m = group * 64 + rh * 32 + (lane & 31), i0 = 16 * kh + 8 * hf;
+
+    // resident activations: hi and lo halves of this wavefront's 32 rows over its k-steps (zero beyond its share)
+    bf16x8 b[KW2][2];
+    int koff[KW2];   // k-step of each resident slot, clamped into the matrix
+#pragma unroll
+    for (int kk = 0; kk < KW2; ++kk) {
+        koff[kk] = min(wk0 + kk, a.KS - 1);
+#pragma unroll
+        for (int hl = 0; hl < 2; ++hl) {
+            uint4 u = make_uint4(0, 0, 0, 0);
+            if (kk < nk) u = a.pack[(((size_t)group * a.KS + wk0 + kk) * 4 + 2 * hl + rh) * 64 + lane];
+            b[kk][hl] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
+
+    const int t0 = min(bx * a.tiles_per_wg, a.n_tiles), t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
+    const size_t tile_stride = (size_t)a.KS * 64;
+    uint4 w[KW2];
+    f32x16 acc_hi, acc_lo;
+    float own[8];
+
+    // the MFMAs of the tile held in w; with REFILL every entry is overwritten by tile tn (which must exist) once it has been read
+    auto mfma_tile = [&](auto refill, int tn) {
+        const uint4 *wp = a.Wt + (size_t)tn * tile_stride + lane;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { acc_hi[r] = 0.f; acc_lo[r] = 0.f; }
+#pragma unroll
+        for (int kk = 0; kk < KW2; ++kk) {
+            const bf16x8 wv = __builtin_bit_cast(bf16x8, w[kk]);
+            acc_hi = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][0], acc_hi, 0, 0, 0);
+            acc_lo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[kk][1], acc_lo, 0, 0, 0);
+            if (decltype(refill)::value) w[kk] = wp[(size_t)koff[kk] * 64];
+        }
+    };
+    // hi + lo; the runs of 8 MFMA rows this wavefront finishes stay in registers, the other two quads go to the partner
+    auto send = [&](int buf) {
+        float sum[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum[r] = acc_hi[r] + acc_lo[r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) own[e] = kh ? sum[8 + e] : sum[e];
+        xb[buf][wave][0][lane] = kh ? make_float4(sum[0], sum[1], sum[2], sum[3]) : make_float4(sum[8], sum[9], sum[10], sum[11]);
+        xb[buf][wave][1][lane] = kh ? make_float4(sum[4], sum[5], sum[6], sum[7]) : make_float4(sum[12], sum[13], sum[14], sum[15]);
+    };
+    auto finish = [&](auto par, int t, int buf) {
+        const float4 p0 = xb[buf][wave ^ 1][0][lane], p1 = xb[buf][wave ^ 1][1][lane];
+        const float v[8] = {own[0] + p0.x, own[1] + p0.y, own[2] + p0.z, own[3] + p0.w, own[4] + p1.x, own[5] + p1.y, own[6] + p1.z, own[7] + p1.w};
+        epi.template tile<decltype(par)::value>(t, m, i0, v);
+    };
+    using No = std::integral_constant<bool, false>;
+    using Yes = std::integral_constant<bool, true>;
+    using Par0 = std::integral_constant<int, 0>;
+    using Par1 = std::integral_constant<int, 1>;
+
+    epi.begin();
+    epi.row(m);
+    int t = t0;
+    if (t0 < t1) {
+        {
+            const uint4 *wp = a.Wt + (size_t)t0 * tile_stride + lane;
+#pragma unroll
+            for (int kk = 0; kk < KW2; ++kk) w[kk] = wp[(size_t)koff[kk] * 64];
+        }
+        if (t0 + 1 < t1) mfma_tile(Yes{}, t0 + 1); else mfma_tile(No{}, t0);
+        // from here on: the accumulators hold tile t, the ring holds tile t + 1 (where it exists).
+        // Long tile ranges: nothing conditional inside, so the compiler can wait for exactly the registers it needs.
+        for (; t + 3 < t1; t += 2) {
+            send(0);
+            __syncthreads();
+            mfma_tile(Yes{}, t + 2);
+            finish(Par0{}, t, 0);
+            send(1);
+            __syncthreads();
+            mfma_tile(Yes{}, t + 3);
+            finish(Par1{}, t + 1, 1);
+        }
+        // up to three tiles are left
+        auto tail_step = [&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            if (t + i < t1) {
+                send(i & 1);
+                __syncthreads();
+                if (t + i + 2 < t1) mfma_tile(Yes{}, t + i + 2);
+                else if (t + i + 1 < t1) mfma_tile(No{}, t + i + 1);
+                finish(std::integral_constant<int, (i & 1)>{}, t + i, i & 1);
+            }
+        };
+        tail_step(std::integral_constant<int, 0>{});
+        tail_step(std::integral_constant<int, 1>{});
+        tail_step(std::integral_constant<int, 2>{});
+    }
+    epi.end(reinterpret_cast<float *>(&xb[0][0][0][0]), rh * 32 + (lane & 31), 2 * kh + hf);
+}
+
+template <class Epi>
+static void launch_gemm22_kw(hipStream_t s, const GemmArgs &a, dim3 grid, const Epi &epi)
+{
+    const int per = (a.ksw + 1) / 2;
+    if (per <= 4) hipLaunchKernelGGL((gemm22_kernel<4, Epi>), grid, dim3(256), 0, s, a, epi);
+    else if (per <= 8) hipLaunchKernelGGL((gemm22_kernel<8, Epi>), grid, dim3(256), 0, s, a, epi);
+    else if (per <= 16) hipLaunchKernelGGL((gemm22_kernel<16, Epi>), grid, dim3(256), 0, s, a, epi);
+    else hipLaunchKernelGGL((gemm22_kernel<28, Epi>), grid, dim3(256), 0, s, a, epi);
 }
 
 template <int NCB, class Epi>
@@ -1030,7 +1177,13 @@ static void launch_gemm(hipStream_t s, const GemmArgs &a, int nsplit, const Epi 
     GemmArgs b = a;
     b.half = 0;
     if (a.M <= 32) launch_gemm_kw<2>(s, b, grid, epi);
-    else if constexpr (!Epi::half_only) launch_gemm_kw<4>(s, b, grid, epi);   // half-only epilogues never get here: no 64-row instance of them
+    else if constexpr (!Epi::half_only) {   // half-only epilogues never get here: no 64-row instance of them
+        // One 64-row group: weights come from HBM once and the LDS reduction is what limits a tile, so K and rows are
+        // split two ways each. Several groups re-read the weights from L2, where loading every tile twice per
+        // workgroup costs more than the smaller reduction saves: they keep the four-way K split.
+        if (groups == 1) launch_gemm22_kw(s, b, grid, epi);
+        else launch_gemm_kw<4>(s, b, grid, epi);
+    }
 }
 
 int mfma_ncb(int M) { return M <= 32 ? 2 : 4; }
