@@ -246,7 +246,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "c064040d56b0ba9bd2659dbb730cf8d692e284f0d15dd279e06bbbf092759d46", "fetch_bytes": 274353814, "write_bytes": 256000}
+LMHEAD_TRAFFIC = {"source_sha256": "1700717b9f4ed1aa4932b85ded7ecf06dfa7acd92e8fc5417ca33ddc2e8ebed0", "fetch_bytes": 274427088, "write_bytes": 256000}
 
 
 def main():
@@ -322,7 +322,7 @@ def main():
                    "batch": B, "max_seq": MAX_SEQ, "seed": SEED, "prefill_seconds": prefill_s,
                    "algorithmic_bytes_per_step": step_bytes, "hbm_roofline_tokens_per_s": roof_tok_s,
                    "fraction_of_hbm_roofline": tok_s / roof_tok_s},
-        "roofline": {"bound": "hbm", "kernel": "gemm_kernel<4,14,EpiLmHead> (LM head of the routing tail, 64 rows)", "achieved": lm_bytes / lm_avg_s / 1e9 if lm_n else None,
+        "roofline": {"bound": "hbm", "kernel": "gemm22_kernel<28,EpiLmHead> (LM head of the routing tail, 64 rows)", "achieved": lm_bytes / lm_avg_s / 1e9 if lm_n else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": (lm_bytes / lm_avg_s / 1e9 / HBM_PEAK_GBPS) if lm_n else None,
                      "traffic": measured_traffic(), "launches": lm_n, "avg_us": lm_avg_s * 1e6, "algorithmic_bytes_per_launch": lm_bytes,
                      "event_pair_avg_us": lm_raw[0] / max(lm_n, 1) * 1e3, "empty_event_pair_avg_us": lm_raw[1] / max(lm_n, 1) * 1e3},
