@@ -64,6 +64,13 @@ typedef struct tr_config {
     int32_t max_batch;     /* number of sequence slots */
     int32_t max_seq;       /* cache capacity per slot, in tokens */
     int32_t route_policy;  /* TR_POLICY_*; router_hidden is ignored unless TR_POLICY_MLP */
+    int32_t kv_page;       /* 0: every slot owns max_seq contiguous cache positions. > 0: paged cache (the cache management
+                              for alternating prefill and decode stages that Section 2.3 of the paper asks for): positions
+                              live in pages of kv_page tokens (a power of two >= 32; kv_dtype must be TR_BF16) taken from a
+                              common pool as sequences grow and given back by tr_seq_truncate / tr_prefill; tr_seq_fork
+                              shares pages and a shared page is copied only when one side is about to write into it */
+    int32_t kv_pool_pages; /* pages in the pool; 0 = max_batch * ceil(max_seq / kv_page) (no call can run out). With a smaller
+                              pool a call that needs more pages than are free returns TR_ERR_CAPACITY and changes nothing */
 } tr_config;
 
 /* DEVICE pointers, row-major [out][in], all in tr_config.dtype. BORROWED: they must stay valid and

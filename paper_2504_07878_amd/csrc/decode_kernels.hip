@@ -405,15 +405,16 @@ __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float 
     const int r0 = blockIdx.y * MB;
     // what the epilogue needs from memory is requested now (position -> rotary pair is a chain of two dependent loads)
     // and arrives while the weights stream
-    int pos[MB], slot[MB];
+    KvPlace place[MB];   // where the row's new key and value go
     float2 cs[MB];
     float b1 = 0.f, b2 = 0.f;
     if (bias) { b1 = widen(bias, n1); b2 = widen(bias, n2); }
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
         const int r = min(r0 + m, rows.n - 1);
-        pos[m] = rows.pos[r]; slot[m] = rows.slot[r];
-        cs[m] = rope[(size_t)pos[m] * half + j];
+        const int pos = rows.pos[r];
+        place[m] = kv_place(D, rows.slot[r], pos);
+        cs[m] = rope[(size_t)pos * half + j];
     }
     float acc[2][MB], ss[MB];
     wg_dots<WT, 2, MB, true>(wrow, (const WT *)w.ln1, StageRows{x + (size_t)r0 * D.d, (size_t)D.d}, rows.n - r0, D.d, xs, acc, ss);
@@ -432,12 +433,12 @@ __global__ __launch_bounds__(256) void qkv_kernel(Dims D, LayerW w, const float 
             q[(size_t)r * D.qw + n1] = y1;
             q[(size_t)r * D.qw + n2] = y2;
         } else if (hh < D.Hq + D.Hkv) {
-            KT *dst = kc + (((size_t)slot[m] * D.Hkv + head) * D.max_seq + pos[m]) * D.dh;
+            KT *dst = kc + k_offset(D, place[m].unit, head, place[m].pos, 0);
             store_kv(dst + j, y1);
             store_kv(dst + j + half, y2);
         } else {
-            store_kv(vc + v_offset(D, slot[m], head, pos[m], j), y1);
-            store_kv(vc + v_offset(D, slot[m], head, pos[m], j + half), y2);
+            store_kv(vc + v_offset(D, place[m].unit, head, place[m].pos, j), y1);
+            store_kv(vc + v_offset(D, place[m].unit, head, place[m].pos, j + half), y2);
         }
     }
 }
@@ -972,14 +973,14 @@ __global__ void load_kv_kernel(Dims D, int slot, int len, const KT *k, const KT 
 {
     const size_t per_layer_src = (size_t)D.Hkv * len * D.dh;
     const size_t total = (size_t)D.L * per_layer_src;
-    const size_t layer_stride = (size_t)D.max_batch * D.Hkv * D.max_seq * D.dh;
-    const size_t v_layer_stride = (size_t)D.max_batch * D.Hkv * D.dh * (D.vts ? D.vts : D.max_seq);
+    const size_t layer_stride = (size_t)D.units * D.Hkv * kv_unit_len(D) * D.dh;
+    const size_t v_layer_stride = (size_t)D.units * D.Hkv * D.dh * (kv_unit_vts(D) ? kv_unit_vts(D) : kv_unit_len(D));
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const size_t l = i / per_layer_src, rem = i % per_layer_src;
         const size_t g = rem / ((size_t)len * D.dh), pe = rem % ((size_t)len * D.dh);
-        const size_t dst = l * layer_stride + ((size_t)slot * D.Hkv + g) * D.max_seq * D.dh + pe;
-        kc[dst] = k[i];
-        vc[l * v_layer_stride + v_offset(D, slot, (int)g, (int)(pe / D.dh), (int)(pe % D.dh))] = v[i];
+        const KvPlace at = kv_place(D, slot, (int)(pe / D.dh));
+        kc[l * layer_stride + k_offset(D, at.unit, (int)g, at.pos, (int)(pe % D.dh))] = k[i];
+        vc[l * v_layer_stride + v_offset(D, at.unit, (int)g, at.pos, (int)(pe % D.dh))] = v[i];
     }
 }
 

@@ -359,15 +359,19 @@ __device__ __forceinline__ void to_hi_lo(const float (&v)[8], bf16x8 &hi, bf16x8
 // The walk of one wavefront over the blocks of 32 keys t_begin, t_begin + t_step, ... < j1 of one (row, kv head):
 // running maximum m and sum l of its head column (both lanes of a head agree on m; l is per lane) and the
 // unnormalised output o, accumulator register rr of block db = dim db*32 + 8*(rr/4) + 4*hf + rr%4 of head j.
-template <int DH>
+// kc, vt: one layer's K cache and transposed V cache; PAGED: the row's keys live in pages looked up per block of 32 keys.
+template <int DH, bool PAGED>
 struct AttnWave {
     static constexpr int KSQ = DH / 16, DB = DH / 32;
     float m, l;
     f32x16 o[DB];
 
-    __device__ __forceinline__ void run(const Dims &D, const float *qrow /* q of this row */, const bf16_t *Kb, const bf16_t *Vb, int g, int t_begin,
-                                        int t_step, int j1)
+    __device__ __forceinline__ void run(const Dims &D, const float *qrow /* q of this row */, const bf16_t *kc, const bf16_t *vt, int slot, int g,
+                                        int t_begin, int t_step, int j1)
     {
+        const int ulen = PAGED ? D.page : D.max_seq, uvts = PAGED ? D.page : D.vts;   // positions per storage unit
+        const bf16_t *Kb = kc + ((size_t)slot * D.Hkv + g) * (size_t)ulen * DH, *Vb = vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * uvts;   // contiguous cache
+        [[maybe_unused]] const int t_last = (j1 - 1) & ~31;   // last block of 32 keys that holds a key of this row
         const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
         bf16x8 qh[KSQ], ql[KSQ];
         {
@@ -396,11 +400,22 @@ struct AttnWave {
             uint4 ka[NB][KSQ], va[NB][2][DB];
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const int t = t0 + nb * t_step;   // may start past j1 in the last trip: rows are clamped, V^T rows are padded to 32
-                const bf16_t *kp = Kb + (size_t)min(t + krow, j1 - 1) * DH + hf * 8;
+                int t = t0 + nb * t_step;   // may start past j1 in the last trip
+                const bf16_t *kp;
+                int tv;                     // start of the block of V^T rows inside its storage unit
+                if constexpr (PAGED) {
+                    t = min(t, t_last);     // such a block's requests are redirected to the row's last block and unused
+                    const int unit = D.ptab[(size_t)slot * D.maxp + t / D.page];
+                    Kb = kc + ((size_t)unit * D.Hkv + g) * (size_t)ulen * DH;
+                    Vb = vt + ((size_t)unit * D.Hkv + g) * (size_t)DH * uvts;
+                    tv = t % D.page;
+                    kp = Kb + (size_t)(tv + min(krow, j1 - 1 - t)) * DH + hf * 8;
+                } else {                    // rows are clamped, V^T rows are padded to 32
+                    kp = Kb + (size_t)min(t + krow, j1 - 1) * DH + hf * 8;
+                    tv = min(t, D.vts - 32);
+                }
 #pragma unroll
                 for (int ks = 0; ks < KSQ; ++ks) ka[nb][ks] = *reinterpret_cast<const uint4 *>(kp + ks * 16);
-                const int tv = min(t, D.vts - 32);
 #pragma unroll
                 for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
@@ -460,7 +475,7 @@ struct AttnWave {
 
 // One wavefront per (query row, chunk of the context), kv head along gridDim.y: partials for the merge, or the final
 // rows when there is a single chunk.
-template <int DH>
+template <int DH, bool PAGED>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows, int chunk,
                                                         int nchunks, float *part, float *att)
 {
@@ -474,9 +489,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     const int slot = rows.slot[r];
     if (j0 >= ctx) return;   // no key of this row in the chunk: the merge never reads its partial
 
-    AttnWave<DH> w;
-    w.run(D, q + (size_t)r * D.qw, kc + ((size_t)slot * D.Hkv + g) * (size_t)D.max_seq * DH, vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * D.vts, g, j0, 32,
-          j1);
+    AttnWave<DH, PAGED> w;
+    w.run(D, q + (size_t)r * D.qw, kc, vt, slot, g, j0, 32, j1);
     const float lt = w.l + __shfl_xor(w.l, 32, 64);      // both lanes of a head used the same running maximum
     if (j >= G) return;
     const int head = g * G + j;
@@ -510,7 +524,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
 // pairs to fill the chip this replaces the chunked kernel plus the separate merge.
 constexpr int ATT_ROW_WAVES = 8;
 
-template <int DH>
+template <int DH, bool PAGED>
 __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows,
                                                                       int span, float *part, int *cnt, float *att, uint4 *pack, int ncb)
 {
@@ -528,9 +542,8 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
     const int j0 = pt * len, j1 = min(ctx, j0 + len);
 
     if (j0 + wv * 32 < j1) {
-        AttnWave<DH> w;
-        w.run(D, q + (size_t)r * D.qw, kc + ((size_t)slot * D.Hkv + g) * (size_t)D.max_seq * DH, vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * D.vts, g,
-              j0 + wv * 32, NW * 32, j1);
+        AttnWave<DH, PAGED> w;
+        w.run(D, q + (size_t)r * D.qw, kc, vt, slot, g, j0 + wv * 32, NW * 32, j1);
         const float lt = w.l + __shfl_xor(w.l, 32, 64);
         if (j < G) {
 #pragma unroll
@@ -645,12 +658,12 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
         if ((size_t)(max_ctx + span - 1) / span > room) span = 256 * (int)((max_ctx + 256 * room - 1) / (256 * room));
         const int P = (max_ctx + span - 1) / span;
         const dim3 grid(rows.n, D.Hkv, P);
-        if (D.dh == 64)
-            hipLaunchKernelGGL(attn_rows_kernel<64>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, span, part,
-                               cnt, pack ? nullptr : att, (uint4 *)pack, ncb);
-        else
-            hipLaunchKernelGGL(attn_rows_kernel<128>, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, span, part,
-                               cnt, pack ? nullptr : att, (uint4 *)pack, ncb);
+        auto go = [&](auto kern) {
+            hipLaunchKernelGGL(kern, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, span, part, cnt,
+                               pack ? nullptr : att, (uint4 *)pack, ncb);
+        };
+        if (D.dh == 64) { if (D.page) go(attn_rows_kernel<64, true>); else go(attn_rows_kernel<64, false>); }
+        else { if (D.page) go(attn_rows_kernel<128, true>); else go(attn_rows_kernel<128, false>); }
         return;
     }
     // decode: up to 32 chunks of the context per row, merged afterwards; prompts: one wavefront walks the whole context of a row
@@ -663,10 +676,9 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
     }
     const dim3 grid((rows.n * nchunks + 3) / 4, D.Hkv);
     float *direct = nchunks == 1 ? att : nullptr;
-    if (D.dh == 64)
-        hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
-    else
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct);
+    auto go = [&](auto kern) { hipLaunchKernelGGL(kern, grid, dim3(256), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, chunk, nchunks, part, direct); };
+    if (D.dh == 64) { if (D.page) go(attn_mfma_kernel<64, true>); else go(attn_mfma_kernel<64, false>); }
+    else { if (D.page) go(attn_mfma_kernel<128, true>); else go(attn_mfma_kernel<128, false>); }
     if (nchunks > 1 && defer && !pack && rows.n <= 4 && nchunks <= 16) {   // the consumer merges
         defer->part = part; defer->pos = rows.pos; defer->nchunks = nchunks; defer->chunk = chunk;
         return;
@@ -721,11 +733,18 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
     const int *slot, *pos;
     float *q;
     KT *kc, *vc;
-    int M, Hq, Hkv, dh, max_seq, qw, vts;
-    int rpos, rslot;          // position and slot of this thread's batch row, fetched ahead of the weight stream
+    int M, Hq, Hkv, dh, max_seq, qw, vts;   // max_seq, vts: positions per storage unit of the cache (a slot or a page)
+    const int *ptab;          // paged cache: page table [slot][maxp] and page length; page = 0: the unit is the slot
+    int page, maxp;
+    int rpos, runit, rupos;   // position of this thread's batch row (for the rotation) and where its key and value go:
+                              // storage unit and position inside it, fetched ahead of the weight stream
     __device__ void block(int, int) {}
     __device__ void begin() {}
-    __device__ void row(int m) { rpos = pos[min(m, M - 1)]; rslot = slot[min(m, M - 1)]; }
+    __device__ void row(int m)
+    {
+        rpos = pos[min(m, M - 1)]; runit = slot[min(m, M - 1)]; rupos = rpos;
+        if (page) { runit = ptab[(size_t)runit * maxp + rpos / page]; rupos = rpos % page; }
+    }
     // v: tile rows i0..i0+7 = the pairs (j, j + dh/2), j = 16*sub + i0/2 .. +3, as (first, partner) x 4
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
@@ -754,11 +773,11 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
         } else {
             const int head = hh < Hq + Hkv ? hh - Hq : hh - Hq - Hkv;
             if (hh < Hq + Hkv || vts == 0) {
-                KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)rslot * Hkv + head) * max_seq + p) * dh + j0;
+                KT *dst = (hh < Hq + Hkv ? kc : vc) + (((size_t)runit * Hkv + head) * max_seq + rupos) * dh + j0;
                 store4(dst, lo);
                 store4(dst + half, hi);
             } else {   // block-transposed V: one position of 8 dim rows
-                KT *dst = vc + ((((size_t)rslot * Hkv + head) * (vts >> 5) + (p >> 5)) * dh + j0) * 32 + (p & 31);
+                KT *dst = vc + ((((size_t)runit * Hkv + head) * (vts >> 5) + (rupos >> 5)) * dh + j0) * 32 + (rupos & 31);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { store1(dst + e * 32, lo[e]); store1(dst + (half + e) * 32, hi[e]); }
             }
@@ -1197,7 +1216,8 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *pa
                                                          float *q, KT *kc, KT *vc)
 {
     const int m = blockIdx.y, half = D.dh / 2, N = D.qw + 2 * D.kvw, npairs = (D.Hq + 2 * D.Hkv) * half;
-    const int pos = rows.pos[m], slot = rows.slot[m];
+    const int pos = rows.pos[m];
+    const KvPlace at = kv_place(D, rows.slot[m], pos);
     for (int pr = blockIdx.x * blockDim.x + threadIdx.x; pr < npairs; pr += gridDim.x * blockDim.x) {
         const int hh = pr / half, j = pr % half, n1 = hh * D.dh + j, n2 = n1 + half;
         const int c1 = hh * D.dh + (j >> 4) * 32 + 2 * (j & 15), c2 = c1 + 1;   // columns of the pair in the interleaved tile order
@@ -1222,13 +1242,13 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *pa
             q[(size_t)m * D.qw + n1] = y1;
             q[(size_t)m * D.qw + n2] = y2;
         } else if (hh < D.Hq + D.Hkv) {
-            KT *dst = kc + (((size_t)slot * D.Hkv + (hh - D.Hq)) * D.max_seq + pos) * D.dh;
+            KT *dst = kc + k_offset(D, at.unit, hh - D.Hq, at.pos, 0);
             EpiQkv<KT>::store1(dst + j, y1);
             EpiQkv<KT>::store1(dst + j + half, y2);
         } else {
             const int head = hh - D.Hq - D.Hkv;
-            EpiQkv<KT>::store1(vc + v_offset(D, slot, head, pos, j), y1);
-            EpiQkv<KT>::store1(vc + v_offset(D, slot, head, pos, j + half), y2);
+            EpiQkv<KT>::store1(vc + v_offset(D, at.unit, head, at.pos, j), y1);
+            EpiQkv<KT>::store1(vc + v_offset(D, at.unit, head, at.pos, j + half), y2);
         }
     }
 }
@@ -1377,10 +1397,12 @@ void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, cons
     a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, rows.n > 32 ? 2 * ((rows.n + 63) / 64) : 1, 1);
     a.half = 1;
     if (kdt == DT_F32) {
-        EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, 0, 0};
+        EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, kv_unit_len(D), D.qw, kv_unit_vts(D),
+                        D.ptab, D.page, D.maxp, 0, 0, 0};
         launch_gemm(s, a, 1, e);
     } else {
-        EpiQkv<bf16_t> e{bias, rope, rows.slot, rows.pos, q, (bf16_t *)kc, (bf16_t *)vc, rows.n, D.Hq, D.Hkv, D.dh, D.max_seq, D.qw, D.vts, 0, 0};
+        EpiQkv<bf16_t> e{bias, rope, rows.slot, rows.pos, q, (bf16_t *)kc, (bf16_t *)vc, rows.n, D.Hq, D.Hkv, D.dh, kv_unit_len(D), D.qw, kv_unit_vts(D),
+                         D.ptab, D.page, D.maxp, 0, 0, 0};
         launch_gemm(s, a, 1, e);
     }
 }

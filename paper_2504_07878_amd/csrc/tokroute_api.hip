@@ -3,6 +3,7 @@
 // flags that feed them) and enqueues the fixed kernel sequence of a step on the caller's stream.
 #include "../../include/tokroute.h"
 #include "tr_internal.h"
+#include "kv_pages.h"
 
 #include <algorithm>
 #include <cmath>
@@ -24,6 +25,8 @@ struct Layout {
     size_t attn_part_floats;
     size_t attn_cnt;
     size_t tail_rpart, tail_rcnt;
+    size_t ptab;       // paged cache: device page table [max_batch][maxp]
+    int maxp, pool;    // pages per slot (table row length) and pages in the pool; 0 for the contiguous cache
     int max_rows, nslices;
     // matrix-core paths: repacked weights, packed activations, split-K partials.
     // mfma: K of the layers with a non-linear epilogue fits one workgroup (d <= 896), those layers are fused GEMMs and the
@@ -68,6 +71,11 @@ int check_config(const tr_config *c)
     if (c->hidden_tap != TR_POST_FINAL_NORM && c->hidden_tap != TR_PRE_FINAL_NORM) return TR_ERR_INVALID_ARG;
     if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return TR_ERR_INVALID_ARG;
     if ((long long)c->max_batch * c->max_seq > (1ll << 31)) return TR_ERR_CAPACITY;
+    if (c->kv_page < 0 || c->kv_pool_pages < 0 || (c->kv_page == 0 && c->kv_pool_pages != 0)) return TR_ERR_INVALID_ARG;
+    if (c->kv_page) {   // pages: a power of two of at least 32 positions; the matrix-core attention kernels (bf16 cache) walk them
+        if (c->kv_page < 32 || (c->kv_page & (c->kv_page - 1)) || c->kv_dtype != TR_BF16) return TR_ERR_SHAPE;
+        if ((long long)c->kv_pool_pages * c->kv_page > (1ll << 31)) return TR_ERR_CAPACITY;
+    }
     return TR_OK;
 }
 
@@ -76,8 +84,14 @@ Layout make_layout(const tr_config *c)
     Layout L{};
     const size_t kvw = (size_t)c->n_kv_heads * c->head_dim, qw = (size_t)c->n_q_heads * c->head_dim;
     const int vts = c->kv_dtype == TR_BF16 ? (c->max_seq + 31) / 32 * 32 : 0;   // bf16 cache: V transposed, rows padded to 32 positions
-    L.k_layer_bytes = (size_t)c->max_batch * c->max_seq * kvw * elem_size(c->kv_dtype);
-    L.v_layer_bytes = (size_t)c->max_batch * (vts ? vts : c->max_seq) * kvw * elem_size(c->kv_dtype);
+    L.maxp = c->kv_page ? (c->max_seq + c->kv_page - 1) / c->kv_page : 0;
+    L.pool = c->kv_page ? (c->kv_pool_pages ? c->kv_pool_pages : c->max_batch * L.maxp) : 0;
+    if (c->kv_page) {   // a pool of pages instead of one block per slot
+        L.k_layer_bytes = L.v_layer_bytes = (size_t)L.pool * c->kv_page * kvw * elem_size(c->kv_dtype);
+    } else {
+        L.k_layer_bytes = (size_t)c->max_batch * c->max_seq * kvw * elem_size(c->kv_dtype);
+        L.v_layer_bytes = (size_t)c->max_batch * (vts ? vts : c->max_seq) * kvw * elem_size(c->kv_dtype);
+    }
     L.max_rows = c->max_batch > c->max_seq ? c->max_batch : c->max_seq;   // a decode batch or one whole prompt
     L.nslices = (c->vocab + tail_slice_rows() - 1) / tail_slice_rows();
     const size_t R = (size_t)L.max_rows;
@@ -94,6 +108,7 @@ Layout make_layout(const tr_config *c)
     L.attn_part = take(L.attn_part_floats * 4);
     L.attn_cnt = take(R * c->n_kv_heads * 4);
     L.tail_rpart = take((size_t)c->max_batch * TAIL_ROUTER_PARTS * 4); L.tail_rcnt = take((size_t)c->max_batch * 4);
+    L.ptab = take((size_t)c->max_batch * (L.maxp ? L.maxp : 1) * 4);
     L.mfma = mfma_supported(c);
     L.split = split_supported(c);
     const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab) : 0;
@@ -145,6 +160,7 @@ struct tr_ctx {
     std::vector<LayerW> layers;
     const void *tok_emb, *head, *final_norm, *r_w1, *r_b1, *r_w2, *r_b2;
     std::vector<int> len;   // -1 = never prefilled
+    KvPages pages;          // paged cache only (c.kv_page > 0)
     float threshold;
     int mode;
     std::string err;
@@ -406,6 +422,34 @@ static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const
     return TR_OK;
 }
 
+// Paged cache: room for the writes [old_len[i], new_len[i]) of the listed slots. All or nothing: when the pool cannot
+// supply the pages, nothing has changed and TR_ERR_CAPACITY is returned. Otherwise the copies of shared pages that are about
+// to be written and the changed rows of the page table are enqueued on the stream, ahead of the kernels of the call.
+static int reserve_pages(tr_ctx *ctx, hipStream_t s, int n, const int *slots, const int *old_len, const int *new_len, const char *who)
+{
+    if (!ctx->c.kv_page) return TR_OK;
+    KvPages &P = ctx->pages;
+    if (P.demand(n, slots, old_len, new_len) > P.free_count()) return fail(ctx, TR_ERR_CAPACITY, "the page pool of the cache is exhausted");
+    std::vector<KvPages::Copy> copies;
+    const Layout &L = ctx->lay;
+    for (int i = 0; i < n; ++i) {
+        if (!P.grow(slots[i], old_len[i], new_len[i], copies)) continue;
+        // pageable source: the copy has left the host array when the call returns
+        const hipError_t e = hipMemcpyAsync(ctx->ws + L.ptab + (size_t)slots[i] * L.maxp * 4, P.row(slots[i]), (size_t)P.npages[(size_t)slots[i]] * 4,
+                                            hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return fail_hip(ctx, e, who);
+    }
+    const size_t page_bytes = L.k_layer_bytes / (size_t)L.pool;   // one page of one layer, K or V
+    for (const KvPages::Copy &c : copies)
+        for (int l = 0; l < ctx->D.L; ++l) {
+            char *k = static_cast<char *>(ctx->kc_layer(l)), *v = static_cast<char *>(ctx->vc_layer(l));
+            hipError_t e = hipMemcpyAsync(k + (size_t)c.to * page_bytes, k + (size_t)c.from * page_bytes, page_bytes, hipMemcpyDeviceToDevice, s);
+            if (e == hipSuccess) e = hipMemcpyAsync(v + (size_t)c.to * page_bytes, v + (size_t)c.from * page_bytes, page_bytes, hipMemcpyDeviceToDevice, s);
+            if (e != hipSuccess) return fail_hip(ctx, e, who);
+        }
+    return TR_OK;
+}
+
 extern "C" {
 
 size_t tr_workspace_bytes(const tr_config *cfg)
@@ -436,6 +480,9 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     D.V = cfg->vocab; D.qw = D.Hq * D.dh; D.kvw = D.Hkv * D.dh; D.G = D.Hq / D.Hkv; D.rh = cfg->router_hidden;
     D.max_batch = cfg->max_batch; D.max_seq = cfg->max_seq; D.eps = cfg->rms_eps;
     D.vts = cfg->kv_dtype == TR_BF16 ? (cfg->max_seq + 31) / 32 * 32 : 0;
+    D.page = cfg->kv_page; D.maxp = lay.maxp; D.units = cfg->kv_page ? lay.pool : cfg->max_batch;
+    D.ptab = reinterpret_cast<const int *>(ctx->ws + lay.ptab);
+    if (cfg->kv_page) ctx->pages.init(cfg->max_batch, cfg->kv_page, lay.maxp, lay.pool);
     bool aligned = true;
     auto chk = [&](const void *p) { if (p && (uintptr_t)p % 16) aligned = false; return p; };
     ctx->layers.resize((size_t)D.L);
@@ -471,6 +518,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.kc, 0, lay.rope - lay.kc);
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.attn_cnt, 0, (size_t)lay.max_rows * cfg->n_kv_heads * 4);
     if (e == hipSuccess) e = hipMemset(ctx->ws + lay.tail_rcnt, 0, (size_t)cfg->max_batch * 4);
+    if (e == hipSuccess) e = hipMemset(ctx->ws + lay.ptab, 0, (size_t)cfg->max_batch * (lay.maxp ? lay.maxp : 1) * 4);   // page 0: a valid page
     if (e == hipSuccess && (lay.mfma || lay.split)) {
         // one-time repack of the bf16 matrices into matrix-core tiles; q|k|v are concatenated, gate/up interleaved
         for (int l = 0; l < D.L; ++l) {
@@ -534,6 +582,7 @@ int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len)
     if (ctx->len[(size_t)slot] < 0) return fail(ctx, TR_ERR_STATE, "tr_seq_truncate: slot was never filled");
     if (new_len < 0 || new_len > ctx->len[(size_t)slot]) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_truncate: new_len outside [0, len]");
     ctx->len[(size_t)slot] = new_len;
+    if (ctx->c.kv_page) ctx->pages.shrink(slot, new_len);   // pages past the new length go back to the pool
     return TR_OK;
 }
 
@@ -560,6 +609,13 @@ int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, c
         if (tokens_flat[i] < 0 || tokens_flat[i] >= ctx->c.vocab) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: token out of range");
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (ctx->c.kv_page) {   // the slots start over: their pages go back to the pool, then the prompts take what they need
+        const KvPages before = ctx->pages;
+        std::vector<int> zero((size_t)n, 0), want((size_t)n);
+        for (int i = 0; i < n; ++i) { ctx->pages.shrink(slots[i], 0); want[(size_t)i] = offsets[i + 1] - offsets[i]; }
+        const int prc = reserve_pages(ctx, s, n, slots, zero.data(), want.data(), "tr_prefill: page table");
+        if (prc != TR_OK) { ctx->pages = before; return prc; }
+    }
     const int rc = ingest(ctx, s, n, slots, tokens_flat, offsets, false, out, 2, "tr_prefill");
     if (rc != TR_OK) return rc;
     for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] = offsets[i + 1] - offsets[i];
@@ -586,6 +642,12 @@ int tr_extend(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, co
         if (tokens_flat[i] < 0 || tokens_flat[i] >= ctx->c.vocab) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: token out of range");
 
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (ctx->c.kv_page) {
+        std::vector<int> from((size_t)n), to((size_t)n);
+        for (int i = 0; i < n; ++i) { from[(size_t)i] = ctx->len[(size_t)slots[i]]; to[(size_t)i] = from[(size_t)i] + offsets[i + 1] - offsets[i]; }
+        const int prc = reserve_pages(ctx, s, n, slots, from.data(), to.data(), "tr_extend: page table");
+        if (prc != TR_OK) return prc;
+    }
     const int rc = ingest(ctx, s, n, slots, tokens_flat, offsets, true, out, 1, "tr_extend");
     if (rc != TR_OK) return rc;
     for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] += offsets[i + 1] - offsets[i];
@@ -611,6 +673,12 @@ int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slot
     }
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const Layout &L = ctx->lay;
+    if (ctx->c.kv_page) {
+        std::vector<int> to((size_t)n);
+        for (int i = 0; i < n; ++i) to[(size_t)i] = pos[(size_t)i] + 1;
+        const int prc = reserve_pages(ctx, s, n, slots, pos.data(), to.data(), "tr_decode_step: page table");
+        if (prc != TR_OK) return prc;
+    }
     launch_setup_rows_embed(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos), ctx->c.dtype,
                             ctx->tok_emb, ctx->D.d, ctx->at<float>(L.x));
     const int pending = run_layers(ctx, s, n, max_ctx, false);
@@ -651,9 +719,19 @@ int tr_seq_fork(tr_ctx *ctx, void *hip_stream, int32_t src, int32_t dst)
     if (ctx->len[(size_t)src] < 0) return fail(ctx, TR_ERR_STATE, "tr_seq_fork: source slot was never filled");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const Layout &L = ctx->lay;
-    // a slot's keys (and values) of one layer are one contiguous block; whole blocks are copied, whatever the length
+    if (ctx->c.kv_page) {
+        // paged cache: the copy refers to the same pages; a page is copied only when one of the two is about to write into it
+        KvPages &P = ctx->pages;
+        P.shrink(dst, 0);
+        P.share(src, dst);
+        if (P.npages[(size_t)dst] > 0) {
+            const hipError_t e = hipMemcpyAsync(ctx->ws + L.ptab + (size_t)dst * L.maxp * 4, P.row(dst), (size_t)P.npages[(size_t)dst] * 4, hipMemcpyHostToDevice, s);
+            if (e != hipSuccess) return fail_hip(ctx, e, "tr_seq_fork: page table");
+        }
+    }
+    // contiguous cache: a slot's keys (and values) of one layer are one block; whole blocks are copied, whatever the length
     const size_t kb = L.k_layer_bytes / (size_t)ctx->c.max_batch, vb = L.v_layer_bytes / (size_t)ctx->c.max_batch;
-    for (int l = 0; l < ctx->D.L; ++l) {
+    for (int l = 0; l < (ctx->c.kv_page ? 0 : ctx->D.L); ++l) {
         char *k = static_cast<char *>(ctx->kc_layer(l)), *v = static_cast<char *>(ctx->vc_layer(l));
         hipError_t e = hipMemcpyAsync(k + (size_t)dst * kb, k + (size_t)src * kb, kb, hipMemcpyDeviceToDevice, s);
         if (e == hipSuccess) e = hipMemcpyAsync(v + (size_t)dst * vb, v + (size_t)src * vb, vb, hipMemcpyDeviceToDevice, s);
@@ -673,6 +751,13 @@ int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, con
     if (slot < 0 || slot >= ctx->c.max_batch) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_load_kv: slot out of range");
     if (len < 1 || len > ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_seq_load_kv: len outside [1, max_seq]");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (ctx->c.kv_page) {
+        const KvPages before = ctx->pages;
+        const int zero = 0, sl = slot, want = len;
+        ctx->pages.shrink(slot, 0);
+        const int prc = reserve_pages(ctx, s, 1, &sl, &zero, &want, "tr_seq_load_kv: page table");
+        if (prc != TR_OK) { ctx->pages = before; return prc; }
+    }
     launch_load_kv(s, ctx->c.kv_dtype, ctx->D, slot, len, k, v, ctx->ws + ctx->lay.kc, ctx->ws + ctx->lay.vc);
     launch_reset_counters(s, ctx->at<long long>(ctx->lay.counters), slot);
     hipError_t e = hipGetLastError();

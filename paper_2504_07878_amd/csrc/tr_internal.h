@@ -12,17 +12,37 @@ enum { DT_F32 = 0, DT_BF16 = 1 };
 
 struct Dims {
     int L, d, Hq, Hkv, dh, F, V, qw, kvw, G, rh, max_batch, max_seq;
-    int vts;   // bf16 cache: V is stored transposed in blocks of 32 positions, [slot][kv head][position / 32][dim][position % 32]
-               // (vts = max_seq rounded up to 32), so that the V^T operand of one block of 32 keys is dh*64 consecutive bytes;
-               // 0: V is stored like K, [slot][kv head][position][dim] (fp32 cache)
+    int vts;   // bf16 cache: V is stored transposed in blocks of 32 positions, [unit][kv head][position / 32][dim][position % 32]
+               // (vts = positions per storage unit rounded up to 32), so that the V^T operand of one block of 32 keys is dh*64
+               // consecutive bytes; 0: V is stored like K, [unit][kv head][position][dim] (fp32 cache)
     float eps;
+    // Storage units of the cache. Contiguous cache (page = 0): one unit per slot, max_seq positions long. Paged cache:
+    // a unit is a page of `page` positions (a power of two, multiple of 32) from a common pool of `units` pages; position
+    // p of a slot lives in page ptab[slot * maxp + p / page] at position p % page.
+    int page, maxp, units;
+    const int *ptab;
 };
 
-// element offset of V[slot][head][pos][dim] inside one layer's V cache
-__host__ __device__ inline size_t v_offset(const Dims &D, int slot, int head, int pos, int dim)
+__host__ __device__ inline int kv_unit_len(const Dims &D) { return D.page ? D.page : D.max_seq; }
+__host__ __device__ inline int kv_unit_vts(const Dims &D) { return D.page ? D.page : D.vts; }
+
+struct KvPlace { int unit, pos; };   // storage unit and position inside it
+__device__ __forceinline__ KvPlace kv_place(const Dims &D, int slot, int pos)
 {
-    return D.vts ? ((((size_t)slot * D.Hkv + head) * (D.vts >> 5) + (pos >> 5)) * D.dh + dim) * 32 + (pos & 31)
-                 : (((size_t)slot * D.Hkv + head) * D.max_seq + pos) * D.dh + dim;
+    if (!D.page) return KvPlace{slot, pos};
+    return KvPlace{D.ptab[(size_t)slot * D.maxp + pos / D.page], pos % D.page};
+}
+
+// element offsets of K[unit][head][pos][dim] and V[unit][head][pos][dim] inside one layer's cache (pos inside the unit)
+__host__ __device__ inline size_t k_offset(const Dims &D, int unit, int head, int pos, int dim)
+{
+    return (((size_t)unit * D.Hkv + head) * kv_unit_len(D) + pos) * D.dh + dim;
+}
+__host__ __device__ inline size_t v_offset(const Dims &D, int unit, int head, int pos, int dim)
+{
+    const int vts = kv_unit_vts(D);
+    return vts ? ((((size_t)unit * D.Hkv + head) * (vts >> 5) + (pos >> 5)) * D.dh + dim) * 32 + (pos & 31)
+               : k_offset(D, unit, head, pos, dim);
 }
 
 // Weights of one decoder layer (device pointers in the model's storage type).

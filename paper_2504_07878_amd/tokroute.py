@@ -31,7 +31,8 @@ class tr_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + [
         ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32), ("kv_dtype", C.c_int32),
         ("tie_lm_head", C.c_int32), ("router_hidden", C.c_int32), ("threshold", C.c_float), ("route_dir", C.c_int32),
-        ("hidden_tap", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("route_policy", C.c_int32)]
+        ("hidden_tap", C.c_int32), ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("route_policy", C.c_int32),
+        ("kv_page", C.c_int32), ("kv_pool_pages", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -123,7 +124,7 @@ class Model:
     """A tr_ctx over device copies of numpy weights (dict name -> array; per-layer names ``l{i}.wq`` ...)."""
 
     def __init__(self, shape: dict, weights: dict, max_batch: int, max_seq: int, route_dir=ROUTE_IF_BELOW,
-                 hidden_tap=POST_FINAL_NORM, device="cuda:0", route_policy=POLICY_MLP):
+                 hidden_tap=POST_FINAL_NORM, device="cuda:0", route_policy=POLICY_MLP, kv_page=0, kv_pool_pages=0):
         if not torch.cuda.is_available():
             raise RuntimeError("tokroute needs a GPU: no CPU path exists")
         self.lib = load_library()
@@ -131,7 +132,7 @@ class Model:
         s = self.shape = dict(shape)
         self.cfg = tr_config(s["n_layers"], s["d_model"], s["n_q_heads"], s["n_kv_heads"], s["head_dim"], s["d_ffn"], s["vocab"],
                              s["rms_eps"], s["rope_theta"], s["dtype"], s["kv_dtype"], s["tie_lm_head"], s["router_hidden"],
-                             s["threshold"], route_dir, hidden_tap, max_batch, max_seq, route_policy)
+                             s["threshold"], route_dir, hidden_tap, max_batch, max_seq, route_policy, kv_page, kv_pool_pages)
         dt, L = s["dtype"], s["n_layers"]
         self.dev = {k: (v if isinstance(v, torch.Tensor) else to_device(v, dt, device)) for k, v in weights.items()}
         self._arrs = []
