@@ -361,6 +361,14 @@ def main():
                                "hbm_roofline_tokens_per_s": HBM_PEAK_GBPS * 1e9 / b1_bytes,
                                "fraction_of_hbm_roofline": (n1 / dt1) / (HBM_PEAK_GBPS * 1e9 / b1_bytes),
                                "lmhead_avg_us": ms1 / max(l1, 1) * 1e3}
+        # the same 64 sequences on the paged cache (pages of 64 positions from a pool): what the page lookups cost
+        paged = tokroute.Model(s.asdict(), model.dev, B, MAX_SEQ, kv_page=64)
+        outp = paged.outputs(B)
+        paged.prefill(slots, prompts, outp)
+        np_steps = min(steps, 256)
+        dtp, _, _, _, _ = time_decode(paged, slots, toks, np_steps, args.warmup, outp)
+        extras["b64_paged_cache"] = {"tokens_per_s": B * np_steps / dtp, "ms_per_step": dtp / np_steps * 1e3, "steps": np_steps, "kv_page": 64}
+        del paged, outp
         # isolated routing tail, 256 rows
         tail_model = tokroute.Model(s.asdict(), model.dev, 256, 8)
         x = torch.from_numpy(synth.hidden_rows(SEED, "cfg4.x", 256, s.d_model, True)).cuda()

@@ -65,7 +65,7 @@ typedef struct tr_config {
     int32_t max_seq;       /* cache capacity per slot, in tokens */
     int32_t route_policy;  /* TR_POLICY_*; router_hidden is ignored unless TR_POLICY_MLP */
     int32_t kv_page;       /* 0: every slot owns max_seq contiguous cache positions. > 0: paged cache (the cache management
-                              for alternating prefill and decode stages that Section 2.3 of the paper asks for): positions
+                              for alternating prefill and decode stages that Section 3 of the paper asks for): positions
                               live in pages of kv_page tokens (a power of two >= 32; kv_dtype must be TR_BF16) taken from a
                               common pool as sequences grow and given back by tr_seq_truncate / tr_prefill; tr_seq_fork
                               shares pages and a shared page is copied only when one side is about to write into it */
@@ -155,7 +155,9 @@ int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len);
 
 /* Copy a slot's whole state (cache up to its length, length, counters) into another slot, after which the two
  * continue independently from the same prefix: a shared prompt, or a rollback point kept aside (the cache management
- * for alternating stages that Section 3 asks for). Enqueues device-to-device copies on the stream. */
+ * for alternating stages that Section 3 asks for). Contiguous cache: enqueues device-to-device copies of the slot's cache
+ * on the stream. Paged cache: no data moves, the copy refers to the same pages (TR_ERR_CAPACITY cannot occur here; a later
+ * write into a shared page takes one page from the pool for a private copy). */
 int tr_seq_fork(tr_ctx *ctx, void *hip_stream, int32_t src_slot, int32_t dst_slot);
 
 /* Overwrite a slot's cache with len tokens of given keys/values (DEVICE pointers in kv_dtype, layout
