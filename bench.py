@@ -246,7 +246,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "1700717b9f4ed1aa4932b85ded7ecf06dfa7acd92e8fc5417ca33ddc2e8ebed0", "fetch_bytes": 274427088, "write_bytes": 256000}
+LMHEAD_TRAFFIC = {"source_sha256": "92ff81fda97f3da97800694ddf58887a800f27e74930b0fff4b5cbee88c3915d", "fetch_bytes": 274406212, "write_bytes": 256000}
 
 
 def main():
