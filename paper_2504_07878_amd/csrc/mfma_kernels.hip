@@ -15,6 +15,7 @@
 //     then an epilogue functor consumes the 32x64 tile (rotary + cache append, SwiGLU, split-K partials, or the
 //     running softmax statistics of the LM head). Everything is deterministic.
 #include "tr_internal.h"
+#include <algorithm>
 #include <type_traits>
 
 namespace tr {
@@ -1375,6 +1376,19 @@ int gemm_partial_splits(int K, int N)
     int S, ksw, tpw;
     plan_partial(K / 16, (N + 31) / 32, 1, &S, &ksw, &tpw);   // one row group: the most splits any launch makes
     return S;
+}
+
+// floats of split-K partials a K x N layer may leave for any number of rows up to max_rows (few rows: many splits;
+// many rows: only as many as K needs)
+size_t gemm_partial_floats(int K, int N, int max_rows)
+{
+    size_t most = 0;
+    for (int groups = 1; groups <= (max_rows + 63) / 64; ++groups) {
+        int S, ksw, tpw;
+        plan_partial(K / 16, (N + 31) / 32, groups, &S, &ksw, &tpw);
+        most = std::max(most, (size_t)S * (size_t)std::min(max_rows, 64 * groups) * (size_t)N);
+    }
+    return most;
 }
 
 void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out)

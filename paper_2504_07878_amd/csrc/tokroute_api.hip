@@ -92,7 +92,9 @@ Layout make_layout(const tr_config *c)
         L.k_layer_bytes = (size_t)c->max_batch * c->max_seq * kvw * elem_size(c->kv_dtype);
         L.v_layer_bytes = (size_t)c->max_batch * (vts ? vts : c->max_seq) * kvw * elem_size(c->kv_dtype);
     }
-    L.max_rows = c->max_batch > c->max_seq ? c->max_batch : c->max_seq;   // a decode batch or one whole prompt
+    // rows of one pass over the weights: a decode batch, one whole prompt, and room to pack several prompts or catch-up
+    // segments into a pass (more 64-row groups per launch: the activations a workgroup keeps are reused for more tiles)
+    L.max_rows = std::max({c->max_batch, c->max_seq, std::min(8192, c->max_batch * c->max_seq)});
     L.nslices = (c->vocab + tail_slice_rows() - 1) / tail_slice_rows();
     const size_t R = (size_t)L.max_rows;
     // room for up to 32 context splits of a full decode batch
@@ -132,18 +134,16 @@ Layout make_layout(const tr_config *c)
         L.pack_d = take(groups * (d / 16) * 4 * 1024);
         L.pack_a = take(groups * (qw / 16) * 4 * 1024);
         L.pack_h = take(groups * (F / 16) * 4 * 1024);
-        // widest set of partial buffers any layer produces: splits x output columns
-        size_t pcols = (size_t)MAX_SPLITS * d;
+        // largest set of split-K partials any layer leaves, over all row counts of a pass
+        const int Ri = (int)R;
+        size_t part_floats = std::max(gemm_partial_floats((int)qw, (int)d, Ri), gemm_partial_floats((int)F, (int)d, Ri));
         if (L.split) {
             const size_t n_qkv = qw + 2 * kvw, n_gu = 2 * tiles(F) * 32;
-            pcols = (size_t)gemm_partial_splits((int)d, (int)n_qkv) * n_qkv;
-            pcols = std::max(pcols, (size_t)gemm_partial_splits((int)d, (int)n_gu) * n_gu);
-            pcols = std::max(pcols, (size_t)gemm_partial_splits((int)qw, (int)d) * d);
-            pcols = std::max(pcols, (size_t)gemm_partial_splits((int)F, (int)d) * d);
+            part_floats = std::max({part_floats, gemm_partial_floats((int)d, (int)n_qkv, Ri), gemm_partial_floats((int)d, (int)n_gu, Ri)});
         }
-        size_t part_bytes = pcols * R * 4;
         if (L.split_head)   // partial logits of a tail call: up to max_batch rows
-            part_bytes = std::max(part_bytes, (size_t)gemm_partial_splits((int)d, c->vocab) * c->vocab * c->max_batch * 4);
+            part_floats = std::max(part_floats, gemm_partial_floats((int)d, c->vocab, c->max_batch));
+        const size_t part_bytes = part_floats * 4;
         L.part = take(part_bytes);
     }
     L.total = off;

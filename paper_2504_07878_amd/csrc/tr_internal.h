@@ -145,6 +145,8 @@ void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void
 // layers with a non-linear epilogue are finished by a small kernel of their own.
 // number of partial buffers launch_gemm_partial will produce for a K x N layer
 int gemm_partial_splits(int K, int N);
+// floats of partial sums such a layer may produce for any number of rows up to max_rows
+size_t gemm_partial_floats(int K, int N, int max_rows);
 // [q|k|v] = sum of partials + bias, rotary embedding, q out, cache append
 void launch_qkv_finish(hipStream_t s, int kdt, const Dims &D, const float *part, int nsplit, const float *bias, Rows rows, const float2 *rope, float *q,
                        void *kc, void *vc);
