@@ -361,30 +361,37 @@ __device__ __forceinline__ void to_hi_lo(const float (&v)[8], bf16x8 &hi, bf16x8
 // running maximum m and sum l of its head column (both lanes of a head agree on m; l is per lane) and the
 // unnormalised output o, accumulator register rr of block db = dim db*32 + 8*(rr/4) + 4*hf + rr%4 of head j.
 // kc, vt: one layer's K cache and transposed V cache; PAGED: the row's keys live in pages looked up per block of 32 keys.
-template <int DH, bool PAGED>
+// MULTI: the 32 accumulator columns hold the heads of nq <= 32/G consecutive query rows of one sequence (column c = row c/G,
+// head c%G) instead of one row's heads in the first G columns: the keys and values of the context are fetched once for all of
+// them (the rows of a prompt). qrow is then the first of these rows, j1 the context of the LAST one; row i sees j1 - (nq-1) + i keys.
+template <int DH, bool PAGED, bool MULTI = false>
 struct AttnWave {
     static constexpr int KSQ = DH / 16, DB = DH / 32;
     float m, l;
     f32x16 o[DB];
 
     __device__ __forceinline__ void run(const Dims &D, const float *qrow /* q of this row */, const bf16_t *kc, const bf16_t *vt, int slot, int g,
-                                        int t_begin, int t_step, int j1)
+                                        int t_begin, int t_step, int j1, int nq = 1)
     {
         const int ulen = PAGED ? D.page : D.max_seq, uvts = PAGED ? D.page : D.vts;   // positions per storage unit
         const bf16_t *Kb = kc + ((size_t)slot * D.Hkv + g) * (size_t)ulen * DH, *Vb = vt + ((size_t)slot * D.Hkv + g) * (size_t)DH * uvts;   // contiguous cache
         [[maybe_unused]] const int t_last = (j1 - 1) & ~31;   // last block of 32 keys that holds a key of this row
         const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
+        const int rq = MULTI ? j / G : 0, hq = MULTI ? j % G : j;          // query row and head of this lane's column
+        const bool used = MULTI ? rq < nq : j < G;
+        const int j1c = MULTI ? j1 - (nq - 1) + rq : j1;                    // keys this column sees
+        const int j1min = MULTI ? j1 - (nq - 1) : j1;
         bf16x8 qh[KSQ], ql[KSQ];
         {
             const float scale = 1.0f / sqrtf((float)DH);
-            const float *qp = qrow + (size_t)(g * G + (j < G ? j : 0)) * DH + hf * 8;
+            const float *qp = qrow + (size_t)(used ? rq : 0) * D.qw + (size_t)(g * G + (used ? hq : 0)) * DH + hf * 8;
 #pragma unroll
             for (int ks = 0; ks < KSQ; ++ks) {
                 float v[8];
                 const float4 a = *reinterpret_cast<const float4 *>(qp + ks * 16), b = *reinterpret_cast<const float4 *>(qp + ks * 16 + 4);
                 v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[e] = j < G ? v[e] * scale : 0.f;
+                for (int e = 0; e < 8; ++e) v[e] = used ? v[e] * scale : 0.f;
                 to_hi_lo(v, qh[ks], ql[ks]);
             }
         }
@@ -437,22 +444,24 @@ struct AttnWave {
                     sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kv, ql[ks], sacc, 0, 0, 0);
                 }
                 // register rr of this lane is key t + 16*(rr/8) + 8*hf + rr%8 of head j
-                if (t + 32 > j1) {   // the last block of the row's context may be ragged
+                if (t + 32 > j1min) {   // the last block of a row's context may be ragged
 #pragma unroll
                     for (int rr = 0; rr < 16; ++rr)
-                        if (t + 16 * (rr >> 3) + 8 * hf + (rr & 7) >= j1) sacc[rr] = -INFINITY;
+                        if (t + 16 * (rr >> 3) + 8 * hf + (rr & 7) >= j1c) sacc[rr] = -INFINITY;
                 }
                 float bm = -INFINITY;
 #pragma unroll
                 for (int rr = 0; rr < 16; ++rr) bm = fmaxf(bm, sacc[rr]);
-                bm = fmaxf(bm, __shfl_xor(bm, 32, 64));      // key t is valid, so the pair maximum is finite
-                const float mn = fmaxf(m, bm);
+                bm = fmaxf(bm, __shfl_xor(bm, 32, 64));      // one row: key t is valid, so the pair maximum is finite
+                const float mraw = fmaxf(m, bm);
+                // a column whose row ends before this block and that has seen nothing yet keeps m = -inf; its exponentials take 0 as reference and vanish
+                const float mn = (MULTI && mraw == -INFINITY) ? 0.f : mraw;
                 const float corr = __expf(m - mn);           // 0 on the first block
                 float p[16], ps = 0.f;
 #pragma unroll
                 for (int rr = 0; rr < 16; ++rr) { p[rr] = __expf(sacc[rr] - mn); ps += p[rr]; }
                 l = l * corr + ps;
-                m = mn;
+                m = mraw;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -643,6 +652,77 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
         *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col + 4) = make_float4(o[4], o[5], o[6], o[7]);
     }
     if (pack) store_packed(pack + (size_t)(r >> 6) * (D.qw / 16) * ncb * 64, ncb, r & 63, col >> 3, o);
+}
+
+// Prompts and catch-up segments: one workgroup of 8 wavefronts per (block of up to 32/G consecutive query rows of one
+// sequence, kv head). The rows share every key and value they read (a wavefront's 32 accumulator columns hold the heads of
+// all the rows, see AttnWave MULTI), so a prompt's cache is walked once per block of rows instead of once per row.
+// Wavefront w walks the key blocks w, w + 8, ... of the whole context; the eight results are combined through LDS in a fixed
+// order. qblock[b] = first row * 8 + number of rows of block b (consecutive positions of one slot).
+template <int DH, bool PAGED>
+__global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_block_kernel(Dims D, const float *q, const bf16_t *kc, const bf16_t *vt, Rows rows,
+                                                                       const int *qblock, float *att, uint4 *pack, int ncb)
+{
+    constexpr int DB = DH / 32, NW = ATT_ROW_WAVES;
+    __shared__ float s_m[NW][32], s_l[NW][32];
+    __shared__ __attribute__((aligned(16))) float s_o[NW][32][DH];
+    const int code = qblock[blockIdx.x], r0 = code >> 3, nq = code & 7, g = blockIdx.y, wv = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
+    const int j1 = rows.pos[r0] + nq;   // context of the block's last row
+    const int slot = rows.slot[r0];
+    if (wv * 32 < j1) {
+        AttnWave<DH, PAGED, true> w;
+        w.run(D, q + (size_t)r0 * D.qw, kc, vt, slot, g, wv * 32, NW * 32, j1, nq);
+        const float lt = w.l + __shfl_xor(w.l, 32, 64);
+        if (j < nq * G) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+                    *reinterpret_cast<float4 *>(&s_o[wv][j][db * 32 + qd * 8 + hf * 4]) =
+                        make_float4(w.o[db][4 * qd], w.o[db][4 * qd + 1], w.o[db][4 * qd + 2], w.o[db][4 * qd + 3]);
+            if (hf == 0) { s_m[wv][j] = w.m; s_l[wv][j] = lt; }
+        }
+    }
+    __syncthreads();
+    const int live = min(NW, (j1 + 31) / 32);        // wavefronts that had keys
+    const int task = threadIdx.x;                    // (column = row and head, 8 dims)
+    if (task >= nq * G * (DH / 8)) return;
+    const int c = task / (DH / 8), d0 = (task % (DH / 8)) * 8, r = r0 + c / G, h = c % G;
+    float M = -INFINITY, L = 0.f, o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+    for (int w2 = 0; w2 < live; ++w2) M = fmaxf(M, s_m[w2][c]);     // finite: key 0 is seen by every row
+    for (int w2 = 0; w2 < live; ++w2) {
+        const float f = __expf(s_m[w2][c] - M);                     // 0 for a wavefront whose keys all lie past this row
+        L = fmaf(s_l[w2][c], f, L);
+        const float4 a = *reinterpret_cast<const float4 *>(&s_o[w2][c][d0]), b = *reinterpret_cast<const float4 *>(&s_o[w2][c][d0 + 4]);
+        o[0] = fmaf(a.x, f, o[0]); o[1] = fmaf(a.y, f, o[1]); o[2] = fmaf(a.z, f, o[2]); o[3] = fmaf(a.w, f, o[3]);
+        o[4] = fmaf(b.x, f, o[4]); o[5] = fmaf(b.y, f, o[5]); o[6] = fmaf(b.z, f, o[6]); o[7] = fmaf(b.w, f, o[7]);
+    }
+    const float inv = 1.0f / L;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] *= inv;
+    const int col = (g * G + h) * DH + d0;
+    if (att) {
+        *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col) = make_float4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<float4 *>(att + (size_t)r * D.qw + col + 4) = make_float4(o[4], o[5], o[6], o[7]);
+    }
+    if (pack) store_packed(pack + (size_t)(r >> 6) * (D.qw / 16) * ncb * 64, ncb, r & 63, col >> 3, o);
+}
+
+int attention_block_rows(const Dims &D) { return std::min(4, 32 / D.G); }
+
+void launch_attention_blocks(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, const int *qblock, int nblocks,
+                             float *att, void *pack, int ncb)
+{
+    const dim3 grid(nblocks, D.Hkv);
+    auto go = [&](auto kern) {
+        hipLaunchKernelGGL(kern, grid, dim3(64 * ATT_ROW_WAVES), 0, s, D, q, (const bf16_t *)kc, (const bf16_t *)vt, rows, qblock, pack ? nullptr : att,
+                           (uint4 *)pack, ncb);
+    };
+    if (D.dh == 64) { if (D.page) go(attn_block_kernel<64, true>); else go(attn_block_kernel<64, false>); }
+    else { if (D.page) go(attn_block_kernel<128, true>); else go(attn_block_kernel<128, false>); }
 }
 
 void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,

@@ -26,6 +26,7 @@ struct Layout {
     size_t attn_cnt;
     size_t tail_rpart, tail_rcnt;
     size_t ptab;       // paged cache: device page table [max_batch][maxp]
+    size_t qblock;     // query-row blocks of a pass (prompts, catch-up segments): first row * 8 + rows
     int maxp, pool;    // pages per slot (table row length) and pages in the pool; 0 for the contiguous cache
     int max_rows, nslices;
     // matrix-core paths: repacked weights, packed activations, split-K partials.
@@ -146,6 +147,7 @@ Layout make_layout(const tr_config *c)
         const size_t part_bytes = part_floats * 4;
         L.part = take(part_bytes);
     }
+    L.qblock = take(R * 4);
     L.total = off;
     return L;
 }
@@ -161,6 +163,7 @@ struct tr_ctx {
     const void *tok_emb, *head, *final_norm, *r_w1, *r_b1, *r_w2, *r_b2;
     std::vector<int> len;   // -1 = never prefilled
     KvPages pages;          // paged cache only (c.kv_page > 0)
+    int qblocks = 0;        // > 0: the rows of the current pass are grouped into this many query-row blocks (see ingest)
     float threshold;
     int mode;
     std::string err;
@@ -243,6 +246,16 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
     float *x = ctx->at<float>(L.x), *q = ctx->at<float>(L.q), *att = ctx->at<float>(L.att), *h = ctx->at<float>(L.h);
     const size_t attn_part_floats = R <= ctx->c.max_batch ? L.attn_part_floats : 0;
     if (embed) launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
+    // attention of one layer: blocks of query rows that share their keys when the pass was grouped that way, rows one by one otherwise
+    auto attend = [&](int l, const float *q_, Rows rows_, int max_ctx_, float *part_, size_t part_floats_, int *cnt_, float *att_, void *pack_, int ncb_,
+                      AttnPending *defer_) {
+        if (ctx->qblocks > 0) {
+            if (defer_) defer_->nchunks = 0;
+            launch_attention_blocks(s, D, q_, ctx->kc_layer(l), ctx->vc_layer(l), rows_, ctx->at<int>(L.qblock), ctx->qblocks, att_, pack_, ncb_);
+        } else {
+            launch_attention(s, ctx->c.kv_dtype, D, q_, ctx->kc_layer(l), ctx->vc_layer(l), rows_, max_ctx_, part_, part_floats_, cnt_, att_, pack_, ncb_, defer_);
+        }
+    };
     if (ctx->use_split(R)) {
         // wide model: every linear layer leaves split-K partials; rotary/cache append and SwiGLU are finished by kernels of their own
         const int ncb = mfma_ncb(R);
@@ -256,7 +269,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
             launch_prep(s, p);
             launch_gemm_partial(s, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), D.d, D.qw + 2 * D.kvw, R, part, &ns);
             launch_qkv_finish(s, ctx->c.kv_dtype, D, part, ns, ctx->bias(l), rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
-            launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
+            attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                              attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
             launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
             p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
@@ -272,7 +285,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
             launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
-            launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
+            attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                              attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, &pend);
             launch_oproj(s, ctx->c.dtype, D, w.wo, att, pend, R, x);
             launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
@@ -291,7 +304,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         launch_prep(s, p);
         launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
                         ctx->kc_layer(l), ctx->vc_layer(l));
-        launch_attention(s, ctx->c.kv_dtype, D, q, ctx->kc_layer(l), ctx->vc_layer(l), rows, max_ctx, ctx->at<float>(L.attn_part),
+        attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                          attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
         launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
         p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
@@ -387,7 +400,8 @@ static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const
                   const tr_out *out, int counter_mode, const char *who)
 {
     const Layout &L = ctx->lay;
-    struct Pass { std::vector<int> slot, pos, gather, out_slot; };
+    struct Pass { std::vector<int> slot, pos, gather, out_slot, qblock; };
+    const int block_rows = attention_block_rows(ctx->D);
     std::vector<Pass> passes;   // kept until the end: the uploads below read them
     passes.reserve((size_t)n);
     int i = 0;
@@ -399,6 +413,7 @@ static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const
             const int T = offsets[j + 1] - offsets[j], base = from_len ? ctx->len[(size_t)slots[j]] : 0;
             if (j > i && rows + T > L.max_rows) break;
             for (int t = 0; t < T; ++t) { ps.slot.push_back(slots[j]); ps.pos.push_back(base + t); }
+            for (int t = 0; t < T; t += block_rows) ps.qblock.push_back((rows + t) * 8 + std::min(block_rows, T - t));
             rows += T;
             ps.gather.push_back(rows - 1);
             ps.out_slot.push_back(slots[j]);
@@ -410,8 +425,13 @@ static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const
         if (e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.pos), ps.pos.data(), (size_t)rows * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.gather), ps.gather.data(), (size_t)(j - i) * 4, hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.out_slot), ps.out_slot.data(), (size_t)(j - i) * 4, hipMemcpyHostToDevice, s);
+        // bf16 cache and enough blocks of query rows to fill the chip: the rows of a block share the keys and values they read
+        const bool blocks = ctx->c.kv_dtype == TR_BF16 && ps.qblock.size() * (size_t)ctx->D.Hkv >= 256 && ps.qblock.size() < (size_t)rows;
+        if (blocks && e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.qblock), ps.qblock.data(), ps.qblock.size() * 4, hipMemcpyHostToDevice, s);
         if (e != hipSuccess) return fail_hip(ctx, e, who);
+        ctx->qblocks = blocks ? (int)ps.qblock.size() : 0;
         const int pending = run_layers(ctx, s, rows, max_ctx);
+        ctx->qblocks = 0;
         TailArgs t = tail_args(ctx, out, i, j - i);
         t.gather = ctx->at<int>(L.gather);
         t.slot = ctx->at<int>(L.out_slot);

@@ -115,6 +115,11 @@ void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w,
 // workgroups that share a row when its context is split)
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
                       float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
+// bf16 cache, many rows of few sequences (prompts, catch-up segments): blocks of up to attention_block_rows() consecutive query
+// rows of one slot share the keys and values they read. qblock[b] = first row * 8 + rows in block b (device array).
+int attention_block_rows(const Dims &D);
+void launch_attention_blocks(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, const int *qblock, int nblocks,
+                             float *att, void *pack, int ncb);
 void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const void *kc, const void *vt, Rows rows, int max_ctx, float *part,
                            size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
 void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb);
