@@ -180,8 +180,9 @@ struct tr_ctx {
     char *wt(int l, size_t which) const { return ws + lay.wt_layers + (size_t)l * lay.wt_layer_stride + which; }
     float *bias(int l) const { return reinterpret_cast<float *>(ws + lay.bias + (size_t)l * lay.bias_stride); }
     bool use_mfma(int rows) const { return lay.mfma && rows > GEMV_MAX_ROWS; }
-    // wide models: the streaming kernels take 4 rows per pass over the weights, so the matrix cores win from 5 rows on
-    bool use_split(int rows) const { return lay.split && rows > 4; }
+    // wide models: the streaming kernels slow down with the rows (7B-class gate/up: 46 us at 1 row, 52 at 2, 69 at 4) while the
+    // matrix-core path is nearly flat in them; measured on the 7B-class model it wins from 3 rows on
+    bool use_split(int rows) const { return lay.split && rows > 2; }
 };
 
 namespace {
@@ -323,7 +324,7 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     const Layout &L = ctx->lay;
     hipEvent_t e0, e1, e2;
     next_events(ctx, &e0, &e1, &e2);
-    if (ctx->lay.split_head && t.n > 4) {
+    if (ctx->lay.split_head && t.n > 2) {
         // wide model, more rows than one pass of the streaming head takes: final norm + pack, the head as split-K partial
         // logits on the matrix cores, softmax statistics per vocabulary slice from the partials
         PrepArgs p{};
