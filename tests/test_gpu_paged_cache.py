@@ -161,6 +161,34 @@ def test_paged_other_paths(tr, tro):
     assert ex <= 3
 
 
+@pytest.mark.parametrize("B", [2, 33])
+def test_paged_and_contiguous_caches_give_identical_bits(tr, B):
+    """Paging changes where keys and values are stored, not one arithmetic operation: logits, scores and confidences of a
+    paged and a contiguous context must agree bit for bit through prefill, decode steps, a catch-up step and a fork."""
+    s, w = small()
+    max_seq = 500
+    a = tr.Model(s.asdict(), w, B + 1, max_seq); b = tr.Model(s.asdict(), w, B + 1, max_seq, kv_page=32)
+    lens = synth.prompt_lengths(SEED, f"pgb.{B}", B, 1, 300)
+    prompts = [synth.prompt_tokens(SEED, f"pgb.{B}.{i}", int(n), s.vocab) for i, n in enumerate(lens)]
+    slots = list(range(B))
+
+    def same(x, y, what):
+        for f in ("logits", "score", "conf", "token", "flag", "hidden"):
+            assert np.array_equal(getattr(x, f), getattr(y, f)), f"{what}: {f}"
+
+    x = a.prefill(slots, prompts, want_logits=True).cpu(); y = b.prefill(slots, prompts, want_logits=True).cpu()
+    same(x, y, "prefill")
+    for step in range(5):
+        toks = x.token.copy()
+        x = a.decode_step(slots, toks, want_logits=True).cpu(); y = b.decode_step(slots, toks, want_logits=True).cpu()
+        same(x, y, f"step {step}")
+    for m in (a, b):
+        m.seq_fork(0, B)
+    segs = [synth.prompt_tokens(SEED, f"pgb.{B}.seg{i}", 1 + 5 * (i % 7), s.vocab) for i in range(B + 1)]
+    x = a.extend(slots + [B], segs, want_logits=True).cpu(); y = b.extend(slots + [B], segs, want_logits=True).cpu()
+    same(x, y, "catch-up after a fork")
+
+
 def test_paged_config_is_validated(tr):
     s, w = small()
     for bad in (dict(kv_page=48), dict(kv_page=16), dict(kv_page=0, kv_pool_pages=4)):
