@@ -918,6 +918,11 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     int M, V;
     float mx, sum;
     int idx, bx, grp, nwg;   // nwg: workgroups that own tiles (the grid may be padded)
+    // The tiles from index vt on are not vocabulary rows but the hidden units of the router's first layer (its weight
+    // rows are appended to the head matrix: same activations, so the product comes for free inside this launch): their
+    // raw sums go to r1[row][unit] and are kept out of the softmax statistics. vt = INT_MAX: no such tiles.
+    float *r1;
+    int vt, r1_stride;
     __device__ void block(int b, int g) { bx = b; grp = g; }
     __device__ void begin() { mx = -INFINITY; sum = 0.f; idx = 0x7fffffff; }
     __device__ void row(int) {}
@@ -930,21 +935,28 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
             for (int e = 0; e < 8; ++e)
                 if (m < M && n0 + e < V) logits[(size_t)m * V + n0 + e] = vin[e];
         }
+        const bool router_tile = t >= vt;   // uniform over the workgroup
         float v[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = (!RAGGED || n0 + e < V) ? vin[e] : -INFINITY;   // a tile always holds at least one real row
+        for (int e = 0; e < 8; ++e) v[e] = ((!RAGGED || n0 + e < V) && !router_tile) ? vin[e] : -INFINITY;   // a vocabulary tile holds at least one real row
         float lm = v[7];
         int li = 7;
 #pragma unroll
         for (int e = 6; e >= 0; --e)
             if (v[e] >= lm) { lm = v[e]; li = e; }                  // descending scan: the lowest index wins ties
         const float nm = fmaxf(mx, lm);
+        const float ref = nm == -INFINITY ? 0.f : nm;               // nothing but router tiles so far: every exponential below is 0
         idx = lm > mx ? n0 + li : idx;                              // strict: earlier tiles win ties
         float add = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) add += __expf(v[e] - nm);       // exp(-inf) = 0 for the rows past the vocabulary
-        sum = fmaf(sum, __expf(mx - nm), add);                      // mx = -inf before the first tile: factor 0 on a zero sum
+        for (int e = 0; e < 8; ++e) add += __expf(v[e] - ref);      // exp(-inf) = 0 for the rows past the vocabulary
+        sum = fmaf(sum, __expf(mx - ref), add);                     // mx = -inf before the first tile: factor 0 on a zero sum
         mx = nm;
+        if (router_tile && m < M) {
+            float *dst = r1 + (size_t)m * r1_stride + (t - vt) * 32 + i0;
+            *reinterpret_cast<float4 *>(dst) = make_float4(vin[0], vin[1], vin[2], vin[3]);
+            *reinterpret_cast<float4 *>(dst + 4) = make_float4(vin[4], vin[5], vin[6], vin[7]);
+        }
     }
     // the four threads that share a batch row (one per band of 8 features) merge through LDS; row_local: the thread's
     // batch row inside its 64-row group, band: which 8 features of every tile it held
@@ -1515,21 +1527,23 @@ void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void
     }
 }
 
-int lmhead_mfma_wgs(int V)
+int lmhead_mfma_wgs(int V, int router_tiles)
 {
-    const int n_tiles = (V + 31) / 32;
+    const int n_tiles = (V + 31) / 32 + router_tiles;
     const int tpw = (n_tiles + 255) / 256;
     return (n_tiles + tpw - 1) / tpw;
 }
 
-void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits)
+void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits, float *r1, int router_tiles)
 {
     GemmArgs a{};
-    a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.V + 31) / 32; a.M = M;
+    const int vt = (D.V + 31) / 32;
+    a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = vt + router_tiles; a.M = M;
     a.tiles_per_wg = (a.n_tiles + 255) / 256;
     a.remap_groups = M > 64 ? (M + 63) / 64 : 0;
     auto go = [&](auto e) {
-        e.part = (float4 *)part; e.logits = logits; e.M = M; e.V = D.V; e.nwg = lmhead_mfma_wgs(D.V);
+        e.part = (float4 *)part; e.logits = logits; e.M = M; e.V = D.V; e.nwg = lmhead_mfma_wgs(D.V, router_tiles);
+        e.r1 = r1; e.vt = router_tiles > 0 ? vt : 0x7fffffff; e.r1_stride = router_tiles * 32;
         launch_gemm(s, a, 1, e);
     };
     if (logits) { if (D.V % 32) go(EpiLmHead<true, true>{}); else go(EpiLmHead<true, false>{}); }

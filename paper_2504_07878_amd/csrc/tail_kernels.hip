@@ -201,7 +201,8 @@ __global__ __launch_bounds__(TF_THREADS) void tail_final_kernel(int d, int rh, T
             for (int h = 0; h < 2; ++h)
                 rw[q][h].load(w1 + (size_t)min(j0 + q * TF_WAVES, rh - 1) * d + min(k0 + h * 512 + lane * 8, d - 8));
     };
-    if (mlp) {
+    const bool given = mlp && t.r1 != nullptr;   // the first layer's sums were computed by the LM-head launch
+    if (mlp && !given) {
         for (int k = tid; k < d; k += TF_THREADS) s_u[k] = u[k];
         issue(j_lo + wave, 0);
     }
@@ -246,7 +247,16 @@ __global__ __launch_bounds__(TF_THREADS) void tail_final_kernel(int d, int rh, T
         a = t_wave_sum(a);
         if (lane == 0) s_ws[1][wave] = a;
     }
-    if (mlp) {
+    if (given) {
+        const WT *b1 = (const WT *)t.r_b1, *w2 = (const WT *)t.r_w2;
+        float a = 0.f;
+        for (int j = tid; j < rh; j += TF_THREADS) {
+            const float hb = t.r1[(size_t)i * t.r1_stride + j] + (b1 ? t_widen(b1, j) : 0.f);
+            a = fmaf(t_widen(w2, j), hb > 0.f ? hb : 0.f, a);
+        }
+        a = t_wave_sum(a);
+        if (lane == 0) s_ws[1][wave] = a;
+    } else if (mlp) {
         const WT *b1 = (const WT *)t.r_b1, *w2 = (const WT *)t.r_w2;
         __syncthreads();   // s_u is complete
         for (int j0 = j_lo + wave; j0 < j_hi; j0 += RQ * TF_WAVES) {
@@ -345,7 +355,7 @@ void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
     // the MLP router's hidden units go to up to TAIL_ROUTER_PARTS workgroups per row, at least 64 units each, as long
     // as all workgroups of the launch fit the chip at once (beyond that the split only adds the exchange)
     int parts = 1;
-    if (t.policy == 0 && D.rh > 0 && t.rpart && t.rcnt) parts = std::max(1, std::min({TAIL_ROUTER_PARTS, (D.rh + 63) / 64, 256 / t.n}));
+    if (t.policy == 0 && D.rh > 0 && t.rpart && t.rcnt && !t.r1) parts = std::max(1, std::min({TAIL_ROUTER_PARTS, (D.rh + 63) / 64, 256 / t.n}));
     if (wdt == DT_F32) hipLaunchKernelGGL(tail_final_kernel<float>, dim3(t.n, parts), dim3(TF_THREADS), 0, s, D.d, D.rh, t);
     else hipLaunchKernelGGL(tail_final_kernel<bf16_t>, dim3(t.n, parts), dim3(TF_THREADS), 0, s, D.d, D.rh, t);
 }

@@ -26,6 +26,8 @@ struct Layout {
     size_t attn_cnt;
     size_t tail_rpart, tail_rcnt;
     size_t ptab;       // paged cache: device page table [max_batch][maxp]
+    size_t r1;         // sums of the router's first layer, [max_batch][router_tiles * 32], written by the LM-head launch
+    int router_tiles;  // tiles of router weight rows appended to the repacked head matrix (0: the merge kernel computes the router itself)
     size_t qblock;     // query-row blocks of a pass (prompts, catch-up segments): first row * 8 + rows
     int maxp, pool;    // pages per slot (table row length) and pages in the pool; 0 for the contiguous cache
     int max_rows, nslices;
@@ -114,7 +116,10 @@ Layout make_layout(const tr_config *c)
     L.ptab = take((size_t)c->max_batch * (L.maxp ? L.maxp : 1) * 4);
     L.mfma = mfma_supported(c);
     L.split = split_supported(c);
-    const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab) : 0;
+    // fused matrix-core tail with the MLP router on the normalised hidden state: the router's first layer rides along in the LM-head launch
+    L.router_tiles = (L.mfma && c->route_policy == TR_POLICY_MLP && c->router_hidden > 0 && c->hidden_tap == TR_POST_FINAL_NORM) ? (c->router_hidden + 31) / 32 : 0;
+    L.r1 = take((size_t)c->max_batch * (L.router_tiles ? L.router_tiles : 1) * 32 * 4);
+    const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab, L.router_tiles) : 0;
     L.tail_part = take((size_t)(L.nslices > head_wgs ? L.nslices : head_wgs) * c->max_batch * sizeof(float4));
     if (L.mfma || L.split) {
         const size_t d = (size_t)c->d_model, F = (size_t)c->d_ffn;
@@ -127,7 +132,7 @@ Layout make_layout(const tr_config *c)
         L.wt_d = o2;   o2 += tiles(d) * tile_f;
         L.wt_layer_stride = align_up(o2);
         L.wt_layers = take(L.wt_layer_stride * c->n_layers);
-        L.wt_head = (L.mfma || (L.split && c->vocab % 8 == 0)) ? take(tiles((size_t)c->vocab) * tile_d) : 0;
+        L.wt_head = (L.mfma || (L.split && c->vocab % 8 == 0)) ? take((tiles((size_t)c->vocab) + L.router_tiles) * tile_d) : 0;
         L.split_head = L.split && c->vocab % 8 == 0;
         L.bias_stride = align_up((qw + 2 * kvw) * 4);
         L.bias = take(L.bias_stride * c->n_layers);
@@ -364,8 +369,9 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     t.x = x + (size_t)row0 * D.d;
     if (e0) (void)hipEventRecord(e0, s);
     // the head is streamed by the matrix-core kernel for any row count: one row costs the same bytes as 32
-    t.nslices = lmhead_mfma_wgs(D.V);
-    launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits);
+    t.nslices = lmhead_mfma_wgs(D.V, L.router_tiles);
+    launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits, ctx->at<float>(L.r1), L.router_tiles);
+    if (L.router_tiles) { t.r1 = ctx->at<float>(L.r1); t.r1_stride = L.router_tiles * 32; }
     if (e1) (void)hipEventRecord(e1, s);
     if (e2) (void)hipEventRecord(e2, s);
     launch_tail_final(s, ctx->c.dtype, D, t);
@@ -556,6 +562,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
             launch_widen_bias(nullptr, lw.bv, D.kvw, ctx->bias(l) + D.qw + D.kvw);
         }
         if (lay.mfma || lay.split_head) launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1, 0);
+        if (lay.router_tiles) launch_repack(nullptr, ctx->r_w1, D.rh, D.d, ctx->ws + lay.wt_head, (D.V + 31) / 32, 1, 0);
         e = hipMemset(ctx->ws + lay.pack_d, 0, lay.part - lay.pack_d);   // padding rows of the packed activations stay zero
         if (e == hipSuccess) e = hipDeviceSynchronize();
         if (e == hipSuccess) e = hipGetLastError();

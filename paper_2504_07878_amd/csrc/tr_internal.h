@@ -99,6 +99,8 @@ struct TailArgs {
     int policy;              // TR_POLICY_*
     float *rpart;            // [n][TAIL_ROUTER_PARTS]: partial pre-activations of the router's output unit, one per workgroup of a row
     int *rcnt;               // [n]: arrival counters of those workgroups, zero before and after every launch (NULL: one workgroup per row)
+    const float *r1;         // [n][r1_stride]: sums W1 . hidden of the router's first layer, computed by the LM-head launch (NULL: computed here)
+    int r1_stride;
 };
 constexpr int TAIL_ROUTER_PARTS = 4;
 
@@ -161,7 +163,8 @@ void launch_swiglu_finish(hipStream_t s, const Dims &D, const float *part, int n
 // writes slice_part[slice][m] = {max, lowest argmax, sum-exp} (what the tail's final kernel merges) and, when asked, the logits.
 constexpr int LMHEAD_FINISH_COLS = 2048;
 void launch_lmhead_finish(hipStream_t s, const float *part, int nsplit, int M, int V, float *slice_part, float *logits);
-int lmhead_mfma_wgs(int V);
-void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits);
+int lmhead_mfma_wgs(int V, int router_tiles);
+// router_tiles > 0: the matrix holds that many extra tiles after the vocabulary (the router's first layer); their raw sums go to r1[row][router_tiles * 32]
+void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits, float *r1, int router_tiles);
 
 }  // namespace tr
