@@ -310,7 +310,7 @@ def main():
     ctx_sum = sum(int(n) + i % room for n in base for i in range(steps))        # sum over steps and sequences of cached tokens read
     step_bytes = weight_bytes_per_step(s) + (ctx_sum + B * steps) * kvb / steps
     roof_tok_s = B / (step_bytes / (HBM_PEAK_GBPS * 1e9))
-    lm_bytes = 2 * s.vocab * s.d_model
+    lm_bytes = 2 * (s.vocab + s.router_hidden) * s.d_model   # the head matrix and, in the same launch, the rows of the router's first layer
     lm_avg_s = lm_ms / 1e3 / max(lm_n, 1)
     result = {
         # the metric names three figures: value is the batch-64 one (the workload below); batch 1 and the isolated tail are in extras
