@@ -382,7 +382,7 @@ def main():
             tail_model.tail(x, outt)
         torch.cuda.synchronize()
         dtt = (time.perf_counter() - t0) / reps
-        tail_bytes = lm_bytes + 256 * s.d_model * 4 + 2 * (s.router_hidden * s.d_model + s.router_hidden) + 256 * 16
+        tail_bytes = lm_bytes + 256 * s.d_model * 4 + 2 * 2 * s.router_hidden + 256 * 16   # head + router layer 1 (in lm_bytes), rows in, router biases and output unit, results out
         # at 256 rows the head is a 256 x 151936 x 896 product with exact (hi + lo bf16) activations: twice the flops of a plain bf16 product
         tail_flops = 2 * 2.0 * 256 * s.vocab * s.d_model
         extras["tail_b256"] = {"GB_per_s": tail_bytes / dtt / 1e9, "us_per_call": dtt * 1e6, "algorithmic_bytes": tail_bytes,
