@@ -97,6 +97,11 @@ typedef struct tr_out {
     float *logits;  /* [n][vocab] full logits, for debugging and parity checks; costs a write of n*vocab*4 bytes */
 } tr_out;
 
+/* General: a context is not thread-safe (the caller serialises the calls on one context; different contexts are
+ * independent). With a paged cache (kv_page > 0) tr_prefill, tr_decode_step, tr_extend and tr_seq_load_kv also return
+ * TR_ERR_CAPACITY when the page pool cannot supply the pages the call needs; like every error, that leaves all state
+ * (cache, page tables, lengths, counters) as it was. */
+
 /* Bytes of device workspace tr_create needs for this configuration (cache, tables, scratch); 0 if the
  * configuration is invalid. */
 size_t tr_workspace_bytes(const tr_config *cfg);
