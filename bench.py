@@ -361,6 +361,25 @@ def main():
                                "hbm_roofline_tokens_per_s": HBM_PEAK_GBPS * 1e9 / b1_bytes,
                                "fraction_of_hbm_roofline": (n1 / dt1) / (HBM_PEAK_GBPS * 1e9 / b1_bytes),
                                "lmhead_avg_us": ms1 / max(l1, 1) * 1e3}
+        # free-running greedy generation of one sequence: each step's token read back by the host and passed in again, against
+        # the steps chained on the device (tr_decode_step_dev: the token output of a step is the next step's input)
+        model.seq_truncate(0, 256)
+        nf = min(steps, 256)
+        o1 = model.decode_step([0], toks[0, :1], out1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(nf):
+            o1 = model.decode_step([0], o1.cpu(("token",)).token, out1)
+        torch.cuda.synchronize()
+        dt_host = time.perf_counter() - t0
+        model.seq_truncate(0, 257)
+        t0 = time.perf_counter()
+        for _ in range(nf):
+            model.decode_step_dev([0], out1.token, out1)
+        torch.cuda.synchronize()
+        dt_dev = time.perf_counter() - t0
+        extras["b1_free_running"] = {"host_fed_tokens_per_s": nf / dt_host, "device_fed_tokens_per_s": nf / dt_dev,
+                                     "host_fed_ms_per_step": dt_host / nf * 1e3, "device_fed_ms_per_step": dt_dev / nf * 1e3, "steps": nf}
         # the same 64 sequences on the paged cache (pages of 64 positions from a pool): what the page lookups cost
         paged = tokroute.Model(s.asdict(), model.dev, B, MAX_SEQ, kv_page=64)
         outp = paged.outputs(B)

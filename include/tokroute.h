@@ -134,6 +134,13 @@ int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, c
 int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens,
                    const tr_out *out);
 
+/* The same step with the input tokens in DEVICE memory (int32 [n]), e.g. the token field of the previous step's tr_out:
+ * a caller that does not need the flags on the host every step (small_only mode, or between two routing decisions it
+ * has already taken) can enqueue many steps without a device-to-host copy in between. The tokens cannot be checked on the
+ * host: values outside [0, vocab) are clamped into that range by the kernel. slots is a HOST array as above. */
+int tr_decode_step_dev(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens_dev,
+                       const tr_out *out);
+
 /* Catch-up ("extend") step: each listed slot ingests the T >= 1 tokens of its segment, which another model
  * produced (Section 3.2, Figure 2: several rounds of prefill and decode inside one request; the prototype of
  * Section 4.1 re-runs the whole prefix instead), at positions len .. len+T-1 over its existing cache, and

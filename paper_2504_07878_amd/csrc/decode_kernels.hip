@@ -344,34 +344,37 @@ __global__ void embed_kernel(const WT *E, const int *tok, int d, float *x)
 }
 
 // Row metadata from the kernel arguments and the embedding lookup of the same rows in one launch (a decode step's first kernel)
+// dev_tok != NULL: the tokens come from device memory (e.g. the previous step's output) instead of the arguments; they cannot
+// be checked on the host, so values outside the vocabulary are clamped into it.
 template <typename WT>
-__global__ void setup_embed_kernel(SetupArgs a, int *d_slot, int *d_tok, int *d_pos, int base, const WT *E, int d, float *x)
+__global__ void setup_embed_kernel(SetupArgs a, int *d_slot, int *d_tok, int *d_pos, int base, const WT *E, int d, float *x, const int *dev_tok, int vocab)
 {
     const int i = blockIdx.x, r = base + i;
+    const int tok = dev_tok ? min(max(dev_tok[r], 0), vocab - 1) : a.tok[i];
     if (threadIdx.x == 0) {
         d_slot[r] = a.slot[i];
-        d_tok[r] = a.tok[i];
+        d_tok[r] = tok;
         d_pos[r] = a.pos[i];
     }
-    const WT *e = E + (size_t)a.tok[i] * d;
+    const WT *e = E + (size_t)tok * d;
     for (int j = threadIdx.x; j < d; j += blockDim.x) x[(size_t)r * d + j] = widen(e, j);
 }
 
 void launch_setup_rows_embed(hipStream_t s, int n, const int *slots, const int *toks, const int *poss, int *d_slot, int *d_tok, int *d_pos, int wdt,
-                             const void *E, int d, float *x)
+                             const void *E, int d, float *x, const int *dev_toks, int vocab)
 {
     for (int base = 0; base < n; base += 256) {
         SetupArgs a;
         a.n = n - base < 256 ? n - base : 256;
         for (int i = 0; i < a.n; ++i) {
             a.slot[i] = slots[base + i];
-            a.tok[i] = toks[base + i];
+            a.tok[i] = toks ? toks[base + i] : 0;
             a.pos[i] = poss[base + i];
         }
         if (wdt == DT_F32)
-            hipLaunchKernelGGL(setup_embed_kernel<float>, dim3(a.n), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base, (const float *)E, d, x);
+            hipLaunchKernelGGL(setup_embed_kernel<float>, dim3(a.n), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base, (const float *)E, d, x, dev_toks, vocab);
         else
-            hipLaunchKernelGGL(setup_embed_kernel<bf16_t>, dim3(a.n), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base, (const bf16_t *)E, d, x);
+            hipLaunchKernelGGL(setup_embed_kernel<bf16_t>, dim3(a.n), dim3(256), 0, s, a, d_slot, d_tok, d_pos, base, (const bf16_t *)E, d, x, dev_toks, vocab);
     }
 }
 

@@ -684,15 +684,17 @@ int tr_extend(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, co
     return TR_OK;
 }
 
-int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens, const tr_out *out)
+// one decode step; the input tokens are either a host array (checked here) or a device array (clamped by the kernel)
+static int decode_step_impl(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens, const int32_t *dev_tokens,
+                            const tr_out *out)
 {
     if (!ctx) return TR_ERR_INVALID_ARG;
-    if (!slots || !in_tokens || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: null argument");
+    if (!slots || (!in_tokens && !dev_tokens) || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: null argument");
     if (!slots_ok(ctx, n, slots)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: bad slot list");
     int max_ctx = 0;
     std::vector<int> pos((size_t)n);
     for (int i = 0; i < n; ++i) {
-        if (in_tokens[i] < 0 || in_tokens[i] >= ctx->c.vocab) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: token out of range");
+        if (in_tokens && (in_tokens[i] < 0 || in_tokens[i] >= ctx->c.vocab)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: token out of range");
         const int len = ctx->len[(size_t)slots[i]];
         if (len < 0) return fail(ctx, TR_ERR_STATE, "tr_decode_step: slot was never prefilled");
         if (len >= ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_decode_step: slot is full");
@@ -708,7 +710,7 @@ int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slot
         if (prc != TR_OK) return prc;
     }
     launch_setup_rows_embed(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos), ctx->c.dtype,
-                            ctx->tok_emb, ctx->D.d, ctx->at<float>(L.x));
+                            ctx->tok_emb, ctx->D.d, ctx->at<float>(L.x), dev_tokens, ctx->c.vocab);
     const int pending = run_layers(ctx, s, n, max_ctx, false);
     TailArgs t = tail_args(ctx, out, 0, n);
     t.gather = nullptr;
@@ -719,6 +721,18 @@ int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slot
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_decode_step: launch");
     for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] += 1;
     return TR_OK;
+}
+
+int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens, const tr_out *out)
+{
+    if (!in_tokens) return ctx ? fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: null argument") : TR_ERR_INVALID_ARG;
+    return decode_step_impl(ctx, hip_stream, n, slots, in_tokens, nullptr, out);
+}
+
+int tr_decode_step_dev(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens_dev, const tr_out *out)
+{
+    if (!in_tokens_dev) return ctx ? fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step_dev: null argument") : TR_ERR_INVALID_ARG;
+    return decode_step_impl(ctx, hip_stream, n, slots, nullptr, in_tokens_dev, out);
 }
 
 int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out)

@@ -110,7 +110,7 @@ void launch_iota_rows(hipStream_t s, int n, int slot, int base, int *d_slot, int
 void launch_embed(hipStream_t s, int wdt, const void *E, const int *tok, int R, int d, float *x);
 // row metadata from host arrays (passed in the kernel arguments, 256 rows per launch) and the embedding lookup of those rows
 void launch_setup_rows_embed(hipStream_t s, int n, const int *slots, const int *toks, const int *poss, int *d_slot, int *d_tok, int *d_pos, int wdt,
-                             const void *E, int d, float *x);
+                             const void *E, int d, float *x, const int *dev_toks, int vocab);   // dev_toks: device tokens [n] instead of toks (then NULL)
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope,
                 float *q, void *kc, void *vc);
 // cnt: one zero-initialised int per (row, kv head), left at zero again by every launch (arrival counters of the

@@ -22,7 +22,7 @@ ROUTE_IF_BELOW, ROUTE_IF_ABOVE = 0, 1
 POLICY_MLP, POLICY_CONFIDENCE, POLICY_LINEAR = 0, 1, 2
 POST_FINAL_NORM, PRE_FINAL_NORM = 0, 1
 
-EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_extend", "tr_tail", "tr_set_threshold",
+EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_decode_step_dev", "tr_extend", "tr_tail", "tr_set_threshold",
            "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_fork", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable",
            "tr_profile_read", "tr_last_error"]
 
@@ -66,6 +66,7 @@ def load_library():
         L.tr_prefill.argtypes = [vp, vp, i32, vp, vp, vp, C.POINTER(tr_out)]
         L.tr_extend.argtypes = [vp, vp, i32, vp, vp, vp, C.POINTER(tr_out)]
         L.tr_decode_step.argtypes = [vp, vp, i32, vp, vp, C.POINTER(tr_out)]
+        L.tr_decode_step_dev.argtypes = [vp, vp, i32, vp, vp, C.POINTER(tr_out)]
         L.tr_tail.argtypes = [vp, vp, i32, vp, C.POINTER(tr_out)]
         L.tr_set_threshold.argtypes = [vp, f32]
         L.tr_set_mode.argtypes = [vp, i32]
@@ -211,6 +212,15 @@ class Model:
         out = out or self.outputs(len(slots), want_logits)
         self._check(self.lib.tr_decode_step(self._h, self._stream(), len(slots), slots.ctypes.data, toks.ctypes.data,
                                             C.byref(out.struct)), "tr_decode_step")
+        return out
+
+    def decode_step_dev(self, slots, in_tokens: torch.Tensor, out: Outputs = None, want_logits=False):
+        """Decode step whose input tokens are a device int32 tensor [n] (e.g. the `token` field of the previous outputs)."""
+        slots = np.ascontiguousarray(slots, dtype=np.int32)
+        assert in_tokens.is_cuda and in_tokens.dtype == torch.int32 and in_tokens.is_contiguous() and in_tokens.numel() == len(slots)
+        out = out or self.outputs(len(slots), want_logits)
+        self._check(self.lib.tr_decode_step_dev(self._h, self._stream(), len(slots), slots.ctypes.data, in_tokens.data_ptr(),
+                                                C.byref(out.struct)), "tr_decode_step_dev")
         return out
 
     def tail(self, x: torch.Tensor, out: Outputs = None, want_logits=False):

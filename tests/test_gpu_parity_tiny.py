@@ -443,3 +443,33 @@ def test_shapes_that_fill_no_tile_exactly(tr, tro, name, B):
     cnt = g.counters()
     for b in range(B):
         assert g.seq_len(b) == o.seq_len(b) and tuple(cnt[b]) == o.counters(b)
+
+
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
+def test_decode_steps_fed_from_device_memory(tr, tro, tiny_weights, dtype):
+    """tr_decode_step_dev: a chain of greedy steps that feeds each step's token output straight into the next step without
+    the host seeing it must produce the token stream of the same chain fed through the host (bit-identical logits at every
+    step), and for the fp32 model the oracle's own free-running stream; out-of-vocabulary device tokens are clamped."""
+    s = synth.TINY.with_(dtype=dtype, kv_dtype=dtype)
+    w = tiny_weights if dtype == synth.F32 else synth.make_weights(s, SEED + 31, std=0.05)
+    B, steps = 3, 12
+    a = tr.Model(s.asdict(), w, B, 128); b = tr.Model(s.asdict(), w, B, 128); o = tro.Model(s.asdict(), w, B, 128)
+    prompts = [synth.prompt_tokens(SEED, f"dev.p{i}", 5 + 11 * i, s.vocab) for i in range(B)]
+    slots = list(range(B))
+    xa = a.prefill(slots, prompts, want_logits=True); xb = b.prefill(slots, prompts, want_logits=True); oo = o.prefill(slots, prompts, want_logits=True)
+    dev_stream = []
+    for t in range(steps):
+        host_tok = xa.cpu().token.copy()
+        xa = a.decode_step(slots, host_tok, want_logits=True)              # through the host
+        xb = b.decode_step_dev(slots, xb.token, xb, want_logits=True)      # device to device: the outputs object feeds itself
+        oo = o.decode_step(slots, oo.token, want_logits=True)
+        ca, cb = xa.cpu(), xb.cpu()
+        assert np.array_equal(ca.logits, cb.logits) and np.array_equal(ca.token, cb.token) and np.array_equal(ca.flag, cb.flag), f"step {t}"
+        dev_stream.append(cb.token.copy())
+        if dtype == synth.F32:
+            assert np.array_equal(cb.token, oo.token), f"free-running token stream differs from the oracle at step {t}"
+    assert b.seq_len(0) == len(prompts[0]) + steps and tuple(b.counters()[1]) == tuple(a.counters()[1])
+    bad = torch.tensor([-5, s.vocab + 7, 3], dtype=torch.int32, device="cuda")
+    good = np.array([0, s.vocab - 1, 3], np.int32)
+    ya = a.decode_step(slots, good, want_logits=True).cpu(); yb = b.decode_step_dev(slots, bad, want_logits=True).cpu()
+    assert np.array_equal(ya.logits, yb.logits)
