@@ -180,7 +180,7 @@ def llm7b_workload(steps, warmup):
     print(json.dumps({"metric": "large-model decode on the routed subset, routed tokens/s", "value": routed / dt, "unit": "tokens/s", "n_gpus": 1,
                       "steps": steps, "warmup": warmup, "ms_per_step": dt / steps * 1e3, "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
                       "config": {"workload": "7B-class bf16 decoder, 32 sequences with 2048 cached positions (synthetic cache), each flagged with "
-                                             "probability 0.07 per step, decode on the flagged ones (BASELINE configs[4])",
+                                             "probability 0.07 per step, decode on the flagged ones",
                                  "routed_tokens": routed, "steps_by_rows": {str(n): c for n, c in sorted(hist.items())},
                                  "ms_per_nonempty_step": dt / max(1, steps - hist.get(0, 0)) * 1e3,
                                  "algorithmic_GB_per_s": nbytes / dt / 1e9, "fraction_of_hbm_roofline": nbytes / dt / 1e9 / HBM_PEAK_GBPS}}), flush=True)
@@ -318,7 +318,7 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "0.5B-class bf16 decoder + router, 64 concurrent sequences, prompts U[128,1024], contiguous KV cache, "
-                               f"{steps} decode steps after prefill (BASELINE configs[2])",
+                               f"{steps} decode steps after prefill",
                    "batch": B, "max_seq": MAX_SEQ, "seed": SEED, "prefill_seconds": prefill_s,
                    "algorithmic_bytes_per_step": step_bytes, "hbm_roofline_tokens_per_s": roof_tok_s,
                    "fraction_of_hbm_roofline": tok_s / roof_tok_s},
