@@ -339,6 +339,9 @@ static void launch_lmhead_gemv_t(hipStream_t s, const Dims &D, const TailArgs &t
     if (t.n == 1)
         hipLaunchKernelGGL((lmhead_kernel<WT, 1>), dim3(t.nslices, 1), dim3(256), 0, s, (const WT *)t.head, D.V, D.d, t.hn, t.n,
                            (float4 *)t.part, t.logits);
+    else if (t.n == 2)
+        hipLaunchKernelGGL((lmhead_kernel<WT, 2>), dim3(t.nslices, 1), dim3(256), 0, s, (const WT *)t.head, D.V, D.d, t.hn, t.n,
+                           (float4 *)t.part, t.logits);
     else
         hipLaunchKernelGGL((lmhead_kernel<WT, 4>), dim3(t.nslices, (t.n + 3) / 4), dim3(256), 0, s, (const WT *)t.head, D.V, D.d, t.hn, t.n,
                            (float4 *)t.part, t.logits);
