@@ -73,11 +73,13 @@ int check_config(const tr_config *c)
     if (c->route_policy < TR_POLICY_MLP || c->route_policy > TR_POLICY_LINEAR) return TR_ERR_INVALID_ARG;
     if (c->hidden_tap != TR_POST_FINAL_NORM && c->hidden_tap != TR_PRE_FINAL_NORM) return TR_ERR_INVALID_ARG;
     if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return TR_ERR_INVALID_ARG;
-    if ((long long)c->max_batch * c->max_seq > (1ll << 31)) return TR_ERR_CAPACITY;
+    if ((long long)c->max_batch * c->max_seq >= (1ll << 31)) return TR_ERR_CAPACITY;   // row and position indices are ints
     if (c->kv_page < 0 || c->kv_pool_pages < 0 || (c->kv_page == 0 && c->kv_pool_pages != 0)) return TR_ERR_INVALID_ARG;
     if (c->kv_page) {   // pages: a power of two of at least 32 positions; the matrix-core attention kernels (bf16 cache) walk them
         if (c->kv_page < 32 || (c->kv_page & (c->kv_page - 1)) || c->kv_dtype != TR_BF16) return TR_ERR_SHAPE;
-        if ((long long)c->kv_pool_pages * c->kv_page > (1ll << 31)) return TR_ERR_CAPACITY;
+        const long long per_slot = (c->max_seq + (long long)c->kv_page - 1) / c->kv_page;
+        const long long pool = c->kv_pool_pages ? c->kv_pool_pages : c->max_batch * per_slot;
+        if (pool * c->kv_page >= (1ll << 31)) return TR_ERR_CAPACITY;
     }
     return TR_OK;
 }
@@ -564,9 +566,10 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
         if (lay.mfma || lay.split_head) launch_repack(nullptr, ctx->head, D.V, D.d, ctx->ws + lay.wt_head, 0, 1, 0);
         if (lay.router_tiles) launch_repack(nullptr, ctx->r_w1, D.rh, D.d, ctx->ws + lay.wt_head, (D.V + 31) / 32, 1, 0);
         e = hipMemset(ctx->ws + lay.pack_d, 0, lay.part - lay.pack_d);   // padding rows of the packed activations stay zero
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-        if (e == hipSuccess) e = hipGetLastError();
     }
+    // everything above ran on the null stream; the caller's streams need not be ordered after it, so finish it here
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipGetLastError();
     if (e != hipSuccess) { delete ctx; return TR_ERR_HIP; }
     *out = ctx;
     return TR_OK;
@@ -815,7 +818,11 @@ int tr_profile_enable(tr_ctx *ctx, int32_t on)
         ctx->ev.resize(3 * 256);
         for (auto &e : ctx->ev) {
             hipError_t rc = hipEventCreate(&e);
-            if (rc != hipSuccess) { ctx->ev.clear(); return fail_hip(ctx, rc, "tr_profile_enable: hipEventCreate"); }
+            if (rc != hipSuccess) {
+                for (hipEvent_t *made = ctx->ev.data(); made != &e; ++made) (void)hipEventDestroy(*made);
+                ctx->ev.clear();
+                return fail_hip(ctx, rc, "tr_profile_enable: hipEventCreate");
+            }
         }
     }
     if (on && !ctx->profile) { ctx->prof_ms = ctx->prof_gap_ms = 0.0; ctx->prof_launches = 0; ctx->ev_used = 0; }
