@@ -121,19 +121,34 @@ struct StageAttn {
     __device__ __forceinline__ float4 load(int m, int k) const
     {
         const int r = r0 + m, head = k / dh, d0 = k % dh, ps = dh + 4;
-        const int live = min(a.nchunks, (a.pos[r] + a.chunk) / a.chunk);
+        // chunks that hold keys: positions 0..pos, or 0..pos-1 when the new key joins here (chunk 0 is always written then)
+        const int live = a.qn ? max(1, min(a.nchunks, (a.pos[r] + a.chunk - 1) / a.chunk)) : min(a.nchunks, (a.pos[r] + a.chunk) / a.chunk);
         const float *pp = a.part + ((size_t)r * Hq + head) * a.nchunks * ps;
+        // the row's own key: its score is taken here, from the rotated query and the key as the cache holds it. The 16 lanes
+        // that stage one 64-wide head (consecutive lanes, 4 dims each) share the dot product.
+        float snew = -INFINITY;
+        float4 vnew = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (a.qn) {
+            const float *kp = a.kvn + (size_t)r * 2 * a.kvw + (size_t)(head / a.G) * dh;
+            const float4 qv = *reinterpret_cast<const float4 *>(a.qn + (size_t)r * Hq * dh + k), kv = *reinterpret_cast<const float4 *>(kp + d0);
+            vnew = *reinterpret_cast<const float4 *>(kp + a.kvw + d0);
+            float dot = fmaf(qv.x, kv.x, fmaf(qv.y, kv.y, fmaf(qv.z, kv.z, qv.w * kv.w)));
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) dot += __shfl_xor(dot, o, 64);
+            snew = dot * 0.125f;   // 1 / sqrt(64)
+        }
         float mc[16], lc[16];
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
             const float *pc = pp + min(c, live - 1) * ps + dh;
             mc[c] = pc[0]; lc[c] = pc[1];
         }
-        float M = -INFINITY;
+        float M = snew;
 #pragma unroll
         for (int c = 0; c < 16; ++c) M = fmaxf(M, mc[c]);   // clamped entries repeat a live chunk
-        float L = 0.f;
-        float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float wnew = __expf(snew - M);                 // 0 when no new key joins
+        float L = wnew;
+        float4 o = make_float4(vnew.x * wnew, vnew.y * wnew, vnew.z * wnew, vnew.w * wnew);
 #pragma unroll
         for (int c0 = 0; c0 < 16; c0 += 8) {
             if (c0 >= live) break;
@@ -468,6 +483,278 @@ void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w,
     else launch_qkv_t<bf16_t, bf16_t>(s, D, w, x, rows, rope, q, kc, vc);
 }
 
+// ------------------------------------------------------------------ q|k|v projection and attention in one launch
+// (one or two decode rows, bf16 weights and cache, 64-wide heads, d <= 1024).
+// A decode step of one sequence is a chain of small dependent kernels, each costing several microseconds whatever it
+// does; this kernel removes one link per layer. Two kinds of workgroups (8 wavefronts):
+//  * (query head h, chunk c of the keys cached BEFORE this step): computes q_h = rotate(W_q[h] n + b) itself -- 64 weight
+//    rows of d columns, re-read from L2 by the other chunks of the head -- while its keys and values are already on
+//    their way, then scores its chunk (one key per 4 lanes), and leaves (weighted V sum, max, sum of exponentials) as a
+//    partial. Chunk 0 also stores q_h.
+//  * k/v workgroups: the new key (rotated) and value of the row, appended to the cache and also left, as the cache holds
+//    them, in kvn.
+// No workgroup has both q_h and the new key, so the new key's score and its share of the softmax are taken by the
+// consumer of the partials (StageAttn) in the output projection.
+// Rows must belong to different slots: a row's keys are read while other rows' keys are being appended.
+
+// dot products of NR weight rows with one activation row of K <= 1024 columns (gain applied, sum of squares taken):
+// each lane fetches the 16 columns it multiplies; results in every lane
+template <int NR>
+struct RowDots {
+    Raw8<bf16_t> rw[2][NR], gr[2];
+    float4 xa[2][2];
+    __device__ __forceinline__ void request(const bf16_t *const (&wrow)[NR], const bf16_t *gain, const float *xrow, int K)
+    {
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int kk = min(u * 512 + lane * 8, K - 8);
+#pragma unroll
+            for (int r = 0; r < NR; ++r) rw[u][r].load(wrow[r] + kk);
+            xa[u][0] = *reinterpret_cast<const float4 *>(xrow + kk); xa[u][1] = *reinterpret_cast<const float4 *>(xrow + kk + 4);
+            gr[u].load(gain + kk);
+        }
+    }
+    __device__ __forceinline__ void finish(int K, float (&acc)[NR], float &ss)
+    {
+    const int lane = threadIdx.x & 63;
+    ss = 0.f;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (u * 512 + lane * 8 < K) {
+            float xe[8] = {xa[u][0].x, xa[u][0].y, xa[u][0].z, xa[u][0].w, xa[u][1].x, xa[u][1].y, xa[u][1].z, xa[u][1].w};
+            float g[8];
+            gr[u].get(g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { ss = fmaf(xe[e], xe[e], ss); xe[e] *= g[e]; }
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                float wv[8];
+                rw[u][r].get(wv);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[r] = fmaf(wv[e], xe[e], acc[r]);
+            }
+        }
+    ss = wave_sum(ss);
+    }
+};
+
+// Sums each of NR (a power of two <= 16) per-lane values over the wavefront with NR - 1 + log2(64 / NR) exchanges instead of
+// 6 NR: every step halves the number of values a lane carries. Afterwards lane L holds the total of value L / (64 / NR).
+template <int N, int O>   // one halving step: N values remain afterwards, exchanged with the lane O away
+__device__ __forceinline__ void wave_sum_step(float *v)
+{
+    const bool up = threadIdx.x & O;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        const float keep = up ? v[i + N] : v[i], send = up ? v[i] : v[i + N];
+        v[i] = keep + __shfl_xor(send, O, 64);
+    }
+}
+template <int NR>
+__device__ __forceinline__ float wave_sum_n(float (&v)[NR])
+{
+    static_assert(NR == 4 || NR == 8 || NR == 16, "4, 8 or 16 values");
+    // every array index below is a compile-time constant: the values stay in registers
+    if constexpr (NR == 16) { wave_sum_step<8, 32>(v); wave_sum_step<4, 16>(v); wave_sum_step<2, 8>(v); wave_sum_step<1, 4>(v); }
+    if constexpr (NR == 8) { wave_sum_step<4, 32>(v); wave_sum_step<2, 16>(v); wave_sum_step<1, 8>(v); }
+    if constexpr (NR == 4) { wave_sum_step<2, 32>(v); wave_sum_step<1, 16>(v); }
+    float t = v[0];
+#pragma unroll
+    for (int o = 64 / NR / 2; o >= 1; o >>= 1) t += __shfl_xor(t, o, 64);
+    return t;
+}
+
+constexpr int QA_WAVES = 8;                  // wavefronts per workgroup (measured at a context of 384: 8.3 us per launch; 16 wavefronts 8.6 us; 4 spill registers)
+constexpr int QA_PAIRS = 32 / QA_WAVES;       // rotary pairs (two weight rows each) per wavefront
+constexpr int QA_NR = 2 * QA_PAIRS;
+constexpr int QA_LG = 64 / QA_NR;             // lanes that end up with the same sum
+constexpr int QA_KEYS = 128 / QA_WAVES;       // keys a wavefront scores at a time
+constexpr int QA_LPK = 64 / QA_KEYS;          // lanes per key
+constexpr int QA_DPL = 64 / QA_LPK;           // dims of a key per lane
+constexpr int QA_STRIDE = QA_WAVES * QA_KEYS; // 128 keys per trip of a workgroup
+
+__global__ __launch_bounds__(64 * QA_WAVES) void qkv_attn_kernel(Dims D, LayerW w, const float *x, Rows rows, const float2 *rope, float *q, bf16_t *kc,
+                                                                 bf16_t *vc, int chunk, int nchunks, float *part, float *kvn)
+{
+    constexpr int DH = 64, HALF = 32, PS = DH + 4;
+    __shared__ __attribute__((aligned(16))) float q_s[DH];
+    __shared__ float wp[QA_WAVES][DH + 2];
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int r = blockIdx.y, pos = rows.pos[r], slot = rows.slot[r];
+    const float *xrow = x + (size_t)r * D.d;
+    const int n_att = D.Hq * nchunks;
+    const int grp = lane / QA_LG;                            // which of the wavefront's sums this lane ends up with
+    const bool second = grp >= QA_PAIRS;                     // ... the second row of its rotary pair
+    const int jpair = wave * QA_PAIRS + (grp % QA_PAIRS);    // rotary pair (jpair, jpair + 32) of the head
+    const int dim_own = jpair + (second ? HALF : 0);
+
+    if ((int)blockIdx.x >= n_att) {
+        // ---- new key and value of the row: workgroup i takes kv "head" i (keys of head i, then values of head i - Hkv)
+        const int hk = blockIdx.x - n_att;
+        const bool is_k = hk < D.Hkv;
+        const int head = is_k ? hk : hk - D.Hkv;
+        const bf16_t *W = (const bf16_t *)(is_k ? w.wk : w.wv), *bias = (const bf16_t *)(is_k ? w.bk : w.bv);
+        const bf16_t *wrow[QA_NR];
+#pragma unroll
+        for (int i = 0; i < QA_PAIRS; ++i) {
+            wrow[i] = W + (size_t)(head * DH + wave * QA_PAIRS + i) * D.d;
+            wrow[i + QA_PAIRS] = wrow[i] + (size_t)HALF * D.d;
+        }
+        RowDots<QA_NR> rd;
+        rd.request(wrow, (const bf16_t *)w.ln1, xrow, D.d);
+        const float b_own = bias ? widen(bias, head * DH + dim_own) : 0.f;
+        const float2 cs = rope[(size_t)pos * HALF + jpair];
+        const KvPlace place = kv_place(D, slot, pos);
+        float acc[QA_NR], ss;
+        rd.finish(D.d, acc, ss);
+        const float rstd = 1.0f / sqrtf(ss / (float)D.d + D.eps);
+        const float y_own = wave_sum_n<QA_NR>(acc) * rstd + b_own;
+        const float y_other = __shfl_xor(y_own, 32, 64);
+        float y = y_own;
+        if (is_k) y = second ? y_own * cs.x + y_other * cs.y : y_own * cs.x - y_other * cs.y;
+        if (lane % QA_LG == 0) {
+            const bf16_t yb = f32_to_bf16(y);
+            if (is_k) kc[k_offset(D, place.unit, head, place.pos, dim_own)] = yb;
+            else vc[v_offset(D, place.unit, head, place.pos, dim_own)] = yb;
+            kvn[((size_t)r * 2 + (is_k ? 0 : 1)) * D.kvw + head * DH + dim_own] = bf16_to_f32(yb);
+        }
+        return;
+    }
+
+    // ---- query head h over chunk c of the cached keys
+    const int h = blockIdx.x / nchunks, c = blockIdx.x % nchunks, g = h / D.G;
+    const int j0 = c * chunk, j1 = min(pos, j0 + chunk);       // keys j0 .. j1-1, all cached before this step
+    if (c > 0 && j0 >= pos) return;                            // nothing here; the merge does not read this partial
+    const int kk = lane / QA_LPK, qd = lane % QA_LPK;          // scores: key of the group and part of its dims
+    const int last = max(j1 - 1, 0);                           // requests past the chunk are redirected to its last key and unused
+    uint4 kraw[QA_DPL / 8], vraw[QA_KEYS / 8];
+    auto request = [&](int t) {
+        const KvPlace pk = kv_place(D, slot, min(t + kk, last));
+        const bf16_t *kp = kc + k_offset(D, pk.unit, g, pk.pos, qd * QA_DPL);
+#pragma unroll
+        for (int i = 0; i < QA_DPL / 8; ++i) kraw[i] = *reinterpret_cast<const uint4 *>(kp + 8 * i);
+        const KvPlace pv = kv_place(D, slot, min(t, last & ~(QA_KEYS - 1)));
+        const bf16_t *vp = vc + v_offset(D, pv.unit, g, pv.pos, lane);     // QA_KEYS consecutive positions of dim `lane`
+#pragma unroll
+        for (int i = 0; i < QA_KEYS / 8; ++i) vraw[i] = *reinterpret_cast<const uint4 *>(vp + 8 * i);
+    };
+    const bf16_t *wrow[QA_NR];
+#pragma unroll
+    for (int i = 0; i < QA_PAIRS; ++i) {
+        wrow[i] = (const bf16_t *)w.wq + (size_t)(h * DH + wave * QA_PAIRS + i) * D.d;
+        wrow[i + QA_PAIRS] = wrow[i] + (size_t)HALF * D.d;
+    }
+    // the weights are requested first (their addresses need nothing from memory), then the keys and values, whose
+    // addresses wait for the row's slot and position
+    RowDots<QA_NR> rd;
+    rd.request(wrow, (const bf16_t *)w.ln1, xrow, D.d);
+    int t = j0 + wave * QA_KEYS;
+    request(t);
+    const float b_own = w.bq ? widen((const bf16_t *)w.bq, h * DH + dim_own) : 0.f;
+    const float2 cs = rope[(size_t)pos * HALF + jpair];
+    float acc[QA_NR], ss;
+    rd.finish(D.d, acc, ss);
+    const float rstd = 1.0f / sqrtf(ss / (float)D.d + D.eps);
+    const float y_own = wave_sum_n<QA_NR>(acc) * rstd + b_own;
+    const float y_other = __shfl_xor(y_own, 32, 64);
+    const float yq = second ? y_own * cs.x + y_other * cs.y : y_own * cs.x - y_other * cs.y;
+    if (lane % QA_LG == 0) {
+        q_s[dim_own] = yq * (1.0f / sqrtf((float)DH));
+        if (c == 0) q[(size_t)r * D.qw + h * DH + dim_own] = yq;
+    }
+    __syncthreads();
+
+    float qv[QA_DPL];
+#pragma unroll
+    for (int e = 0; e < QA_DPL; e += 4) {
+        const float4 a = *reinterpret_cast<const float4 *>(q_s + qd * QA_DPL + e);
+        qv[e] = a.x; qv[e + 1] = a.y; qv[e + 2] = a.z; qv[e + 3] = a.w;
+    }
+    float m_run = -INFINITY, l_run = 0.f, o_run = 0.f;         // o_run: dim `lane` of the weighted V sum
+    for (; t < j1; t += QA_STRIDE) {
+        float kf[QA_DPL], vf[QA_KEYS];
+#pragma unroll
+        for (int i = 0; i < QA_DPL / 8; ++i) {
+            float a[8];
+            Raw8<bf16_t> ra{kraw[i]};
+            ra.get(a);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) kf[8 * i + e] = a[e];
+        }
+#pragma unroll
+        for (int i = 0; i < QA_KEYS / 8; ++i) {
+            float a[8];
+            Raw8<bf16_t> ra{vraw[i]};
+            ra.get(a);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vf[8 * i + e] = a[e];
+        }
+        if (t + QA_STRIDE < j1) request(t + QA_STRIDE);        // the next group, while this one is consumed
+        float sc = 0.f;
+#pragma unroll
+        for (int e = 0; e < QA_DPL; ++e) sc = fmaf(qv[e], kf[e], sc);
+#pragma unroll
+        for (int o = 1; o < QA_LPK; o <<= 1) sc += __shfl_xor(sc, o, 64);
+        if (t + kk >= j1) sc = -INFINITY;
+        float bm = sc;                                         // the lanes of a key agree already
+#pragma unroll
+        for (int o = 32; o >= QA_LPK; o >>= 1) bm = fmaxf(bm, __shfl_xor(bm, o, 64));
+        const float m_new = fmaxf(m_run, bm);                  // finite: key t is valid
+        const float corr = __expf(m_run - m_new);              // 0 the first time
+        const float p = __expf(sc - m_new);
+        float psum = p;
+#pragma unroll
+        for (int o = 32; o >= QA_LPK; o >>= 1) psum += __shfl_xor(psum, o, 64);
+        l_run = l_run * corr + psum;
+        o_run *= corr;
+#pragma unroll
+        for (int e = 0; e < QA_KEYS; ++e) o_run = fmaf(__shfl(p, QA_LPK * e, 64), vf[e], o_run);
+        m_run = m_new;
+    }
+    wp[wave][lane] = o_run;
+    if (lane == 0) { wp[wave][DH] = m_run; wp[wave][DH + 1] = l_run; }
+    __syncthreads();
+    if (wave != 0) return;
+    float M = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < QA_WAVES; ++i) M = fmaxf(M, wp[i][DH]);
+    float L = 0.f, O = 0.f;
+    if (M > -INFINITY) {
+#pragma unroll
+        for (int i = 0; i < QA_WAVES; ++i) {
+            const float wgt = __expf(wp[i][DH] - M);            // 0 for a wavefront that saw no key
+            L = fmaf(wp[i][DH + 1], wgt, L);
+            O = fmaf(wp[i][lane], wgt, O);
+        }
+    }
+    float *dst = part + (((size_t)r * D.Hq + h) * nchunks + c) * PS;
+    dst[lane] = O;
+    if (lane == 0) { dst[DH] = M; dst[DH + 1] = L; }
+}
+
+bool launch_qkv_attention(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, int max_ctx,
+                          const float2 *rope, float *q, void *kc, void *vc, float *part, size_t part_floats, float *kvn, AttnPending *pend)
+{
+    if (wdt != DT_BF16 || kdt != DT_BF16 || D.dh != 64 || D.d > 1024 || D.d % 8 || rows.n < 1 || rows.n > 2 || !pend) return false;
+    // chunks of 128 cached keys (16 per wavefront), longer ones when the consumer's limit of 16 chunks asks for it
+    const int cached = max_ctx > 1 ? max_ctx - 1 : 0;
+    int chunk = QA_STRIDE, nchunks = (cached + chunk - 1) / chunk;
+    if (nchunks > 16) {
+        chunk = QA_STRIDE * ((cached + QA_STRIDE * 16 - 1) / (QA_STRIDE * 16));
+        nchunks = (cached + chunk - 1) / chunk;
+    }
+    if (nchunks < 1) nchunks = 1;
+    if ((size_t)rows.n * D.Hq * nchunks * (D.dh + 4) > part_floats) return false;
+    const dim3 grid(D.Hq * nchunks + 2 * D.Hkv, rows.n);
+    hipLaunchKernelGGL(qkv_attn_kernel, grid, dim3(64 * QA_WAVES), 0, s, D, w, x, rows, rope, q, (bf16_t *)kc, (bf16_t *)vc, chunk, nchunks, part, kvn);
+    pend->part = part; pend->pos = rows.pos; pend->nchunks = nchunks; pend->chunk = chunk;
+    pend->qn = q; pend->kvn = kvn; pend->G = D.G; pend->kvw = D.kvw;
+    return true;
+}
+
 // ------------------------------------------------------------------ grouped-query attention over the cache.
 // One workgroup (4 wavefronts) serves one query row, one kv head (all G query heads of its group share the
 // K/V loads) and one contiguous chunk of the context ("split"); partial (max, sum, weighted V) triples of
@@ -794,7 +1081,7 @@ static bool launch_attention_wave(hipStream_t s, const Dims &D, const float *q, 
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,
                       float *part, size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer)
 {
-    if (defer) defer->nchunks = 0;
+    if (defer) { defer->nchunks = 0; defer->qn = defer->kvn = nullptr; }
     if (kdt == DT_BF16) {   // bf16 cache: V is stored transposed and attention runs on the matrix cores
         launch_attention_mfma(s, D, q, kc, vc, rows, max_ctx, part, part_floats, cnt, att, pack, ncb, defer);
         return;

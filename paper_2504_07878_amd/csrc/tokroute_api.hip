@@ -29,6 +29,7 @@ struct Layout {
     size_t r1;         // sums of the router's first layer, [max_batch][router_tiles * 32], written by the LM-head launch
     int router_tiles;  // tiles of router weight rows appended to the repacked head matrix (0: the merge kernel computes the router itself)
     size_t qblock;     // query-row blocks of a pass (prompts, catch-up segments): first row * 8 + rows
+    size_t kvn;        // new keys and values of up to two decode rows, [row][2][kv width] floats (fused q|k|v + attention kernel)
     int maxp, pool;    // pages per slot (table row length) and pages in the pool; 0 for the contiguous cache
     int max_rows, nslices;
     // matrix-core paths: repacked weights, packed activations, split-K partials.
@@ -40,7 +41,10 @@ struct Layout {
     size_t pack_d, pack_a, pack_h, part;
 };
 
-constexpr int GEMV_MAX_ROWS = 8;   // up to this many rows the streaming GEMV kernels are used
+// Up to this many rows the streaming GEMV kernels are used where the matrix-core path exists. Measured decode step of the
+// 0.5B-class model (context 256): 0.63 ms at 1 row and 0.83 at 2 on the streaming kernels, which then climb to 1.15 (3 rows),
+// 1.26 (4) and 1.40 (8), while the matrix-core path takes 1.05 ms from 3 to 16 rows.
+constexpr int GEMV_MAX_ROWS = 2;
 
 // The matrix-core kernels keep 896 columns of K per workgroup resident, and the layers with a non-linear
 // epilogue (rotary, SwiGLU, softmax statistics) cannot split K across workgroups.
@@ -155,6 +159,7 @@ Layout make_layout(const tr_config *c)
         L.part = take(part_bytes);
     }
     L.qblock = take(R * 4);
+    L.kvn = take(2 * 2 * kvw * 4);
     L.total = off;
     return L;
 }
@@ -246,7 +251,8 @@ void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1, hipEvent_t *e2)
 
 // All layers over the rows currently described by the device row arrays. Returns the number of split-K partial
 // buffers of the last down projection that still have to be added to the residual stream (matrix-core path).
-int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true)
+// distinct_slots: every row belongs to a different slot (a decode step), so no row reads a key another row appends.
+int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true, bool distinct_slots = false)
 {
     const Dims &D = ctx->D;
     const Layout &L = ctx->lay;
@@ -292,9 +298,13 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         AttnPending pend{};
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
-            launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
-            attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
-                             attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, &pend);
+            // one or two rows of a decode step: projection and attention over the cached keys in one launch, merged by the output projection
+            if (!(distinct_slots && launch_qkv_attention(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, max_ctx, ctx->at<float2>(L.rope), q, ctx->kc_layer(l),
+                                                         ctx->vc_layer(l), ctx->at<float>(L.attn_part), attn_part_floats, ctx->at<float>(L.kvn), &pend))) {
+                launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+                attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
+                                 attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, &pend);
+            }
             launch_oproj(s, ctx->c.dtype, D, w.wo, att, pend, R, x);
             launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
             launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
@@ -714,7 +724,7 @@ static int decode_step_impl(tr_ctx *ctx, void *hip_stream, int32_t n, const int3
     }
     launch_setup_rows_embed(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos), ctx->c.dtype,
                             ctx->tok_emb, ctx->D.d, ctx->at<float>(L.x), dev_tokens, ctx->c.vocab);
-    const int pending = run_layers(ctx, s, n, max_ctx, false);
+    const int pending = run_layers(ctx, s, n, max_ctx, false, true);
     TailArgs t = tail_args(ctx, out, 0, n);
     t.gather = nullptr;
     t.slot = ctx->at<int>(L.slot);

@@ -62,6 +62,11 @@ struct AttnPending {
     const float *part;   // [row][head][nchunks][dh + 4]: unnormalised weighted V sums, then running max and sum of exponentials
     const int *pos;
     int nchunks, chunk;  // nchunks == 0: nothing pending, the merged rows are in the fp32 buffer
+    // Set by the fused q|k|v + attention kernel: its partials cover the keys cached BEFORE the step only, and the row's own
+    // new key and value join in the merge. qn: rotated queries [row][q width]; kvn: the new key and value as the cache holds
+    // them (rounded to its type), [row][2][kv width]. NULL: the partials already cover the new key.
+    const float *qn, *kvn;
+    int G, kvw;
 };
 
 constexpr int MAX_SPLITS = 32;   // most split-K partial buffers a linear layer may produce
@@ -113,6 +118,11 @@ void launch_setup_rows_embed(hipStream_t s, int n, const int *slots, const int *
                              const void *E, int d, float *x, const int *dev_toks, int vocab);   // dev_toks: device tokens [n] instead of toks (then NULL)
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope,
                 float *q, void *kc, void *vc);
+// One or two decode rows of DIFFERENT slots, bf16 weights and cache, 64-wide heads, d <= 1024: the q|k|v projection and the attention
+// over the cached keys in one launch (see qkv_attn_kernel). Returns false, having done nothing, when the case is not covered.
+// kvn: scratch [rows][2][kv width] floats. The partials are left for the output projection to merge (pend).
+bool launch_qkv_attention(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, int max_ctx,
+                          const float2 *rope, float *q, void *kc, void *vc, float *part, size_t part_floats, float *kvn, AttnPending *pend);
 // cnt: one zero-initialised int per (row, kv head), left at zero again by every launch (arrival counters of the
 // workgroups that share a row when its context is split)
 void launch_attention(hipStream_t s, int kdt, const Dims &D, const float *q, const void *kc, const void *vc, Rows rows, int max_ctx,

@@ -473,3 +473,34 @@ def test_decode_steps_fed_from_device_memory(tr, tro, tiny_weights, dtype):
     good = np.array([0, s.vocab - 1, 3], np.int32)
     ya = a.decode_step(slots, good, want_logits=True).cpu(); yb = b.decode_step_dev(slots, bad, want_logits=True).cpu()
     assert np.array_equal(ya.logits, yb.logits)
+
+
+@pytest.mark.parametrize("kv_page", [0, 32])
+def test_one_and_two_row_decode_steps_at_chunk_boundaries(tr, tro, kv_page):
+    """Decode steps of one or two sequences with bf16 weights and cache run the projection and the attention over the cached
+    keys as one kernel, whose partials (chunks of 128 cached keys) the output projection merges with the row's own new key.
+    Cases: a sequence rolled back to nothing and decoded from position 0 (no cached key at all), one whose cache crosses
+    positions 127, 128 and 129 (first chunk filling up, second chunk starting), both in one call (very different contexts)
+    and each alone; the same on the paged cache (pages of 32)."""
+    s = synth.TINY.with_(dtype=synth.BF16, kv_dtype=synth.BF16)
+    w = synth.make_weights(s, SEED + 41, std=0.05, bias_std=0.05, gain_std=0.1)
+    g = tr.Model(s.asdict(), w, 2, 300, kv_page=kv_page); o = tro.Model(s.asdict(), w, 2, 300)
+    p0 = synth.prompt_tokens(SEED, "qa.p0", 3, s.vocab)
+    g.prefill([0], [p0]); o.prefill([0], [p0])
+    g.seq_truncate(0, 0); o.seq_truncate(0, 0)
+    k, v = synth.kv_fill(SEED, "qa.kv", s, 126)
+    o.load_kv(1, synth.bf16_bits_to_f32(k), synth.bf16_bits_to_f32(v)); g.load_kv(1, tr.to_device(k, synth.BF16), tr.to_device(v, synth.BF16))
+    toks = synth.prompt_tokens(SEED, "qa.tok", 2, s.vocab)
+    ex = 0
+    for step in range(5):     # slot 0 at positions 0..4, slot 1 at 126..130
+        go = g.decode_step([0, 1], toks, want_logits=True).cpu(); oo = o.decode_step([0, 1], toks, want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"two rows, step {step}")
+        toks = oo.token.copy()
+    for slot in (1, 0):
+        t1 = toks[slot:slot + 1]
+        for step in range(2):
+            go = g.decode_step([slot], t1, want_logits=True).cpu(); oo = o.decode_step([slot], t1, want_logits=True)
+            ex += compare_outputs(go, oo, s.dtype, s.threshold, f"slot {slot} alone, step {step}")
+            t1 = oo.token.copy()
+    assert ex <= 1
+    assert g.seq_len(0) == 7 and g.seq_len(1) == 133
