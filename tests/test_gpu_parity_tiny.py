@@ -418,7 +418,10 @@ ODD_SHAPES = {
 
 
 @pytest.mark.parametrize("name,B", [("f32_g1", 5), ("bf16_g8", 3), ("bf16_g8", 21), ("bf16_f32kv", 21), ("wide_g5", 3), ("wide_g5", 12),
-                                    ("wide_g5", 1), ("ffn_1544", 1), ("ffn_3000", 1), ("ffn_6152", 1)])
+                                    ("wide_g5", 1), ("ffn_1544", 1), ("ffn_3000", 1), ("ffn_6152", 1),
+                                    # one and two rows: the LDS-free short path, the split rows of the output projections and, with bf16
+                                    # weights and cache, the fused projection + attention kernel (272 columns: one partly used step; 8 heads per group)
+                                    ("bf16_g8", 1), ("bf16_g8", 2), ("ffn_3000", 2), ("ffn_6152", 2), ("bf16_f32kv", 2), ("f32_g1", 2), ("wide_g5", 2)])
 def test_shapes_that_fill_no_tile_exactly(tr, tro, name, B):
     """Model shapes whose widths are not multiples of the kernels' tiles (reduction length, FFN width, vocabulary, router
     width, heads per group), on every kernel family: prefill, decode steps and a catch-up step against the oracle."""
