@@ -428,9 +428,11 @@ static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const
         passes.emplace_back();
         Pass &ps = passes.back();
         int rows = 0, max_ctx = 0, j = i;
+        bool one_token_each = true;   // every segment of the pass is a single token: its rows belong to different slots, like a decode step's
         for (; j < n; ++j) {
             const int T = offsets[j + 1] - offsets[j], base = from_len ? ctx->len[(size_t)slots[j]] : 0;
             if (j > i && rows + T > L.max_rows) break;
+            if (T != 1) one_token_each = false;
             for (int t = 0; t < T; ++t) { ps.slot.push_back(slots[j]); ps.pos.push_back(base + t); }
             for (int t = 0; t < T; t += block_rows) ps.qblock.push_back((rows + t) * 8 + std::min(block_rows, T - t));
             rows += T;
@@ -449,7 +451,7 @@ static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const
         if (blocks && e == hipSuccess) e = hipMemcpyAsync(ctx->at<int>(L.qblock), ps.qblock.data(), ps.qblock.size() * 4, hipMemcpyHostToDevice, s);
         if (e != hipSuccess) return fail_hip(ctx, e, who);
         ctx->qblocks = blocks ? (int)ps.qblock.size() : 0;
-        const int pending = run_layers(ctx, s, rows, max_ctx);
+        const int pending = run_layers(ctx, s, rows, max_ctx, true, one_token_each);
         ctx->qblocks = 0;
         TailArgs t = tail_args(ctx, out, i, j - i);
         t.gather = ctx->at<int>(L.gather);

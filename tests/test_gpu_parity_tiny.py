@@ -505,5 +505,9 @@ def test_one_and_two_row_decode_steps_at_chunk_boundaries(tr, tro, kv_page):
             go = g.decode_step([slot], t1, want_logits=True).cpu(); oo = o.decode_step([slot], t1, want_logits=True)
             ex += compare_outputs(go, oo, s.dtype, s.threshold, f"slot {slot} alone, step {step}")
             t1 = oo.token.copy()
+    # a catch-up call whose segments are one token each is a decode step and takes the same kernels
+    segs = [synth.prompt_tokens(SEED, f"qa.seg{i}", 1, s.vocab) for i in range(2)]
+    go = g.extend([1, 0], segs, want_logits=True).cpu(); oo = o.extend([1, 0], segs, want_logits=True)
+    ex += compare_outputs(go, oo, s.dtype, s.threshold, "one-token segments")
     assert ex <= 1
-    assert g.seq_len(0) == 7 and g.seq_len(1) == 133
+    assert g.seq_len(0) == 8 and g.seq_len(1) == 134
