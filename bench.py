@@ -262,7 +262,7 @@ def main():
     ap.add_argument("--no-extras", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
+        log("bench.py: the library runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
         sys.exit(2)
 
     import torch
