@@ -246,7 +246,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "50ac22b072e54d16b55f8c5429f1273e94c3bb54ce48b898464fdaa813414686", "fetch_bytes": 274979710, "write_bytes": 322560}
+LMHEAD_TRAFFIC = {"source_sha256": "315b75bd416a9f79ad2de4a54b522ca30448356beaa30a7dbcc7386ceb940ac3", "fetch_bytes": 274908805, "write_bytes": 322560}
 
 
 def main():

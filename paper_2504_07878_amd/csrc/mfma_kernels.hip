@@ -1527,10 +1527,17 @@ void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void
     }
 }
 
-int lmhead_mfma_wgs(int V, int router_tiles)
+// tiles per workgroup of the LM-head launch: the whole launch (every 64-row group over every tile) is one round of at most 256 workgroups
+static int lmhead_tiles_per_wg(int n_tiles, int M)
+{
+    const int groups = (M + 63) / 64, per_group = groups >= 256 ? 1 : 256 / groups;
+    return (n_tiles + per_group - 1) / per_group;
+}
+
+int lmhead_mfma_wgs(int V, int router_tiles, int M)
 {
     const int n_tiles = (V + 31) / 32 + router_tiles;
-    const int tpw = (n_tiles + 255) / 256;
+    const int tpw = lmhead_tiles_per_wg(n_tiles, M);
     return (n_tiles + tpw - 1) / tpw;
 }
 
@@ -1539,10 +1546,10 @@ void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void
     GemmArgs a{};
     const int vt = (D.V + 31) / 32;
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = vt + router_tiles; a.M = M;
-    a.tiles_per_wg = (a.n_tiles + 255) / 256;
+    a.tiles_per_wg = lmhead_tiles_per_wg(a.n_tiles, M);
     a.remap_groups = M > 64 ? (M + 63) / 64 : 0;
     auto go = [&](auto e) {
-        e.part = (float4 *)part; e.logits = logits; e.M = M; e.V = D.V; e.nwg = lmhead_mfma_wgs(D.V, router_tiles);
+        e.part = (float4 *)part; e.logits = logits; e.M = M; e.V = D.V; e.nwg = lmhead_mfma_wgs(D.V, router_tiles, M);
         e.r1 = r1; e.vt = router_tiles > 0 ? vt : 0x7fffffff; e.r1_stride = router_tiles * 32;
         launch_gemm(s, a, 1, e);
     };

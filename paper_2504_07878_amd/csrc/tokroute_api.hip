@@ -125,7 +125,7 @@ Layout make_layout(const tr_config *c)
     // fused matrix-core tail with the MLP router on the normalised hidden state: the router's first layer rides along in the LM-head launch
     L.router_tiles = (L.mfma && c->route_policy == TR_POLICY_MLP && c->router_hidden > 0 && c->hidden_tap == TR_POST_FINAL_NORM) ? (c->router_hidden + 31) / 32 : 0;
     L.r1 = take((size_t)c->max_batch * (L.router_tiles ? L.router_tiles : 1) * 32 * 4);
-    const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab, L.router_tiles) : 0;
+    const int head_wgs = L.mfma ? lmhead_mfma_wgs(c->vocab, L.router_tiles, 1) : 0;
     L.tail_part = take((size_t)(L.nslices > head_wgs ? L.nslices : head_wgs) * c->max_batch * sizeof(float4));
     if (L.mfma || L.split) {
         const size_t d = (size_t)c->d_model, F = (size_t)c->d_ffn;
@@ -381,7 +381,7 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     t.x = x + (size_t)row0 * D.d;
     if (e0) (void)hipEventRecord(e0, s);
     // the head is streamed by the matrix-core kernel for any row count: one row costs the same bytes as 32
-    t.nslices = lmhead_mfma_wgs(D.V, L.router_tiles);
+    t.nslices = lmhead_mfma_wgs(D.V, L.router_tiles, t.n);
     launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits, ctx->at<float>(L.r1), L.router_tiles);
     if (L.router_tiles) { t.r1 = ctx->at<float>(L.r1); t.r1_stride = L.router_tiles * 32; }
     if (e1) (void)hipEventRecord(e1, s);

@@ -173,7 +173,7 @@ void launch_swiglu_finish(hipStream_t s, const Dims &D, const float *part, int n
 // writes slice_part[slice][m] = {max, lowest argmax, sum-exp} (what the tail's final kernel merges) and, when asked, the logits.
 constexpr int LMHEAD_FINISH_COLS = 2048;
 void launch_lmhead_finish(hipStream_t s, const float *part, int nsplit, int M, int V, float *slice_part, float *logits);
-int lmhead_mfma_wgs(int V, int router_tiles);
+int lmhead_mfma_wgs(int V, int router_tiles, int M);   // workgroups per 64-row group that own tiles, for M rows (most at M <= 64)
 // router_tiles > 0: the matrix holds that many extra tiles after the vocabulary (the router's first layer); their raw sums go to r1[row][router_tiles * 32]
 void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits, float *r1, int router_tiles);
 
