@@ -51,3 +51,78 @@ def generate(slm, llm, prompts, max_new: int):
         if t + 1 < max_new:
             out = slm.decode_step(slots, tok).cpu(NEEDED)
     return tokens, routed
+
+
+def generate_overlapped(slm, llm, prompts, max_new: int):
+    """The same decoding as `generate`, sequence by sequence, scheduled for throughput: a flagged sequence waits for the
+    large model while the others keep decoding.
+
+    The large model runs on a stream of its own, one call at a time, on every sequence that is waiting when the previous call
+    has finished (prefill for a sequence's first call, catch-up segments afterwards); the small model steps the sequences that
+    are not waiting. What a sequence emits does not depend on the schedule (each of its positions is still the small model's
+    token unless the router flags it, and the large model's otherwise), only the order in which the sequences advance does.
+    Returns (tokens, routed) like `generate`.
+    """
+    import torch
+    B = len(prompts)
+    seq = [list(map(int, p)) for p in prompts]
+    llm_len = [0] * B
+    done = [0] * B                         # tokens emitted per sequence
+    next_tok = np.zeros(B, np.int32)       # input of a running sequence's next small-model step
+    running = [False] * B
+    tokens = np.zeros((B, max_new), np.int32)
+    routed = np.zeros((B, max_new), bool)
+    pending = []                           # flagged, not yet handed to the large model
+    s_small, s_large = torch.cuda.Stream(), torch.cuda.Stream()
+    host_tok = torch.empty(2 * B, dtype=torch.int32, pin_memory=True)
+    inflight = None                        # (sequences, output objects kept alive, event)
+
+    def emit(b, tok, by_large):
+        tokens[b, done[b]] = tok
+        routed[b, done[b]] = by_large
+        seq[b].append(int(tok))
+        done[b] += 1
+        running[b] = done[b] < max_new
+        next_tok[b] = tok
+
+    def take(bs, out):
+        for i, b in enumerate(bs):
+            running[b] = False
+            if out.flag[i]:
+                pending.append(b)
+            else:
+                emit(b, out.token[i], False)
+
+    start = torch.cuda.current_stream()
+    s_small.wait_stream(start); s_large.wait_stream(start)
+    with torch.cuda.stream(s_small):
+        take(list(range(B)), slm.prefill(list(range(B)), prompts).cpu(NEEDED, stream_only=True))
+    while inflight or pending or any(running):
+        if inflight and (inflight[2].query() or not any(running)):
+            bs, _, ev = inflight
+            ev.synchronize()
+            for i, b in enumerate(bs):
+                llm_len[b] = len(seq[b])
+                emit(b, int(host_tok[i]), True)
+            inflight = None
+        if not inflight and pending:
+            first = [b for b in pending if llm_len[b] == 0]
+            later = [b for b in pending if llm_len[b] > 0]
+            keep = []
+            with torch.cuda.stream(s_large):
+                if first:
+                    keep.append(llm.prefill(first, [seq[b] for b in first]))
+                    host_tok[:len(first)].copy_(keep[-1].token[:len(first)], non_blocking=True)
+                if later:
+                    keep.append(llm.extend(later, [seq[b][llm_len[b]:] for b in later]))
+                    host_tok[len(first):len(first) + len(later)].copy_(keep[-1].token[:len(later)], non_blocking=True)
+                ev = torch.cuda.Event()
+                ev.record(s_large)
+            inflight = (first + later, keep, ev)
+            pending = []
+        run = [b for b in range(B) if running[b]]
+        if run:
+            with torch.cuda.stream(s_small):
+                take(run, slm.decode_step(run, next_tok[run]).cpu(NEEDED, stream_only=True))
+    start.wait_stream(s_small); start.wait_stream(s_large)
+    return tokens, routed

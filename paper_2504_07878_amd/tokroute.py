@@ -111,9 +111,13 @@ class Outputs:
 
     FIELDS = ("token", "conf", "score", "flag", "hidden", "logits")
 
-    def cpu(self, fields=FIELDS):
-        """Synchronise and copy the named outputs (default: all) to numpy; the others are None."""
-        torch.cuda.synchronize()
+    def cpu(self, fields=FIELDS, stream_only=False):
+        """Synchronise and copy the named outputs (default: all) to numpy; the others are None.
+
+        stream_only: wait for the current stream only (the one the outputs were produced on) instead of the whole device,
+        so that work on other streams keeps running."""
+        if not stream_only:
+            torch.cuda.synchronize()
         o = type("HostOutputs", (), {})()
         for k in self.FIELDS:
             v = getattr(self, k) if k in fields else None

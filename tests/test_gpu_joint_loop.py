@@ -37,8 +37,11 @@ def oracle_joint(tro, slm_shape, slm_w, llm_shape, llm_w, prompt, max_new, max_s
     return toks, routed, gaps
 
 
+@pytest.mark.parametrize("overlapped", [False, True])
 @pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
-def test_joint_decoding_matches_the_plain_loop(tr, tro, dtype):
+def test_joint_decoding_matches_the_plain_loop(tr, tro, dtype, overlapped):
+    """overlapped: the schedule in which flagged sequences wait for the large model on a second stream while the others keep
+    decoding; what each sequence emits must not depend on it."""
     from paper_2504_07878_amd import joint
     slm_shape = synth.TINY.with_(dtype=dtype, kv_dtype=dtype)
     llm_shape = synth.TINY.with_(name="tiny-large", n_layers=3, d_ffn=1536, router_hidden=0, tie_lm_head=0, dtype=dtype, kv_dtype=dtype)
@@ -48,7 +51,7 @@ def test_joint_decoding_matches_the_plain_loop(tr, tro, dtype):
     prompts = [synth.prompt_tokens(SEED, f"joint.p{b}", n, slm_shape.vocab) for b, n in enumerate((5, 17, 40, 9, 64, 2))]
     slm = tr.Model(slm_shape.asdict(), slm_w, B, max_seq)
     llm = tr.Model(llm_shape.asdict(), llm_w, B, max_seq)
-    tokens, routed = joint.generate(slm, llm, prompts, max_new)
+    tokens, routed = (joint.generate_overlapped if overlapped else joint.generate)(slm, llm, prompts, max_new)
     n_routed = 0
     for b in range(B):
         toks, rt, gaps = oracle_joint(tro, slm_shape, slm_w, llm_shape, llm_w, prompts[b], max_new, max_seq)
