@@ -256,7 +256,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "315b75bd416a9f79ad2de4a54b522ca30448356beaa30a7dbcc7386ceb940ac3", "fetch_bytes": 274908805, "write_bytes": 322560}
+LMHEAD_TRAFFIC = {"source_sha256": "26a7a5df9647f79a1ca63706f09e15c9b1dba07cf87ff6606f3da4dda7db457d", "fetch_bytes": 274909263, "write_bytes": 322560}
 
 
 def main():

@@ -729,13 +729,22 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
                            size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer)
 {
     if (defer) defer->nchunks = 0;
-    if (rows.n * D.Hkv >= 64 && D.G <= 8) {   // enough (row, kv head) pairs to fill the chip with one workgroup each
-        // parts of 768 keys (three key blocks per wavefront; measured best among 256..1024 on the ragged 64-sequence workload),
-        // longer ones when the partials buffer or the limit of 16 parts asks for it
+    // Few rows whose partials the consumer can merge while it stages them (the output projection of the GEMV path) keep the
+    // chunked kernel below; everything else takes one workgroup per (row, kv head, part of the context), whose last arriver
+    // merges the parts: no merge kernel.
+    const bool consumer_merges = defer && !pack && rows.n <= 4 && max_ctx <= 16 * 64;
+    // (128-wide heads with few rows stay on the chunked kernel too: the 7B-class routed-subset step measured 3.25 ms with it and
+    // the merge kernel, 3.31 ms with parts of 256 keys here)
+    const bool many = rows.n * D.Hkv >= 64;
+    if (D.G <= 8 && (many || (!consumer_merges && D.dh == 64))) {
+        // enough (row, kv head) pairs to fill the chip with one workgroup each: parts of 768 keys (three key blocks per
+        // wavefront; measured best among 256..1024 on the ragged 64-sequence workload); fewer pairs: parts of 256 keys (one
+        // block per wavefront), so that more compute units take part. Longer parts when the partials buffer or the limit
+        // of 16 parts asks for it.
         size_t room = part_floats / ((size_t)rows.n * D.Hq * (D.dh + 4));
         if (room > 16) room = 16;
         if (room < 1) room = 1;
-        int span = 768;
+        int span = many ? 768 : 256;
         if ((size_t)(max_ctx + span - 1) / span > room) span = 256 * (int)((max_ctx + 256 * room - 1) / (256 * room));
         const int P = (max_ctx + span - 1) / span;
         const dim3 grid(rows.n, D.Hkv, P);
