@@ -188,7 +188,7 @@ def test_tiny_run_twice_is_bit_identical(tr, tiny_weights):
 
 @pytest.mark.parametrize("B", [9, 33, 70, 256])
 def test_small_bf16_model_on_the_matrix_core_path(tr, tro, B):
-    """bf16 weights and more than 8 rows take the MFMA kernels: batches of 9 (one column block), 33 (two) and 70 (two row
+    """bf16 weights and 3 or more rows take the MFMA kernels: batches of 9 (one column block), 33 (two) and 70 (two row
     groups) and 256 (four row groups, the LM head's XCD-aware placement), ragged prompts up to several 64-row groups,
     non-zero biases, non-unit gains."""
     s = synth.TINY.with_(dtype=synth.BF16, kv_dtype=synth.BF16)
@@ -241,8 +241,8 @@ def test_small_bf16_model_long_contexts(tr, tro, B, ctx):
 @pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
 def test_catch_up_step_over_an_existing_cache(tr, tro, dtype):
     """tr_extend against the oracle's definition (cached decode steps, only the last one visible): segments of 1, 5, 14
-    (the paper's ~7 % routing means about 14 small-model tokens between two routed ones), 40 and 130 tokens — up to 8 rows
-    run the GEMV kernels, more run the matrix-core ones — over caches of very different lengths, several slots per call,
+    (the paper's ~7 % routing means about 14 small-model tokens between two routed ones), 40 and 130 tokens — one or two rows
+    run the GEMV kernels, more run the matrix-core ones (bf16) — over caches of very different lengths, several slots per call,
     alternating with ordinary decode steps; counters, lengths and error paths included."""
     s = synth.TINY.with_(dtype=dtype, kv_dtype=dtype)
     w = synth.make_weights(s, SEED + 5, std=0.05, bias_std=0.05, gain_std=0.1)
@@ -346,7 +346,7 @@ def test_other_routing_scores(tr, tro, dtype, B):
 
 @pytest.mark.parametrize("B", [12, 70])
 def test_wide_bf16_model_on_the_split_k_path(tr, tro, B):
-    """A model wider than one workgroup's share of K (d_model 1024 > 896, head dim 128): with more than 8 rows every linear
+    """A model wider than one workgroup's share of K (d_model 1024 > 896, head dim 128): with more than 2 rows every linear
     layer goes through split-K partials and the rotary/cache-append and SwiGLU steps are finished by their own kernels; the
     tail stays on the streaming kernels. Ragged prefill, decode steps, a catch-up step, and the row counts in between."""
     s = synth.TINY.with_(name="wide", d_model=1024, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ffn=2048, dtype=synth.BF16, kv_dtype=synth.BF16)
