@@ -256,7 +256,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "26a7a5df9647f79a1ca63706f09e15c9b1dba07cf87ff6606f3da4dda7db457d", "fetch_bytes": 274909263, "write_bytes": 322560}
+LMHEAD_TRAFFIC = {"source_sha256": "bbb3fe555e50b1f3faefb2948576dd4711e9a711579b7d9c7cda9a0103ac5031", "fetch_bytes": 274909111, "write_bytes": 322560}
 
 
 def main():

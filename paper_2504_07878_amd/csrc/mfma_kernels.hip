@@ -738,13 +738,18 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
     const bool many = rows.n * D.Hkv >= 64;
     if (D.G <= 8 && (many || (!consumer_merges && D.dh == 64))) {
         // enough (row, kv head) pairs to fill the chip with one workgroup each: parts of 768 keys (three key blocks per
-        // wavefront; measured best among 256..1024 on the ragged 64-sequence workload); fewer pairs: parts of 256 keys (one
-        // block per wavefront), so that more compute units take part. Longer parts when the partials buffer or the limit
-        // of 16 parts asks for it.
+        // wavefront; measured best among 256..1024 on the ragged 64-sequence workload); fewer pairs: parts of 512 keys, so
+        // that more compute units take part (0.5B-class step at 4 / 16 / 28 rows and contexts of ~1350: 1.031 / 1.049 / 1.063 ms;
+        // with 256 keys 1.025 / 1.046 / 1.172, with 768 keys 1.072 / 1.085 / 1.095). Longer parts when the partials buffer
+        // or the limit of 16 parts asks for it.
         size_t room = part_floats / ((size_t)rows.n * D.Hq * (D.dh + 4));
         if (room > 16) room = 16;
         if (room < 1) room = 1;
-        int span = many ? 768 : 256;
+        int span = 768;
+        if (!many) {   // parts of 512 keys, longer ones when the launch would otherwise exceed one round of 256 workgroups
+            const int max_parts = std::max(1, 256 / (rows.n * D.Hkv));
+            span = std::max(512, 256 * ((max_ctx + 256 * max_parts - 1) / (256 * max_parts)));
+        }
         if ((size_t)(max_ctx + span - 1) / span > room) span = 256 * (int)((max_ctx + 256 * room - 1) / (256 * room));
         const int P = (max_ctx + span - 1) / span;
         const dim3 grid(rows.n, D.Hkv, P);
