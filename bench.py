@@ -68,24 +68,25 @@ def time_decode(model, slots, tokens_per_step, steps, warmup, out):
     return dt, ms - gap_ms, launches, base, (ms, gap_ms)
 
 
-def cpu_baseline(s, weights, seconds_budget=20.0):
-    """The oracle, as it stands, on the host cores: decode steps of a few sequences over a synthetic cache."""
+def cpu_baseline(s, weights, seconds_budget=12.0, max_steps=600):
+    """The oracle, as it stands, on the host cores: decode steps of a few sequences over a synthetic cache, for about
+    `seconds_budget` seconds."""
     from oracle import tro
     from paper_2504_07878_amd import synth
     n_seq, ctx = 2, 576
-    o = tro.Model(s.asdict(), weights, n_seq, ctx + 64)
+    o = tro.Model(s.asdict(), weights, n_seq, ctx + max_steps)
     for b in range(n_seq):
         k, v = synth.kv_fill(SEED, f"cpu.kv{b}", s, ctx)
         o.load_kv(b, synth.bf16_bits_to_f32(k), synth.bf16_bits_to_f32(v))
     toks = synth.prompt_tokens(SEED, "cpu.toks", 64 * n_seq, s.vocab).reshape(64, n_seq)
     done, t0 = 0, time.perf_counter()
-    while done < 64 and time.perf_counter() - t0 < seconds_budget:
-        o.decode_step(list(range(n_seq)), toks[done])
+    while done < max_steps and time.perf_counter() - t0 < seconds_budget:
+        o.decode_step(list(range(n_seq)), toks[done % len(toks)])
         done += 1
     dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": n_seq * done / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"{done} decode steps of {n_seq} sequences at context {ctx} on a synthetic cache (0.5B-class bf16 weights, fp32 oracle)"}
+            "sample": f"{done} decode steps of {n_seq} sequences from context {ctx} on a synthetic cache, {dt:.1f} s (0.5B-class bf16 weights, fp32 oracle)"}
 
 
 def counters_workload(s):
