@@ -257,7 +257,7 @@ def measured_traffic():
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch of the LM-head kernel at 64 rows.
-LMHEAD_TRAFFIC = {"source_sha256": "bbb3fe555e50b1f3faefb2948576dd4711e9a711579b7d9c7cda9a0103ac5031", "fetch_bytes": 274909111, "write_bytes": 322560}
+LMHEAD_TRAFFIC = {"source_sha256": "baf73f74c39325fab69503b75ed3794206441a519fab932f2f932b0006062d1a", "fetch_bytes": 274909129, "write_bytes": 322560}
 
 
 def main():
