@@ -13,8 +13,13 @@
  * General conventions
  *  - Every function returns a status: TR_OK (0) or a negative TR_ERR_* code; nothing throws,
  *    aborts or prints. tr_last_error() gives the text of the last failure on a context.
- *  - On any error the context state (cache, sequence lengths, counters) is unchanged and no
- *    work has been enqueued.
+ *  - Errors of the caller (TR_ERR_INVALID_ARG, TR_ERR_SHAPE, TR_ERR_STATE, TR_ERR_CAPACITY) are detected
+ *    before anything is enqueued or changed: the context state (cache, page tables, sequence lengths,
+ *    counters) is exactly as before the call. TR_ERR_HIP (a failed launch or copy; the code may also
+ *    surface an earlier asynchronous failure of the HIP runtime) can occur after part of the call's work
+ *    has been enqueued: the sequence lengths are not advanced, but cache contents, page tables and
+ *    counters of the slots named in the call are undefined afterwards; reset those slots (tr_prefill)
+ *    or destroy the context.
  *  - "device" pointers are HIP device memory of the current device; "host" pointers are
  *    ordinary host memory. The library allocates no device memory and creates no stream: the
  *    caller hands in a workspace and a hipStream_t (as void*; NULL = the default stream).
@@ -50,7 +55,12 @@ enum { TR_POLICY_MLP = 0, TR_POLICY_CONFIDENCE = 1, TR_POLICY_LINEAR = 2 };
 typedef struct tr_ctx tr_ctx;
 
 /* Model and capacity description. The decoder is the pre-norm GQA / RoPE (half-split pairing) / SwiGLU
- * stack of the model family named in Section 4.2. */
+ * stack of the model family named in Section 4.2. Supported shapes (anything else: tr_workspace_bytes
+ * returns 0 and tr_create TR_ERR_SHAPE): head_dim 64 or 128; n_q_heads a multiple of n_kv_heads with at
+ * most 8 query heads per kv head; d_model and d_ffn multiples of 8; router_hidden <= 1024 (and
+ * d_model <= 4096 with a router). Every such shape runs on the streaming kernels; bf16 models whose
+ * d_model and d_ffn are multiples of 16 (d_ffn of 32 when d_model > 896) and d_model <= 4096 additionally
+ * run batches of 3 or more rows on the matrix cores. */
 typedef struct tr_config {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
     float rms_eps, rope_theta;
@@ -142,18 +152,20 @@ int tr_decode_step_dev(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *
                        const tr_out *out);
 
 /* Catch-up ("extend") step: each listed slot ingests the T >= 1 tokens of its segment, which another model
- * produced (Section 3.2, Figure 2: several rounds of prefill and decode inside one request; the prototype of
+ * produced (opening of Section 3 and Figure 2: several rounds of prefill and decode inside one request; the prototype of
  * Section 4.1 re-runs the whole prefix instead), at positions len .. len+T-1 over its existing cache, and
  * returns the outputs of the last of them: the same result as T decode steps of which only the last is
  * visible. The counters move as for one decode step. Segments are given like prompts: tokens_flat (HOST)
  * holds them back to back, offsets (HOST, n+1 entries, offsets[0] = 0) delimit them; row i of out belongs to
  * slots[i]. Errors (a slot without a cache, a segment that does not fit, an empty segment, a bad token) are
- * detected before anything is enqueued and leave all state unchanged. */
+ * detected before anything is enqueued and leave all state unchanged (TR_ERR_HIP: see the general conventions). */
 int tr_extend(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *tokens_flat,
               const int32_t *offsets, const tr_out *out);
 
 /* The routing tail alone on n rows of residual stream x (DEVICE, fp32 [n][d_model]): final RMSNorm, LM
- * head, softmax confidence + argmax, router, flag. Touches no sequence state and no counters.
+ * head, softmax confidence + argmax, router, flag, i.e. the "token routing selection module" of Section 3
+ * (MLP classifier on the last-layer hidden state and threshold rule of Section 3.1, hidden state exposed as
+ * in Section 3.3) applied to rows the caller supplies. Touches no sequence state and no counters.
  * n <= max_batch. */
 int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out);
 
@@ -161,7 +173,10 @@ int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_o
 int tr_set_threshold(tr_ctx *ctx, float threshold);
 int tr_set_mode(tr_ctx *ctx, int32_t mode);
 
-/* Host-side sequence state. tr_seq_truncate rolls a slot back to its first new_len tokens. */
+/* Host-side sequence state (infrastructure; the paper's request only carries the position as "token_index",
+ * Figure 5). tr_seq_len: number of cached tokens of a slot (0 for a slot never filled). tr_seq_truncate rolls a
+ * slot back to its first new_len tokens, 0 <= new_len <= length (a paged cache gives the freed pages back):
+ * the rollback a caller needs when a token is replaced after the fact; the cache management Section 3 asks for. */
 int tr_seq_len(const tr_ctx *ctx, int32_t slot, int32_t *len);
 int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len);
 
@@ -173,7 +188,10 @@ int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len);
 int tr_seq_fork(tr_ctx *ctx, void *hip_stream, int32_t src_slot, int32_t dst_slot);
 
 /* Overwrite a slot's cache with len tokens of given keys/values (DEVICE pointers in kv_dtype, layout
- * [layer][kv_head][len][head_dim], keys already rotated) and set its length; counters are cleared. */
+ * [layer][kv_head][len][head_dim], keys already rotated) and set its length; counters are cleared.
+ * Infrastructure (no passage of the paper): imports a cache computed elsewhere, e.g. the synthetic
+ * 2048-token contexts of the large-model workload. Errors: TR_ERR_CAPACITY (len outside [1, max_seq], or
+ * the page pool cannot supply the pages). */
 int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, const void *k, const void *v);
 
 /* Device address of the per-slot counters, int64 [max_batch][2] = {n_generated, n_routed}

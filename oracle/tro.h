@@ -90,7 +90,7 @@ int tro_prefill(tro_ctx *, int32_t n, const int32_t *slots, const int32_t *token
 /* One token per listed slot, attending over the slot's cache. */
 int tro_decode_step(tro_ctx *, int32_t n, const int32_t *slots, const int32_t *in_tokens, const tro_out *);
 /* Catch-up ("extend") step: each listed slot ingests the T >= 1 tokens of its segment, which some other model produced
- * (Section 3.2, Figure 2: several rounds of prefill and decode inside one request; the prototype of Section 4.1 re-runs
+ * (opening of Section 3 and Figure 2: several rounds of prefill and decode inside one request; the prototype of Section 4.1 re-runs
  * the whole prefix instead), at positions len .. len+T-1 over its existing cache. By definition this is T cached
  * decode steps of which only the last one is visible: its outputs are returned and the counters move as for one
  * decode step. Segments are given like prompts (tokens_flat, offsets[n+1]). */

@@ -28,6 +28,11 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 constexpr int NWAVES = 4;  // wavefronts per workgroup (one per SIMD, 512 registers each); they split K
 constexpr int MAXKW = 14;  // k-steps a wavefront keeps resident (4 wavefronts x 14 x 16 = 896 columns of K per workgroup)
 
+// Waits until every vector-memory operation this wavefront has issued (loads AND stores: gfx9-family parts count both in
+// vmcnt) has completed. After device-coherent (write-through) stores this is the point from which another workgroup's
+// device-coherent load returns the stored values.
+__device__ __forceinline__ void wait_vector_memory() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ bf16_t m_f32_to_bf16(float f)
 {
     uint32_t u = __float_as_uint(f);
@@ -586,9 +591,12 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
     if (parts > 1) {
         // leave this part's result, count in, and go on only as the last arrival of the row
         // The exchange goes through device-coherent accesses only (write-through stores, loads that bypass the
-        // non-coherent cache levels): each is visible device-wide once it has completed, so waiting for this
-        // wavefront's outstanding stores is all the ordering needed, and no cache is flushed or invalidated as a whole
-        // (a device-scope fence writes back the entire L2 of the XCD, far more than this exchange is worth).
+        // non-coherent cache levels): each is visible device-wide once it has completed. The ordering is made explicit:
+        // every storing wavefront waits until its outstanding vector-memory operations have been acknowledged (on this
+        // architecture the vector-memory counter covers stores) BEFORE the barrier that precedes the counter update, so
+        // the counter can only reach `parts` after every part's data has landed; the last arriver issues its loads only
+        // after its own read-modify-write has returned. No cache is flushed or invalidated as a whole (a device-scope
+        // release fence writes back the entire L2 of the XCD, far more than this exchange is worth).
         if (worker) {
             float *pp = part + (((size_t)r * D.Hq + g * G + h) * P + pt) * PS;
 #pragma unroll
@@ -598,7 +606,7 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
                 __hip_atomic_store(pp + DH + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // this wavefront's stores have completed
+        wait_vector_memory();   // this wavefront's device-coherent stores have been acknowledged
         __syncthreads();
         if (threadIdx.x == 0) {
             int *c = cnt + (size_t)r * D.Hkv + g;

@@ -312,7 +312,7 @@ __global__ __launch_bounds__(TF_THREADS) void tail_final_kernel(int d, int rh, T
         for (int w = 0; w < TF_WAVES; ++w) pre += s_ws[1][w];
         if (nparts > 1) {
             __hip_atomic_store(t.rpart + (size_t)i * nparts + part_id, pre, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");   // the store has completed
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the device-coherent store has been acknowledged (vmcnt counts stores on this architecture)
             const int old = __hip_atomic_fetch_add(t.rcnt + i, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (old != nparts - 1) return;
             __hip_atomic_store(t.rcnt + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // every part has counted: ready for the next launch

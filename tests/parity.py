@@ -43,7 +43,7 @@ def compare_outputs(g, o, dtype, threshold, what, route_dir_below=True, joint=Tr
         assert_rows_close(g.logits, o.logits, rtol, what + " logits")
     if o.hidden is not None and g.hidden is not None:
         assert_rows_close(g.hidden, o.hidden, rtol, what + " hidden")
-    assert np.allclose(g.conf, o.conf, rtol=rtol * 5 if dtype != synth.F32 else 1e-3, atol=0), (what, g.conf, o.conf)
+    assert np.allclose(g.conf, o.conf, rtol=rtol, atol=0), (what, g.conf, o.conf)
     assert np.allclose(g.score, o.score, rtol=0, atol=score_atol_of(dtype)), (what, g.score, o.score)
     for i in range(n):
         if g.token[i] != o.token[i]:

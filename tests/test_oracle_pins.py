@@ -467,11 +467,33 @@ def test_truncate_then_decode_reproduces_the_same_step(tro):
     assert np.array_equal(k_before[:, :8], k_after[:, :8])
 
 
-def test_fig5_example_fields_map_onto_counters():
+def test_fig5_example_fields_map_onto_counters(tro):
+    """Figure 5's example request, replayed on the oracle: its routing history lists two generated tokens, the first kept
+    from the small model and the second routed, the token being generated has 0-based index 15, and the request carries
+    its own threshold. A sequence driven to that state must report the counters (2, 1), the length 15, and flags that are
+    the comparison of its scores with the request's threshold."""
     rows = dict(l.split(None, 1) for l in open(os.path.join(GOLDEN, "fig5_api_example.txt")) if l.strip() and not l.startswith("#"))
     routes = rows["history_routes"].split()
-    assert int(rows["token_index"]) == 15 and float(rows["routing_threshold"]) == 0.7
-    assert (len(routes), routes.count("LLM")) == (2, 1)   # n_generated, n_routed of that history
+    token_index, tau = int(rows["token_index"]), float(rows["routing_threshold"])
+    s = small_shape()
+    m, _ = build(tro, s)
+    toks = synth.prompt_tokens(SEED, "fig5", token_index - len(routes), s.vocab)   # the history's tokens have indices 13 and 14
+    force = {"SLM": 0.0, "LLM": 1.0}            # no score in (0,1) is below 0; every score is below 1
+    m.set_threshold(force[routes[0]])
+    o = m.prefill([0], [toks])                  # emits history token 0
+    flags = [int(o.flag[0])]
+    for r in routes[1:]:
+        m.set_threshold(force[r])
+        o = m.decode_step([0], [int(o.token[0])])
+        flags.append(int(o.flag[0]))
+    assert flags == [int(r == "LLM") for r in routes]
+    assert m.counters(0) == (len(routes), routes.count("LLM")) == (2, 1)
+    assert m.seq_len(0) == token_index - 1      # tokens 0..13 are cached, token 14 is the next step's input
+    m.set_threshold(tau)                        # the request's own threshold decides the token being generated
+    o = m.decode_step([0], [int(o.token[0])])
+    assert m.seq_len(0) == token_index          # the token this step emitted has 0-based index 15
+    assert int(o.flag[0]) == int(float(o.score[0]) < np.float32(tau)) == tro.route_flag(float(o.score[0]), tau)
+    assert m.counters(0) == (3, 1 + int(o.flag[0]))
 
 
 def test_load_kv_then_decode_equals_prefilled_cache(tro):
@@ -485,7 +507,7 @@ def test_load_kv_then_decode_equals_prefilled_cache(tro):
     assert np.array_equal(a.logits, b.logits) and m.seq_len(1) == 7
 
 
-# ------------------------------------------------------------------ catch-up step (several rounds of prefill and decode, Section 3.2 / Figure 2)
+# ------------------------------------------------------------------ catch-up step (several rounds of prefill and decode: opening of Section 3, Figure 2)
 
 @pytest.mark.parametrize("kv_dtype", [synth.F32, synth.BF16])
 def test_extend_equals_brute_force_forward_of_the_whole_prefix(tro, kv_dtype):
