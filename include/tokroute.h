@@ -169,6 +169,18 @@ int tr_extend(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, co
  * n <= max_batch. */
 int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out);
 
+/* tr_tail for callers that cannot allocate or hand over device memory for scratch at the time of the call (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same computation and arguments, but
+ * every intermediate (normalised rows, per-slice softmax statistics, router partial sums and arrival counters) lives in
+ * a fixed array inside the library's own device image, 3.1 MB per GPU, held until the process ends; the context's
+ * workspace is not touched and nothing is allocated or freed, by the library or through any runtime call. Limits
+ * (TR_ERR_CAPACITY beyond them): n <= 64 rows, d_model <= 4096, vocab <= 262144. It always runs the streaming
+ * (vector-ALU) tail kernels on the borrowed weights, so for models whose tr_tail uses the matrix cores the outputs agree
+ * with tr_tail's to the library's floating-point tolerance rather than bit for bit; otherwise they are identical.
+ * All calls on one GPU share that GPU's array (whatever the context): calls that overlap in time on one GPU race;
+ * the caller serialises them (one stream, or events). Enqueues on the stream and returns, like tr_tail. */
+int tr_tail_noalloc(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out);
+
 /* Threshold slider and mode switch of Section 3.1; they apply to calls made afterwards. */
 int tr_set_threshold(tr_ctx *ctx, float threshold);
 int tr_set_mode(tr_ctx *ctx, int32_t mode);

@@ -358,6 +358,17 @@ void launch_reset_counters(hipStream_t s, long long *counters, int slot)
     hipLaunchKernelGGL(reset_counters_kernel, dim3(1), dim3(2), 0, s, counters, slot);
 }
 
+__global__ void fill_int_kernel(int *p, int n, int value)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+void launch_fill_int(hipStream_t s, int *p, int n, int value)
+{
+    hipLaunchKernelGGL(fill_int_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n, value);
+}
+
 // ------------------------------------------------------------------ embedding lookup: x[r] = E[tok[r]]
 
 template <typename WT>

@@ -14,6 +14,18 @@
 
 using namespace tr;
 
+// ---- scratch of the entry point that allocates nothing (tr_tail_noalloc): one fixed array per GPU, held until the
+// process ends. In host code the array's NAME is only a handle for the runtime: the device address is looked up once per
+// device with hipGetSymbolAddress and only that address is ever handed to kernels.
+constexpr int NOALLOC_MAX_ROWS = 64, NOALLOC_MAX_D = 4096, NOALLOC_MAX_SLICES = 2048;
+constexpr size_t NOALLOC_HN = 0;                                                              // [rows][d] normalised rows
+constexpr size_t NOALLOC_PART = NOALLOC_HN + (size_t)NOALLOC_MAX_ROWS * NOALLOC_MAX_D;        // [slices][rows] x 4 floats
+constexpr size_t NOALLOC_RPART = NOALLOC_PART + (size_t)NOALLOC_MAX_SLICES * NOALLOC_MAX_ROWS * 4;   // [rows][TAIL_ROUTER_PARTS]
+constexpr size_t NOALLOC_RCNT = NOALLOC_RPART + (size_t)NOALLOC_MAX_ROWS * TAIL_ROUTER_PARTS; // [rows] ints
+constexpr size_t NOALLOC_FLOATS = NOALLOC_RCNT + NOALLOC_MAX_ROWS;
+static __device__ __align__(256) float scratch[NOALLOC_FLOATS];
+
+
 namespace {
 
 constexpr size_t ALIGN = 256;
@@ -162,6 +174,27 @@ Layout make_layout(const tr_config *c)
     L.kvn = take(2 * 2 * kvw * 4);
     L.total = off;
     return L;
+}
+
+constexpr int MAX_DEVICES = 64;
+float *g_scratch_ptr[MAX_DEVICES];   // device address of `scratch` on each GPU, looked up on first use
+
+// Device address of the static scratch array on the current device (looked up once per device), or an error.
+hipError_t scratch_address(float **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        float *p = nullptr;
+        e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
 }
 
 }  // namespace
@@ -579,6 +612,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
         if (lay.router_tiles) launch_repack(nullptr, ctx->r_w1, D.rh, D.d, ctx->ws + lay.wt_head, (D.V + 31) / 32, 1, 0);
         e = hipMemset(ctx->ws + lay.pack_d, 0, lay.part - lay.pack_d);   // padding rows of the packed activations stay zero
     }
+    if (e == hipSuccess) { float *sc = nullptr; e = scratch_address(&sc); }   // static scratch of tr_tail_noalloc: address on this device
     // everything above ran on the null stream; the caller's streams need not be ordered after it, so finish it here
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipGetLastError();
@@ -765,6 +799,39 @@ int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_o
     run_tail(ctx, s, t, const_cast<float *>(x), 0, 0, n);   // no partials pending: x is only read
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_tail: launch");
+    return TR_OK;
+}
+
+int tr_tail_noalloc(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (!x || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_tail_noalloc: null argument");
+    if ((uintptr_t)x % 16) return fail(ctx, TR_ERR_INVALID_ARG, "tr_tail_noalloc: x must be 16-byte aligned");
+    const int nslices = (ctx->c.vocab + tail_slice_rows() - 1) / tail_slice_rows();
+    if (n < 1 || n > NOALLOC_MAX_ROWS) return fail(ctx, TR_ERR_CAPACITY, "tr_tail_noalloc: n outside [1, 64]");
+    if (ctx->c.d_model > NOALLOC_MAX_D || nslices > NOALLOC_MAX_SLICES)
+        return fail(ctx, TR_ERR_CAPACITY, "tr_tail_noalloc: d_model above 4096 or vocabulary above 262144");
+    float *sc = nullptr;
+    const hipError_t ea = scratch_address(&sc);
+    if (ea != hipSuccess) return fail_hip(ctx, ea, "tr_tail_noalloc: hipGetSymbolAddress");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    TailArgs t = tail_args(ctx, out, 0, n);
+    t.gather = nullptr;
+    t.slot = nullptr;
+    t.counters = nullptr;
+    t.counter_mode = 0;
+    t.x = x;
+    t.hn = sc + NOALLOC_HN;
+    t.part = sc + NOALLOC_PART;
+    t.nslices = nslices;
+    t.rpart = sc + NOALLOC_RPART;
+    t.rcnt = reinterpret_cast<int *>(sc + NOALLOC_RCNT);
+    // the array keeps what the last call left: the arrival counters must start at zero (a fill kernel, not a memset node,
+    // so that the call can be captured into a graph)
+    launch_fill_int(s, t.rcnt, n, 0);
+    launch_tail(s, ctx->c.dtype, ctx->D, t, nullptr, nullptr, nullptr);   // the streaming kernels, on the borrowed weights
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_tail_noalloc: launch");
     return TR_OK;
 }
 

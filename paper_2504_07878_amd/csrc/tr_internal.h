@@ -142,6 +142,7 @@ void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const fl
 void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1, hipEvent_t ev2);
 void launch_load_kv(hipStream_t s, int kdt, const Dims &D, int slot, int len, const void *k, const void *v, void *kc, void *vc);
 void launch_reset_counters(hipStream_t s, long long *counters, int slot);
+void launch_fill_int(hipStream_t s, int *p, int n, int value);   // p[0..n) = value
 
 int tail_slice_rows();
 void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);

@@ -22,7 +22,7 @@ ROUTE_IF_BELOW, ROUTE_IF_ABOVE = 0, 1
 POLICY_MLP, POLICY_CONFIDENCE, POLICY_LINEAR = 0, 1, 2
 POST_FINAL_NORM, PRE_FINAL_NORM = 0, 1
 
-EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_decode_step_dev", "tr_extend", "tr_tail", "tr_set_threshold",
+EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_decode_step_dev", "tr_extend", "tr_tail", "tr_tail_noalloc", "tr_set_threshold",
            "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_fork", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable",
            "tr_profile_read", "tr_last_error"]
 
@@ -68,6 +68,7 @@ def load_library():
         L.tr_decode_step.argtypes = [vp, vp, i32, vp, vp, C.POINTER(tr_out)]
         L.tr_decode_step_dev.argtypes = [vp, vp, i32, vp, vp, C.POINTER(tr_out)]
         L.tr_tail.argtypes = [vp, vp, i32, vp, C.POINTER(tr_out)]
+        L.tr_tail_noalloc.argtypes = [vp, vp, i32, vp, C.POINTER(tr_out)]
         L.tr_set_threshold.argtypes = [vp, f32]
         L.tr_set_mode.argtypes = [vp, i32]
         L.tr_seq_len.argtypes = [vp, i32, C.POINTER(i32)]
@@ -232,6 +233,12 @@ class Model:
         assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.shape[1] == self.shape["d_model"]
         out = out or self.outputs(x.shape[0], want_logits)
         self._check(self.lib.tr_tail(self._h, self._stream(), x.shape[0], x.data_ptr(), C.byref(out.struct)), "tr_tail")
+        return out
+
+    def tail_noalloc(self, x: torch.Tensor, out: Outputs):
+        """tr_tail with the library's static device scratch; `out` must exist already (nothing is allocated here)."""
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.shape[1] == self.shape["d_model"]
+        self._check(self.lib.tr_tail_noalloc(self._h, self._stream(), x.shape[0], x.data_ptr(), C.byref(out.struct)), "tr_tail_noalloc")
         return out
 
     def set_threshold(self, t):
