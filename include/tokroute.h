@@ -151,6 +151,29 @@ int tr_decode_step(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slot
 int tr_decode_step_dev(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *in_tokens_dev,
                        const tr_out *out);
 
+/* Decode step of the sequences that DEVICE-side flags select: the alternation of the two models inside one request
+ * (opening of Section 3, Figure 2; Section 3.1: a flagged token is produced by the large model) without a trip of the
+ * flags to the host. The caller names n candidate slots (HOST array, distinct, at most 256); flags_dev and in_tokens_dev
+ * are DEVICE int32 arrays [n], typically the flag output of the small model's step and the tokens the large model has to
+ * ingest. The candidates whose flag is non-zero are taken in increasing index, at most n_max of them (3 <= n_max <=
+ * max_batch): each takes one decode step exactly like tr_decode_step (input token appended at the slot's length,
+ * counters updated). Everything is enqueued with launches sized for n_max rows; rows past the number taken are padding
+ * that changes no state, and when no candidate is flagged the large kernels return at once.
+ * Outputs: row r of out (n_max rows) belongs to the r-th taken candidate; padding rows report token -1, conf 0, score 0,
+ * flag 0. active_dev (DEVICE int32 [2 + n_max], required): [0] = rows taken, [1] = candidates flagged (larger than [0]
+ * when more than n_max were flagged: those were NOT stepped; call again), [2 + r] = candidate index of row r (-1 for
+ * padding). next_tokens_dev (DEVICE int32 [n] or NULL): entry i receives the emitted token if candidate i was taken and
+ * is left alone otherwise: pass the small model's next-input buffer and the large model's token replaces the small model's.
+ * Sequence lengths: which slots grew is only known on the device. The library keeps a device-side length array and
+ * brings the host's lengths up to date, by synchronising the stream of the last such call, inside the next call that
+ * needs them (tr_seq_len, tr_prefill, tr_decode_step, tr_extend, ...); consecutive tr_decode_step_active calls need no
+ * synchronisation. Until then a candidate slot is assumed to have grown in every call (capacity check).
+ * Needs a bf16 model that runs on the matrix cores and a contiguous cache (TR_ERR_SHAPE otherwise). Errors:
+ * TR_ERR_INVALID_ARG, TR_ERR_STATE (candidate never prefilled), TR_ERR_CAPACITY (a candidate may be full). */
+int tr_decode_step_active(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *flags_dev,
+                          const int32_t *in_tokens_dev, int32_t n_max, int32_t *active_dev, int32_t *next_tokens_dev,
+                          const tr_out *out);
+
 /* Catch-up ("extend") step: each listed slot ingests the T >= 1 tokens of its segment, which another model
  * produced (opening of Section 3 and Figure 2: several rounds of prefill and decode inside one request; the prototype of
  * Section 4.1 re-runs the whole prefix instead), at positions len .. len+T-1 over its existing cache, and
@@ -211,12 +234,28 @@ int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, con
  * kernel; read them with a device-to-host copy after synchronising. */
 int tr_counters_ptr(const tr_ctx *ctx, const int64_t **dev_counters);
 
-/* Kernel timing for benchmarks: while enabled, the LM-head kernel of every tail launch is bracketed by
- * two HIP events on the launch stream, and a third event is recorded straight after the second, so that
- * the cost of an event pair with nothing in between is measured in the same place of the same stream.
- * tr_profile_read synchronises those events and returns, summed over the launches since enabling, the
- * bracketed duration (ms_total) and the empty intervals (ms_empty_pairs), in milliseconds, and the
- * number of launches: (ms_total - ms_empty_pairs) / launches estimates the kernel's own duration. */
+/* Kernel timing for benchmarks (infrastructure). The launches of a step belong to kernel families (TR_KERNEL_*);
+ * while timing is enabled, ONE launch of the selected family per call (tr_decode_step, tr_tail, each pass of
+ * tr_prefill / tr_extend) is bracketed by two HIP events on the launch stream, and a third event is recorded straight
+ * after the second, so that the cost of an event pair with nothing in between is measured in the same place of the
+ * same stream. A family with several launches per call (one per layer) is sampled in turn: call k brackets launch
+ * k mod (launches per call), so the timed launch costs every call the same overhead whatever the family.
+ * tr_profile_select chooses the family (default TR_KERNEL_LMHEAD) and clears the sums. tr_profile_read synchronises the
+ * events and returns, summed over the bracketed launches since enabling, the bracketed duration (ms_total) and the
+ * empty intervals (ms_empty_pairs), in milliseconds, and their number: (ms_total - ms_empty_pairs) / launches
+ * estimates the duration of one launch of the family. */
+enum { TR_KERNEL_SETUP = 0,      /* row set-up + embedding lookup */
+       TR_KERNEL_PREP,           /* residual update + RMSNorm (+ pack) ahead of a matrix-core layer; final norm of the tail */
+       TR_KERNEL_QKV,            /* q|k|v projection, rotary embedding, cache append */
+       TR_KERNEL_ATTENTION,      /* attention over the cache (and its merge kernel where there is one) */
+       TR_KERNEL_OPROJ,          /* attention output projection */
+       TR_KERNEL_GATEUP,         /* gate/up projections + SwiGLU */
+       TR_KERNEL_DOWN,           /* FFN output projection */
+       TR_KERNEL_LMHEAD,         /* LM head with the running softmax statistics */
+       TR_KERNEL_TAIL_MERGE,     /* merge of the slices, router, flag, counters */
+       TR_KERNEL_QKV_ATTENTION,  /* 1-2 row steps: projection and attention in one launch */
+       TR_KERNEL_FAMILIES };
+int tr_profile_select(tr_ctx *ctx, int32_t family);
 int tr_profile_enable(tr_ctx *ctx, int32_t on);
 int tr_profile_read(tr_ctx *ctx, double *ms_total, double *ms_empty_pairs, int64_t *launches);
 

@@ -369,6 +369,55 @@ void launch_fill_int(hipStream_t s, int *p, int n, int value)
     hipLaunchKernelGGL(fill_int_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n, value);
 }
 
+// ------------------------------------------------------------------ device-side selection of a step's rows
+// (the flags a router left in device memory pick the sequences the other model steps; the host never sees them)
+
+struct ActiveArgs {
+    int n;
+    int slot[256], len[256];   // candidates: slot, and its length where the host knows it (-1: the device-side array is ahead of the host)
+};
+
+__global__ __launch_bounds__(256) void active_setup_kernel(ActiveArgs a, const int *flags, const int *tokens, int n_max, int vocab, int *dev_len,
+                                                           int *d_slot, int *d_tok, int *d_pos, int *active)
+{
+    __shared__ int s_scan[256];
+    const int i = threadIdx.x;
+    const bool cand = i < a.n;
+    const int f = cand && flags[i] != 0 ? 1 : 0;
+    if (cand && a.len[i] >= 0) dev_len[a.slot[i]] = a.len[i];   // slots are distinct: one writer per entry
+    s_scan[i] = f;
+    __syncthreads();
+    for (int o = 1; o < 256; o <<= 1) {   // inclusive scan in a fixed order
+        const int v = i >= o ? s_scan[i - o] : 0;
+        __syncthreads();
+        s_scan[i] += v;
+        __syncthreads();
+    }
+    const int total = s_scan[255], count = min(total, n_max), rank = s_scan[i] - f;
+    if (f && rank < n_max) {
+        const int slot = a.slot[i], len = dev_len[slot];   // this thread's own write above, or the value an earlier step left
+        d_slot[rank] = slot;
+        d_pos[rank] = len;
+        d_tok[rank] = min(max(tokens[i], 0), vocab - 1);
+        dev_len[slot] = len + 1;
+        active[2 + rank] = i;
+    }
+    for (int r = count + i; r < n_max; r += 256) {   // padding rows: a valid slot at position 0, no state changes
+        d_slot[r] = a.slot[0]; d_pos[r] = 0; d_tok[r] = 0;
+        active[2 + r] = -1;
+    }
+    if (i == 0) { active[0] = count; active[1] = total; }
+}
+
+void launch_active_setup(hipStream_t s, int n, const int *cand_slot, const int *host_len, const int *flags_dev, const int *tokens_dev, int n_max,
+                         int vocab, int *dev_len, int *d_slot, int *d_tok, int *d_pos, int *active)
+{
+    ActiveArgs a;
+    a.n = n;
+    for (int i = 0; i < 256; ++i) { a.slot[i] = i < n ? cand_slot[i] : 0; a.len[i] = i < n ? host_len[i] : -1; }
+    hipLaunchKernelGGL(active_setup_kernel, dim3(1), dim3(256), 0, s, a, flags_dev, tokens_dev, n_max, vocab, dev_len, d_slot, d_tok, d_pos, active);
+}
+
 // ------------------------------------------------------------------ embedding lookup: x[r] = E[tok[r]]
 
 template <typename WT>

@@ -497,6 +497,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(Dims D, const float *q, 
     constexpr int DB = DH / 32, PS = DH + 4;
     const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (item >= rows.n * nchunks) return;
+    if (rows.live && *rows.live == 0) return;   // uniform over the launch
     const int r = __builtin_amdgcn_readfirstlane(item / nchunks), c = item % nchunks, g = blockIdx.y;   // one row per wavefront
     const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
     const int ctx = rows.pos[r] + 1;
@@ -549,6 +550,7 @@ __global__ __launch_bounds__(64 * ATT_ROW_WAVES) void attn_rows_kernel(Dims D, c
     __shared__ int s_last;
     const int r = blockIdx.x, g = blockIdx.y, pt = blockIdx.z, P = gridDim.z, wv = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63, j = lane & 31, hf = lane >> 5, G = D.G;
+    if (rows.live && *rows.live == 0) return;   // uniform over the launch, before any barrier
     const int ctx = rows.pos[r] + 1;
     const int slot = rows.slot[r];
     const int parts = (ctx + span - 1) / span;        // parts this row is split into: as few as the longest part allows ...
@@ -806,6 +808,7 @@ struct GemmArgs {
     int M;              // rows in total (groups of 64 along gridDim.z)
     int half;           // 1: every 64-row group is served by two workgroups of 32 rows each (more workgroups for short tile ranges)
     int remap_groups;   // > 0: 1-D grid; the row groups of one tile range are placed on the same XCD, next to each other in time
+    const int *live;    // device-side row count or NULL: with zero live rows the whole launch returns at once
 };
 
 // Epilogues receive, per thread, 8 consecutive output features (rows i0..i0+7 of tile t) of one batch row. PAR is the
@@ -845,12 +848,14 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
     int page, maxp;
     int rpos, runit, rupos;   // position of this thread's batch row (for the rotation) and where its key and value go:
                               // storage unit and position inside it, fetched ahead of the weight stream
+    const int *live;          // device-side row count or NULL: rows from *live on are padding and store nothing
     __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void row(int m)
     {
         rpos = pos[min(m, M - 1)]; runit = slot[min(m, M - 1)]; rupos = rpos;
         if (page) { runit = ptab[(size_t)runit * maxp + rpos / page]; rupos = rpos % page; }
+        if (live) M = min(M, *live);
     }
     // v: tile rows i0..i0+7 = the pairs (j, j + dh/2), j = 16*sub + i0/2 .. +3, as (first, partner) x 4
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
@@ -1023,6 +1028,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 {
     constexpr int NCO = NCB / 2;
     __shared__ __attribute__((aligned(16))) float red[2 * RED_FLOATS];
+    if (a.live && *a.live == 0) return;   // uniform over the launch
     Epi epi = epi_in;   // per-thread epilogue state lives in registers
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int ks0 = blockIdx.y * a.ksw, ks1 = min(a.KS, ks0 + a.ksw);
@@ -1176,6 +1182,7 @@ template <int KW2, class Epi>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm22_kernel(GemmArgs a, Epi epi_in)
 {
     __shared__ float4 xb[2][NWAVES][2][64];
+    if (a.live && *a.live == 0) return;   // uniform over the launch
     Epi epi = epi_in;   // per-thread epilogue state lives in registers
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // uniform: everything derived from it stays in scalar registers
     const int lane = threadIdx.x & 63, kh = wave & 1, rh = wave >> 1, hf = lane >> 5;
@@ -1335,6 +1342,7 @@ __global__ __launch_bounds__(256) void qkv_finish_kernel(Dims D, const float *pa
                                                          float *q, KT *kc, KT *vc)
 {
     const int m = blockIdx.y, half = D.dh / 2, N = D.qw + 2 * D.kvw, npairs = (D.Hq + 2 * D.Hkv) * half;
+    if (rows.live && m >= *rows.live) return;   // padding row: nothing is appended to any cache (its q is never used)
     const int pos = rows.pos[m];
     const KvPlace at = kv_place(D, rows.slot[m], pos);
     for (int pr = blockIdx.x * blockDim.x + threadIdx.x; pr < npairs; pr += gridDim.x * blockDim.x) {
@@ -1509,10 +1517,10 @@ size_t gemm_partial_floats(int K, int N, int max_rows)
     return most;
 }
 
-void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out)
+void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out, const int *live)
 {
     GemmArgs a{};
-    a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = K / 16; a.n_tiles = (N + 31) / 32; a.M = M;
+    a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = K / 16; a.n_tiles = (N + 31) / 32; a.M = M; a.live = live;
     int S, ksw, tpw;
     plan_partial(a.KS, a.n_tiles, (M + 63) / 64, &S, &ksw, &tpw);
     a.ksw = ksw; a.tiles_per_wg = tpw;
@@ -1528,21 +1536,22 @@ void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, cons
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = (D.qw + 2 * D.kvw) / 32; a.M = rows.n;
     a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, rows.n > 32 ? 2 * ((rows.n + 63) / 64) : 1, 1);
     a.half = 1;
+    a.live = rows.live;
     if (kdt == DT_F32) {
         EpiQkv<float> e{bias, rope, rows.slot, rows.pos, q, (float *)kc, (float *)vc, rows.n, D.Hq, D.Hkv, D.dh, kv_unit_len(D), D.qw, kv_unit_vts(D),
-                        D.ptab, D.page, D.maxp, 0, 0, 0};
+                        D.ptab, D.page, D.maxp, 0, 0, 0, rows.live};
         launch_gemm(s, a, 1, e);
     } else {
         EpiQkv<bf16_t> e{bias, rope, rows.slot, rows.pos, q, (bf16_t *)kc, (bf16_t *)vc, rows.n, D.Hq, D.Hkv, D.dh, kv_unit_len(D), D.qw, kv_unit_vts(D),
-                         D.ptab, D.page, D.maxp, 0, 0, 0};
+                         D.ptab, D.page, D.maxp, 0, 0, 0, rows.live};
         launch_gemm(s, a, 1, e);
     }
 }
 
-void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack)
+void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack, const int *live)
 {
     GemmArgs a{};
-    a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = 2 * ((D.F + 31) / 32); a.M = M;
+    a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = 2 * ((D.F + 31) / 32); a.M = M; a.live = live;
     a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, (M + 63) / 64, 2);   // whole gate/up pairs
     if (D.F % 32) {
         EpiSwiglu<true> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}};
@@ -1567,9 +1576,11 @@ int lmhead_mfma_wgs(int V, int router_tiles, int M)
     return (n_tiles + tpw - 1) / tpw;
 }
 
-void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits, float *r1, int router_tiles)
+void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits, float *r1, int router_tiles,
+                        const int *live)
 {
     GemmArgs a{};
+    a.live = live;
     const int vt = (D.V + 31) / 32;
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = vt + router_tiles; a.M = M;
     a.tiles_per_wg = lmhead_tiles_per_wg(a.n_tiles, M);

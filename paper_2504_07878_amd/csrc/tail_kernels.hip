@@ -298,12 +298,15 @@ __global__ __launch_bounds__(TF_THREADS) void tail_final_kernel(int d, int rh, T
     }
     __syncthreads();
     if (tid != 0) return;
+    // padding row of a launch sized before the row count was known: fixed outputs, nothing counted or scattered
+    const bool dead = t.live && i >= *t.live;
     float conf = 0.f;
     if (part_id == 0) {
         float Ssum = 0.f;
         for (int w = 0; w < TF_WAVES; ++w) Ssum += s_ws[0][w];
         conf = 1.0f / Ssum;
-        t.token[i] = I; t.conf[i] = conf;
+        t.token[i] = dead ? -1 : I; t.conf[i] = dead ? 0.f : conf;
+        if (t.scatter && !dead) t.scatter[t.cand[i]] = I;
     }
     float score = 1.0f;
     int flag = 0;
@@ -325,6 +328,7 @@ __global__ __launch_bounds__(TF_THREADS) void tail_final_kernel(int d, int rh, T
         score = conf;
     }
     if ((mlp || linear || t.policy == 1) && t.mode == 0) flag = t.route_dir == 0 ? (score < t.threshold) : (score > t.threshold);
+    if (dead) { t.score[i] = 0.f; t.flag[i] = 0; return; }
     t.score[i] = score; t.flag[i] = flag;
     if (t.counters && t.counter_mode) {
         long long *c = t.counters + 2 * (size_t)t.slot[i];
@@ -363,8 +367,7 @@ void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
     else hipLaunchKernelGGL(tail_final_kernel<bf16_t>, dim3(t.n, parts), dim3(TF_THREADS), 0, s, D.d, D.rh, t);
 }
 
-// the all-streaming tail: norm, LM head slices, merge + router
-void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1, hipEvent_t ev2)
+void launch_tail_norm(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
 {
     if (wdt == DT_F32)
         hipLaunchKernelGGL(tail_norm_kernel<float>, dim3(t.n), dim3(256), 0, s, D.d, D.eps, (const float *)t.final_norm, t.x, t.gather, t.hn,
@@ -372,10 +375,13 @@ void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEv
     else
         hipLaunchKernelGGL(tail_norm_kernel<bf16_t>, dim3(t.n), dim3(256), 0, s, D.d, D.eps, (const bf16_t *)t.final_norm, t.x, t.gather, t.hn,
                            t.hidden, t.hidden_tap);
-    if (ev0) (void)hipEventRecord(ev0, s);
+}
+
+// the all-streaming tail: norm, LM head slices, merge + router
+void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t)
+{
+    launch_tail_norm(s, wdt, D, t);
     launch_lmhead_gemv(s, wdt, D, t);
-    if (ev1) (void)hipEventRecord(ev1, s);
-    if (ev2) (void)hipEventRecord(ev2, s);
     launch_tail_final(s, wdt, D, t);
 }
 

@@ -42,6 +42,7 @@ struct Layout {
     int router_tiles;  // tiles of router weight rows appended to the repacked head matrix (0: the merge kernel computes the router itself)
     size_t qblock;     // query-row blocks of a pass (prompts, catch-up segments): first row * 8 + rows
     size_t kvn;        // new keys and values of up to two decode rows, [row][2][kv width] floats (fused q|k|v + attention kernel)
+    size_t dev_len;    // device-side sequence lengths [max_batch], used by the steps whose rows are selected on the device
     int maxp, pool;    // pages per slot (table row length) and pages in the pool; 0 for the contiguous cache
     int max_rows, nslices;
     // matrix-core paths: repacked weights, packed activations, split-K partials.
@@ -172,6 +173,7 @@ Layout make_layout(const tr_config *c)
     }
     L.qblock = take(R * 4);
     L.kvn = take(2 * 2 * kvw * 4);
+    L.dev_len = take((size_t)c->max_batch * 4);
     L.total = off;
     return L;
 }
@@ -209,15 +211,27 @@ struct tr_ctx {
     std::vector<int> len;   // -1 = never prefilled
     KvPages pages;          // paged cache only (c.kv_page > 0)
     int qblocks = 0;        // > 0: the rows of the current pass are grouped into this many query-row blocks (see ingest)
+    // Steps whose rows are selected on the device (tr_decode_step_active) advance the lengths of the selected slots in a device
+    // array; the host does not know which slots those were. Until the next call that needs lengths, len[] of a candidate slot
+    // is what the host last knew, ahead[] counts the steps it may have taken since, and the device array is the truth.
+    std::vector<int> ahead;
+    bool unsynced = false;
+    hipStream_t active_stream = nullptr;
+    const int *live = nullptr;       // device-side row count of the pass being enqueued (NULL: every row is live)
+    const int *cand = nullptr;       // ... and the candidate index of each of its rows, for the token scatter
+    int32_t *scatter = nullptr;
     float threshold;
     int mode;
     std::string err;
-    // kernel timing
+    // kernel timing: while enabled, ONE launch of the selected kernel family per call is bracketed by events (the launches of
+    // the family take turns from call to call, so that every layer is sampled)
     bool profile = false;
     std::vector<hipEvent_t> ev;   // triples: before the kernel, after it, and once more straight away
     size_t ev_used = 0;
     double prof_ms = 0.0, prof_gap_ms = 0.0;
     long long prof_launches = 0;
+    int prof_family = TR_KERNEL_LMHEAD;
+    int prof_seen = 0, prof_pick = 0;   // launches of the family seen in this call; the one to bracket
 
     template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
     void *kc_layer(int l) const { return ws + lay.kc + (size_t)l * lay.k_layer_bytes; }
@@ -282,6 +296,35 @@ void next_events(tr_ctx *ctx, hipEvent_t *e0, hipEvent_t *e1, hipEvent_t *e2)
     ctx->ev_used += 3;
 }
 
+// Brackets the launches made during its lifetime with events when they belong to the selected family and it is this
+// launch's turn (see tr_ctx::prof_pick).
+struct Bracket {
+    hipStream_t s;
+    hipEvent_t e1 = nullptr, e2 = nullptr;
+    Bracket(tr_ctx *ctx, hipStream_t stream, int family) : s(stream)
+    {
+        if (!ctx->profile || family != ctx->prof_family) return;
+        if (ctx->prof_seen++ != ctx->prof_pick) return;
+        hipEvent_t e0;
+        next_events(ctx, &e0, &e1, &e2);
+        if (e0) (void)hipEventRecord(e0, s);
+    }
+    ~Bracket()
+    {
+        if (e1) (void)hipEventRecord(e1, s);
+        if (e2) (void)hipEventRecord(e2, s);
+    }
+    Bracket(const Bracket &) = delete;
+    Bracket &operator=(const Bracket &) = delete;
+};
+
+// End of a call's launches: the next call brackets the family's next launch.
+void profile_next_turn(tr_ctx *ctx)
+{
+    if (ctx->profile) ctx->prof_pick = ctx->prof_seen > 0 ? (ctx->prof_pick + 1) % ctx->prof_seen : 0;
+    ctx->prof_seen = 0;
+}
+
 // All layers over the rows currently described by the device row arrays. Returns the number of split-K partial
 // buffers of the last down projection that still have to be added to the residual stream (matrix-core path).
 // distinct_slots: every row belongs to a different slot (a decode step), so no row reads a key another row appends.
@@ -289,13 +332,15 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
 {
     const Dims &D = ctx->D;
     const Layout &L = ctx->lay;
-    Rows rows{ctx->at<int>(L.slot), ctx->at<int>(L.pos), ctx->at<int>(L.tok), R};
+    Rows rows{ctx->at<int>(L.slot), ctx->at<int>(L.pos), ctx->at<int>(L.tok), R, ctx->live};
+    const int *live = ctx->live;
     float *x = ctx->at<float>(L.x), *q = ctx->at<float>(L.q), *att = ctx->at<float>(L.att), *h = ctx->at<float>(L.h);
     const size_t attn_part_floats = R <= ctx->c.max_batch ? L.attn_part_floats : 0;
-    if (embed) launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x);
+    if (embed) { Bracket br(ctx, s, TR_KERNEL_SETUP); launch_embed(s, ctx->c.dtype, ctx->tok_emb, rows.tok, R, D.d, x); }
     // attention of one layer: blocks of query rows that share their keys when the pass was grouped that way, rows one by one otherwise
     auto attend = [&](int l, const float *q_, Rows rows_, int max_ctx_, float *part_, size_t part_floats_, int *cnt_, float *att_, void *pack_, int ncb_,
                       AttnPending *defer_) {
+        Bracket br(ctx, s, TR_KERNEL_ATTENTION);
         if (ctx->qblocks > 0) {
             if (defer_) defer_->nchunks = 0;
             launch_attention_blocks(s, D, q_, ctx->kc_layer(l), ctx->vc_layer(l), rows_, ctx->at<int>(L.qblock), ctx->qblocks, att_, pack_, ncb_);
@@ -313,17 +358,23 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
             PrepArgs p{};
             p.x = x; p.row0 = 0; p.part = part; p.nsplit = pending; p.part_M = R; p.M = R; p.d = D.d; p.eps = D.eps;
             p.gain = (const bf16_t *)w.ln1; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = ncb;
-            launch_prep(s, p);
-            launch_gemm_partial(s, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), D.d, D.qw + 2 * D.kvw, R, part, &ns);
-            launch_qkv_finish(s, ctx->c.kv_dtype, D, part, ns, ctx->bias(l), rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+            { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
+            {
+                Bracket br(ctx, s, TR_KERNEL_QKV);
+                launch_gemm_partial(s, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), D.d, D.qw + 2 * D.kvw, R, part, &ns, live);
+                launch_qkv_finish(s, ctx->c.kv_dtype, D, part, ns, ctx->bias(l), rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+            }
             attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                              attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
-            launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
+            { Bracket br(ctx, s, TR_KERNEL_OPROJ); launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending, live); }
             p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
-            launch_prep(s, p);
-            launch_gemm_partial(s, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), D.d, 2 * ((D.F + 31) / 32) * 32, R, part, &ns);
-            launch_swiglu_finish(s, D, part, ns, R, ctx->at<uint4>(L.pack_h));
-            launch_gemm_partial(s, ctx->wt(l, L.wt_d), ctx->at<uint4>(L.pack_h), D.F, D.d, R, part, &pending);
+            { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
+            {
+                Bracket br(ctx, s, TR_KERNEL_GATEUP);
+                launch_gemm_partial(s, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), D.d, 2 * ((D.F + 31) / 32) * 32, R, part, &ns, live);
+                launch_swiglu_finish(s, D, part, ns, R, ctx->at<uint4>(L.pack_h));
+            }
+            { Bracket br(ctx, s, TR_KERNEL_DOWN); launch_gemm_partial(s, ctx->wt(l, L.wt_d), ctx->at<uint4>(L.pack_h), D.F, D.d, R, part, &pending, live); }
         }
         return pending;
     }
@@ -332,15 +383,20 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
             // one or two rows of a decode step: projection and attention over the cached keys in one launch, merged by the output projection
-            if (!(distinct_slots && launch_qkv_attention(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, max_ctx, ctx->at<float2>(L.rope), q, ctx->kc_layer(l),
-                                                         ctx->vc_layer(l), ctx->at<float>(L.attn_part), attn_part_floats, ctx->at<float>(L.kvn), &pend))) {
-                launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+            bool fused = false;
+            if (distinct_slots) {
+                Bracket br(ctx, s, TR_KERNEL_QKV_ATTENTION);
+                fused = launch_qkv_attention(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, max_ctx, ctx->at<float2>(L.rope), q, ctx->kc_layer(l),
+                                             ctx->vc_layer(l), ctx->at<float>(L.attn_part), attn_part_floats, ctx->at<float>(L.kvn), &pend);
+            }
+            if (!fused) {
+                { Bracket br(ctx, s, TR_KERNEL_QKV); launch_qkv(s, ctx->c.dtype, ctx->c.kv_dtype, D, w, x, rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l)); }
                 attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                                  attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, &pend);
             }
-            launch_oproj(s, ctx->c.dtype, D, w.wo, att, pend, R, x);
-            launch_gateup(s, ctx->c.dtype, D, w, x, R, h);
-            launch_down(s, ctx->c.dtype, D, w.wd, h, R, x);
+            { Bracket br(ctx, s, TR_KERNEL_OPROJ); launch_oproj(s, ctx->c.dtype, D, w.wo, att, pend, R, x); }
+            { Bracket br(ctx, s, TR_KERNEL_GATEUP); launch_gateup(s, ctx->c.dtype, D, w, x, R, h); }
+            { Bracket br(ctx, s, TR_KERNEL_DOWN); launch_down(s, ctx->c.dtype, D, w.wd, h, R, x); }
         }
         return 0;
     }
@@ -352,16 +408,19 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         PrepArgs p{};
         p.x = x; p.row0 = 0; p.part = part; p.nsplit = pending; p.part_M = R; p.M = R; p.d = D.d; p.eps = D.eps;
         p.gain = (const bf16_t *)w.ln1; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = ncb;
-        launch_prep(s, p);
-        launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
-                        ctx->kc_layer(l), ctx->vc_layer(l));
+        { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
+        {
+            Bracket br(ctx, s, TR_KERNEL_QKV);
+            launch_gemm_qkv(s, ctx->c.kv_dtype, D, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), ctx->bias(l), rows, ctx->at<float2>(L.rope), q,
+                            ctx->kc_layer(l), ctx->vc_layer(l));
+        }
         attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                          attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
-        launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending);
+        { Bracket br(ctx, s, TR_KERNEL_OPROJ); launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending, live); }
         p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
-        launch_prep(s, p);
-        launch_gemm_swiglu(s, D, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), R, ctx->at<uint4>(L.pack_h));
-        launch_gemm_partial(s, ctx->wt(l, L.wt_d), ctx->at<uint4>(L.pack_h), D.F, D.d, R, part, &pending);
+        { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
+        { Bracket br(ctx, s, TR_KERNEL_GATEUP); launch_gemm_swiglu(s, D, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), R, ctx->at<uint4>(L.pack_h), live); }
+        { Bracket br(ctx, s, TR_KERNEL_DOWN); launch_gemm_partial(s, ctx->wt(l, L.wt_d), ctx->at<uint4>(L.pack_h), D.F, D.d, R, part, &pending, live); }
     }
     return pending;
 }
@@ -372,8 +431,6 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
 {
     const Dims &D = ctx->D;
     const Layout &L = ctx->lay;
-    hipEvent_t e0, e1, e2;
-    next_events(ctx, &e0, &e1, &e2);
     if (ctx->lay.split_head && t.n > 2) {
         // wide model, more rows than one pass of the streaming head takes: final norm + pack, the head as split-K partial
         // logits on the matrix cores, softmax statistics per vocabulary slice from the partials
@@ -382,13 +439,11 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
         p.eps = D.eps;
         p.gain = (const bf16_t *)ctx->final_norm; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = mfma_ncb(t.n);
         p.hn = t.hn; p.hidden = t.hidden; p.hidden_tap = t.hidden_tap;
-        launch_prep(s, p);
+        { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
         t.x = x + (size_t)row0 * D.d;
-        if (e0) (void)hipEventRecord(e0, s);
         int ns = 0;
-        launch_gemm_partial(s, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), D.d, D.V, t.n, ctx->at<float>(L.part), &ns);
-        if (e1) (void)hipEventRecord(e1, s);
-        if (e2) (void)hipEventRecord(e2, s);
+        { Bracket br(ctx, s, TR_KERNEL_LMHEAD); launch_gemm_partial(s, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), D.d, D.V, t.n, ctx->at<float>(L.part), &ns, ctx->live); }
+        Bracket br(ctx, s, TR_KERNEL_TAIL_MERGE);
         launch_lmhead_finish(s, ctx->at<float>(L.part), ns, t.n, D.V, t.part, t.logits);
         t.nslices = (D.V + LMHEAD_FINISH_COLS - 1) / LMHEAD_FINISH_COLS;
         launch_tail_final(s, ctx->c.dtype, D, t);
@@ -399,10 +454,14 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
             PrepArgs p{};
             p.x = x; p.row0 = row0; p.gather = t.gather; p.part = ctx->at<float>(L.part); p.nsplit = pending; p.part_M = part_M; p.M = t.n; p.d = D.d;
             p.eps = D.eps;
+            Bracket br(ctx, s, TR_KERNEL_PREP);
             launch_prep(s, p);
         }
         t.x = x + (size_t)row0 * D.d;
-        launch_tail(s, ctx->c.dtype, D, t, e0, e1, e2);
+        { Bracket br(ctx, s, TR_KERNEL_PREP); launch_tail_norm(s, ctx->c.dtype, D, t); }
+        { Bracket br(ctx, s, TR_KERNEL_LMHEAD); launch_lmhead_gemv(s, ctx->c.dtype, D, t); }
+        Bracket br(ctx, s, TR_KERNEL_TAIL_MERGE);
+        launch_tail_final(s, ctx->c.dtype, D, t);
         return;
     }
     PrepArgs p{};
@@ -410,15 +469,16 @@ void run_tail(tr_ctx *ctx, hipStream_t s, TailArgs t, float *x, int row0, int pe
     p.eps = D.eps;
     p.gain = (const bf16_t *)ctx->final_norm; p.pack = ctx->at<uint4>(L.pack_d); p.ncb = mfma_ncb(t.n);
     p.hn = t.hn; p.hidden = t.hidden; p.hidden_tap = t.hidden_tap;
-    launch_prep(s, p);
+    { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
     t.x = x + (size_t)row0 * D.d;
-    if (e0) (void)hipEventRecord(e0, s);
     // the head is streamed by the matrix-core kernel for any row count: one row costs the same bytes as 32
     t.nslices = lmhead_mfma_wgs(D.V, L.router_tiles, t.n);
-    launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits, ctx->at<float>(L.r1), L.router_tiles);
+    {
+        Bracket br(ctx, s, TR_KERNEL_LMHEAD);
+        launch_gemm_lmhead(s, D, ctx->ws + L.wt_head, ctx->at<uint4>(L.pack_d), t.n, t.part, t.logits, ctx->at<float>(L.r1), L.router_tiles, ctx->live);
+    }
     if (L.router_tiles) { t.r1 = ctx->at<float>(L.r1); t.r1_stride = L.router_tiles * 32; }
-    if (e1) (void)hipEventRecord(e1, s);
-    if (e2) (void)hipEventRecord(e2, s);
+    Bracket br(ctx, s, TR_KERNEL_TAIL_MERGE);
     launch_tail_final(s, ctx->c.dtype, D, t);
 }
 
@@ -439,10 +499,26 @@ TailArgs tail_args(tr_ctx *ctx, const tr_out *out, int out_offset, int n)
     t.threshold = ctx->threshold; t.route_dir = ctx->c.route_dir; t.mode = ctx->mode; t.hidden_tap = ctx->c.hidden_tap;
     t.policy = ctx->c.route_policy;
     t.rpart = ctx->at<float>(L.tail_rpart); t.rcnt = ctx->at<int>(L.tail_rcnt);
+    t.live = ctx->live; t.cand = ctx->cand; t.scatter = ctx->scatter;
     return t;
 }
 
 }  // namespace
+
+// Brings the host's sequence lengths up to date after steps whose rows were selected on the device: waits for the stream those
+// steps were enqueued on and reads the device-side lengths of the slots that were candidates. TR_OK or TR_ERR_HIP.
+static int sync_lengths(tr_ctx *ctx)
+{
+    if (!ctx->unsynced) return TR_OK;
+    std::vector<int> dev((size_t)ctx->c.max_batch);
+    hipError_t e = hipMemcpyAsync(dev.data(), ctx->ws + ctx->lay.dev_len, dev.size() * 4, hipMemcpyDeviceToHost, ctx->active_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->active_stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "reading back the device-side sequence lengths");
+    for (size_t b = 0; b < dev.size(); ++b)
+        if (ctx->ahead[b] > 0) { ctx->len[b] = dev[b]; ctx->ahead[b] = 0; }
+    ctx->unsynced = false;
+    return TR_OK;
+}
 
 // Segments of several slots through all layers in as few passes as the row buffers allow (whole segments per pass):
 // segment i is tokens_flat[offsets[i] .. offsets[i+1]) at positions base_i .. base_i+T_i-1, base_i = the slot's length
@@ -491,6 +567,7 @@ static int ingest(tr_ctx *ctx, hipStream_t s, int n, const int32_t *slots, const
         t.slot = ctx->at<int>(L.out_slot);
         t.counter_mode = counter_mode;
         run_tail(ctx, s, t, ctx->at<float>(L.x), 0, pending, rows);
+        profile_next_turn(ctx);
         i = j;
     }
     return TR_OK;
@@ -573,6 +650,7 @@ int tr_create(const tr_config *cfg, const tr_weights *w, void *workspace, size_t
     ctx->r_w1 = chk(w->r_w1); ctx->r_b1 = w->r_b1; ctx->r_w2 = w->r_w2; ctx->r_b2 = w->r_b2;
     if (!aligned) { delete ctx; return TR_ERR_INVALID_ARG; }
     ctx->len.assign((size_t)cfg->max_batch, -1);
+    ctx->ahead.assign((size_t)cfg->max_batch, 0);
     ctx->threshold = cfg->threshold;
     ctx->mode = TR_JOINT;
 
@@ -648,6 +726,7 @@ int tr_set_mode(tr_ctx *ctx, int32_t mode)
 int tr_seq_len(const tr_ctx *ctx, int32_t slot, int32_t *len)
 {
     if (!ctx || !len || slot < 0 || slot >= ctx->c.max_batch) return TR_ERR_INVALID_ARG;
+    { const int src = sync_lengths(const_cast<tr_ctx *>(ctx)); if (src != TR_OK) return src; }
     *len = ctx->len[(size_t)slot] < 0 ? 0 : ctx->len[(size_t)slot];
     return TR_OK;
 }
@@ -656,6 +735,7 @@ int tr_seq_truncate(tr_ctx *ctx, int32_t slot, int32_t new_len)
 {
     if (!ctx) return TR_ERR_INVALID_ARG;
     if (slot < 0 || slot >= ctx->c.max_batch) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_truncate: slot out of range");
+    { const int src = sync_lengths(ctx); if (src != TR_OK) return src; }
     if (ctx->len[(size_t)slot] < 0) return fail(ctx, TR_ERR_STATE, "tr_seq_truncate: slot was never filled");
     if (new_len < 0 || new_len > ctx->len[(size_t)slot]) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_truncate: new_len outside [0, len]");
     ctx->len[(size_t)slot] = new_len;
@@ -675,6 +755,7 @@ int tr_prefill(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, c
 {
     if (!ctx) return TR_ERR_INVALID_ARG;
     if (!slots || !tokens_flat || !offsets || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: null argument");
+    { const int src = sync_lengths(ctx); if (src != TR_OK) return src; }
     if (!slots_ok(ctx, n, slots)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: bad slot list");
     if (offsets[0] != 0) return fail(ctx, TR_ERR_INVALID_ARG, "tr_prefill: offsets[0] must be 0");
     for (int i = 0; i < n; ++i) {
@@ -706,6 +787,7 @@ int tr_extend(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, co
 {
     if (!ctx) return TR_ERR_INVALID_ARG;
     if (!slots || !tokens_flat || !offsets || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: null argument");
+    { const int src = sync_lengths(ctx); if (src != TR_OK) return src; }
     if (!slots_ok(ctx, n, slots)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: bad slot list");
     if (offsets[0] != 0) return fail(ctx, TR_ERR_INVALID_ARG, "tr_extend: offsets[0] must be 0");
     for (int i = 0; i < n; ++i) {
@@ -739,6 +821,7 @@ static int decode_step_impl(tr_ctx *ctx, void *hip_stream, int32_t n, const int3
 {
     if (!ctx) return TR_ERR_INVALID_ARG;
     if (!slots || (!in_tokens && !dev_tokens) || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: null argument");
+    { const int src = sync_lengths(ctx); if (src != TR_OK) return src; }
     if (!slots_ok(ctx, n, slots)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step: bad slot list");
     int max_ctx = 0;
     std::vector<int> pos((size_t)n);
@@ -758,14 +841,18 @@ static int decode_step_impl(tr_ctx *ctx, void *hip_stream, int32_t n, const int3
         const int prc = reserve_pages(ctx, s, n, slots, pos.data(), to.data(), "tr_decode_step: page table");
         if (prc != TR_OK) return prc;
     }
-    launch_setup_rows_embed(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos), ctx->c.dtype,
-                            ctx->tok_emb, ctx->D.d, ctx->at<float>(L.x), dev_tokens, ctx->c.vocab);
+    {
+        Bracket br(ctx, s, TR_KERNEL_SETUP);
+        launch_setup_rows_embed(s, n, slots, in_tokens, pos.data(), ctx->at<int>(L.slot), ctx->at<int>(L.tok), ctx->at<int>(L.pos), ctx->c.dtype,
+                                ctx->tok_emb, ctx->D.d, ctx->at<float>(L.x), dev_tokens, ctx->c.vocab);
+    }
     const int pending = run_layers(ctx, s, n, max_ctx, false, true);
     TailArgs t = tail_args(ctx, out, 0, n);
     t.gather = nullptr;
     t.slot = ctx->at<int>(L.slot);
     t.counter_mode = 1;
     run_tail(ctx, s, t, ctx->at<float>(L.x), 0, pending, n);
+    profile_next_turn(ctx);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_decode_step: launch");
     for (int i = 0; i < n; ++i) ctx->len[(size_t)slots[i]] += 1;
@@ -784,6 +871,46 @@ int tr_decode_step_dev(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *
     return decode_step_impl(ctx, hip_stream, n, slots, nullptr, in_tokens_dev, out);
 }
 
+int tr_decode_step_active(tr_ctx *ctx, void *hip_stream, int32_t n, const int32_t *slots, const int32_t *flags_dev, const int32_t *in_tokens_dev,
+                          int32_t n_max, int32_t *active_dev, int32_t *next_tokens_dev, const tr_out *out)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (!slots || !flags_dev || !in_tokens_dev || !active_dev || !check_out(out)) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step_active: null argument");
+    if (!slots_ok(ctx, n, slots) || n > 256) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step_active: bad candidate list (distinct slots, at most 256)");
+    if (n_max < 3 || n_max > ctx->c.max_batch) return fail(ctx, TR_ERR_INVALID_ARG, "tr_decode_step_active: n_max outside [3, max_batch]");
+    if (!(ctx->use_mfma(n_max) || ctx->use_split(n_max)) || ctx->c.kv_page)
+        return fail(ctx, TR_ERR_SHAPE, "tr_decode_step_active: needs a bf16 model on the matrix-core path and a contiguous cache");
+    int max_ctx = 0;
+    std::vector<int> host_len((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const size_t b = (size_t)slots[i];
+        if (ctx->len[b] < 0) return fail(ctx, TR_ERR_STATE, "tr_decode_step_active: slot was never prefilled");
+        const int most = ctx->len[b] + ctx->ahead[b];   // the slot's length is at most this
+        if (most >= ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_decode_step_active: a candidate slot may be full");
+        host_len[(size_t)i] = ctx->ahead[b] ? -1 : ctx->len[b];
+        if (most + 1 > max_ctx) max_ctx = most + 1;
+    }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const Layout &L = ctx->lay;
+    launch_active_setup(s, n, slots, host_len.data(), flags_dev, in_tokens_dev, n_max, ctx->c.vocab, ctx->at<int>(L.dev_len), ctx->at<int>(L.slot),
+                        ctx->at<int>(L.tok), ctx->at<int>(L.pos), active_dev);
+    ctx->live = active_dev; ctx->cand = active_dev + 2; ctx->scatter = next_tokens_dev;
+    const int pending = run_layers(ctx, s, n_max, max_ctx, true, false);
+    TailArgs t = tail_args(ctx, out, 0, n_max);
+    t.gather = nullptr;
+    t.slot = ctx->at<int>(L.slot);
+    t.counter_mode = 1;
+    run_tail(ctx, s, t, ctx->at<float>(L.x), 0, pending, n_max);
+    profile_next_turn(ctx);
+    ctx->live = ctx->cand = nullptr; ctx->scatter = nullptr;
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(ctx, e, "tr_decode_step_active: launch");
+    for (int i = 0; i < n; ++i) ctx->ahead[(size_t)slots[i]] += 1;
+    ctx->unsynced = true;
+    ctx->active_stream = s;
+    return TR_OK;
+}
+
 int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_out *out)
 {
     if (!ctx) return TR_ERR_INVALID_ARG;
@@ -797,6 +924,7 @@ int tr_tail(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, const tr_o
     t.counters = nullptr;
     t.counter_mode = 0;
     run_tail(ctx, s, t, const_cast<float *>(x), 0, 0, n);   // no partials pending: x is only read
+    profile_next_turn(ctx);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_tail: launch");
     return TR_OK;
@@ -829,7 +957,7 @@ int tr_tail_noalloc(tr_ctx *ctx, void *hip_stream, int32_t n, const float *x, co
     // the array keeps what the last call left: the arrival counters must start at zero (a fill kernel, not a memset node,
     // so that the call can be captured into a graph)
     launch_fill_int(s, t.rcnt, n, 0);
-    launch_tail(s, ctx->c.dtype, ctx->D, t, nullptr, nullptr, nullptr);   // the streaming kernels, on the borrowed weights
+    launch_tail(s, ctx->c.dtype, ctx->D, t);   // the streaming kernels, on the borrowed weights
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(ctx, e, "tr_tail_noalloc: launch");
     return TR_OK;
@@ -840,6 +968,7 @@ int tr_seq_fork(tr_ctx *ctx, void *hip_stream, int32_t src, int32_t dst)
     if (!ctx) return TR_ERR_INVALID_ARG;
     if (src < 0 || src >= ctx->c.max_batch || dst < 0 || dst >= ctx->c.max_batch || src == dst)
         return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_fork: bad slot pair");
+    { const int src = sync_lengths(ctx); if (src != TR_OK) return src; }
     if (ctx->len[(size_t)src] < 0) return fail(ctx, TR_ERR_STATE, "tr_seq_fork: source slot was never filled");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const Layout &L = ctx->lay;
@@ -873,6 +1002,7 @@ int tr_seq_load_kv(tr_ctx *ctx, void *hip_stream, int32_t slot, int32_t len, con
     if (!ctx) return TR_ERR_INVALID_ARG;
     if (!k || !v) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_load_kv: null argument");
     if (slot < 0 || slot >= ctx->c.max_batch) return fail(ctx, TR_ERR_INVALID_ARG, "tr_seq_load_kv: slot out of range");
+    { const int src = sync_lengths(ctx); if (src != TR_OK) return src; }
     if (len < 1 || len > ctx->c.max_seq) return fail(ctx, TR_ERR_CAPACITY, "tr_seq_load_kv: len outside [1, max_seq]");
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (ctx->c.kv_page) {
@@ -904,9 +1034,19 @@ int tr_profile_enable(tr_ctx *ctx, int32_t on)
             }
         }
     }
-    if (on && !ctx->profile) { ctx->prof_ms = ctx->prof_gap_ms = 0.0; ctx->prof_launches = 0; ctx->ev_used = 0; }
+    if (on && !ctx->profile) { ctx->prof_ms = ctx->prof_gap_ms = 0.0; ctx->prof_launches = 0; ctx->ev_used = 0; ctx->prof_seen = ctx->prof_pick = 0; }
     if (!on && ctx->profile) drain_profile(ctx);
     ctx->profile = on != 0;
+    return TR_OK;
+}
+
+int tr_profile_select(tr_ctx *ctx, int32_t family)
+{
+    if (!ctx) return TR_ERR_INVALID_ARG;
+    if (family < 0 || family >= TR_KERNEL_FAMILIES) return fail(ctx, TR_ERR_INVALID_ARG, "tr_profile_select: unknown kernel family");
+    if (ctx->profile) drain_profile(ctx);
+    ctx->prof_family = family;
+    ctx->prof_ms = ctx->prof_gap_ms = 0.0; ctx->prof_launches = 0; ctx->ev_used = 0; ctx->prof_seen = ctx->prof_pick = 0;
     return TR_OK;
 }
 

@@ -54,6 +54,10 @@ struct LayerW {
 struct Rows {
     const int *slot, *pos, *tok;
     int n;
+    // Device-side row count (NULL: all n rows are live). When given, only rows 0 .. *live - 1 belong to sequences: the rows
+    // from *live on are padding of a launch whose size was fixed before the count was known. They are computed like any row
+    // (on a valid slot at position 0) but must change no state, and with *live == 0 the large kernels return at once.
+    const int *live;
 };
 
 // Attention partials that have not been merged yet: the consumer (the output projection of the GEMV path) merges them
@@ -106,6 +110,9 @@ struct TailArgs {
     int *rcnt;               // [n]: arrival counters of those workgroups, zero before and after every launch (NULL: one workgroup per row)
     const float *r1;         // [n][r1_stride]: sums W1 . hidden of the router's first layer, computed by the LM-head launch (NULL: computed here)
     int r1_stride;
+    const int *live;         // device-side row count (see Rows::live); rows from *live on report token -1, score 0, flag 0 and count nothing
+    const int *cand;         // with scatter: index of output i in the caller's candidate list
+    int32_t *scatter;        // scatter[cand[i]] = token of live row i (the other model's next-input buffer), or NULL
 };
 constexpr int TAIL_ROUTER_PARTS = 4;
 
@@ -138,13 +145,20 @@ void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchu
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x);
-// ev0/ev1 bracket the LM-head kernel, ev2 follows ev1 at once (an empty interval in the same place); all may be null
-void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t, hipEvent_t ev0, hipEvent_t ev1, hipEvent_t ev2);
+void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);
 void launch_load_kv(hipStream_t s, int kdt, const Dims &D, int slot, int len, const void *k, const void *v, void *kc, void *vc);
 void launch_reset_counters(hipStream_t s, long long *counters, int slot);
 void launch_fill_int(hipStream_t s, int *p, int n, int value);   // p[0..n) = value
+// Device-side selection of the rows of a decode step. Candidates i = 0..n-1 (slot cand_slot[i], input token tokens_dev[i]) whose
+// flags_dev[i] is non-zero are taken in increasing i, at most n_max of them: row r gets the r-th of them, at the position the
+// device-side length array holds for its slot, and that length grows by one. host_len[i] >= 0 first sets the slot's device-side
+// length (the host knew it); -1 keeps the device's value. Rows past the count are padding: slot cand_slot[0], position 0, token 0.
+// active[0] = rows taken, active[1] = candidates flagged, active[2 + r] = candidate of row r (-1 for padding). n <= 256.
+void launch_active_setup(hipStream_t s, int n, const int *cand_slot, const int *host_len, const int *flags_dev, const int *tokens_dev, int n_max,
+                         int vocab, int *dev_len, int *d_slot, int *d_tok, int *d_pos, int *active);
 
 int tail_slice_rows();
+void launch_tail_norm(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);   // final RMSNorm of the streaming tail: t.x -> t.hn (and t.hidden)
 void launch_tail_final(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);
 void launch_lmhead_gemv(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);
 
@@ -155,10 +169,11 @@ void launch_widen_bias(hipStream_t s, const void *b, int n, float *out);
 void launch_prep(hipStream_t s, const PrepArgs &p);
 void launch_pack(hipStream_t s, const float *in, int M, int K, void *pack, int ncb);
 int mfma_ncb(int M);
-void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out);
+// live (also below): device-side row count or NULL; the kernel returns at once when it is zero
+void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out, const int *live = nullptr);
 void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, const void *pack, const float *bias, Rows rows, const float2 *rope,
                      float *q, void *kc, void *vc);
-void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack);
+void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack, const int *live = nullptr);
 // Wide models (K beyond what one workgroup keeps resident): every linear layer goes through split-K partials, and the
 // layers with a non-linear epilogue are finished by a small kernel of their own.
 // number of partial buffers launch_gemm_partial will produce for a K x N layer
@@ -176,6 +191,7 @@ constexpr int LMHEAD_FINISH_COLS = 2048;
 void launch_lmhead_finish(hipStream_t s, const float *part, int nsplit, int M, int V, float *slice_part, float *logits);
 int lmhead_mfma_wgs(int V, int router_tiles, int M);   // workgroups per 64-row group that own tiles, for M rows (most at M <= 64)
 // router_tiles > 0: the matrix holds that many extra tiles after the vocabulary (the router's first layer); their raw sums go to r1[row][router_tiles * 32]
-void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits, float *r1, int router_tiles);
+void launch_gemm_lmhead(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, float *part, float *logits, float *r1, int router_tiles,
+                        const int *live = nullptr);
 
 }  // namespace tr

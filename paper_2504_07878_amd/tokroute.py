@@ -21,9 +21,10 @@ JOINT, SMALL_ONLY = 0, 1
 ROUTE_IF_BELOW, ROUTE_IF_ABOVE = 0, 1
 POLICY_MLP, POLICY_CONFIDENCE, POLICY_LINEAR = 0, 1, 2
 POST_FINAL_NORM, PRE_FINAL_NORM = 0, 1
+KERNEL_FAMILIES = ("setup", "prep", "qkv", "attention", "oproj", "gateup", "down", "lmhead", "tail_merge", "qkv_attention")   # TR_KERNEL_*
 
-EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_decode_step_dev", "tr_extend", "tr_tail", "tr_tail_noalloc", "tr_set_threshold",
-           "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_fork", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable",
+EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_decode_step_dev", "tr_decode_step_active", "tr_extend", "tr_tail", "tr_tail_noalloc", "tr_set_threshold",
+           "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_fork", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable", "tr_profile_select",
            "tr_profile_read", "tr_last_error"]
 
 
@@ -67,6 +68,7 @@ def load_library():
         L.tr_extend.argtypes = [vp, vp, i32, vp, vp, vp, C.POINTER(tr_out)]
         L.tr_decode_step.argtypes = [vp, vp, i32, vp, vp, C.POINTER(tr_out)]
         L.tr_decode_step_dev.argtypes = [vp, vp, i32, vp, vp, C.POINTER(tr_out)]
+        L.tr_decode_step_active.argtypes = [vp, vp, i32, vp, vp, vp, i32, vp, vp, C.POINTER(tr_out)]
         L.tr_tail.argtypes = [vp, vp, i32, vp, C.POINTER(tr_out)]
         L.tr_tail_noalloc.argtypes = [vp, vp, i32, vp, C.POINTER(tr_out)]
         L.tr_set_threshold.argtypes = [vp, f32]
@@ -77,6 +79,7 @@ def load_library():
         L.tr_seq_load_kv.argtypes = [vp, vp, i32, i32, vp, vp]
         L.tr_counters_ptr.argtypes = [vp, C.POINTER(vp)]
         L.tr_profile_enable.argtypes = [vp, i32]
+        L.tr_profile_select.argtypes = [vp, i32]
         L.tr_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.tr_last_error.argtypes = [vp]; L.tr_last_error.restype = C.c_char_p
         _lib = L
@@ -228,6 +231,19 @@ class Model:
                                                 C.byref(out.struct)), "tr_decode_step_dev")
         return out
 
+    def decode_step_active(self, slots, flags: torch.Tensor, in_tokens: torch.Tensor, n_max: int, active: torch.Tensor,
+                           next_tokens: torch.Tensor = None, out: Outputs = None, want_logits=False):
+        """Decode step of the candidates (`slots`) whose device-side flag is set, at most n_max of them; see tr_decode_step_active.
+        flags, in_tokens: device int32 [n]; active: device int32 [2 + n_max]; next_tokens: device int32 [n] or None."""
+        slots = np.ascontiguousarray(slots, dtype=np.int32)
+        for t, m in ((flags, len(slots)), (in_tokens, len(slots)), (active, 2 + n_max)) + (((next_tokens, len(slots)),) if next_tokens is not None else ()):
+            assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.numel() == m
+        out = out or self.outputs(n_max, want_logits)
+        self._check(self.lib.tr_decode_step_active(self._h, self._stream(), len(slots), slots.ctypes.data, flags.data_ptr(), in_tokens.data_ptr(),
+                                                   int(n_max), active.data_ptr(), None if next_tokens is None else next_tokens.data_ptr(),
+                                                   C.byref(out.struct)), "tr_decode_step_active")
+        return out
+
     def tail(self, x: torch.Tensor, out: Outputs = None, want_logits=False):
         """x: device fp32 [n][d_model] residual-stream rows."""
         assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.shape[1] == self.shape["d_model"]
@@ -276,6 +292,9 @@ class Model:
 
     def profile_enable(self, on=True):
         self._check(self.lib.tr_profile_enable(self._h, int(bool(on))), "tr_profile_enable")
+
+    def profile_select(self, family: int):
+        self._check(self.lib.tr_profile_select(self._h, int(family)), "tr_profile_select")
 
     def profile_read(self):
         ms, gap, n = C.c_double(), C.c_double(), C.c_int64()
