@@ -259,6 +259,12 @@ int tr_profile_select(tr_ctx *ctx, int32_t family);
 int tr_profile_enable(tr_ctx *ctx, int32_t on);
 int tr_profile_read(tr_ctx *ctx, double *ms_total, double *ms_empty_pairs, int64_t *launches);
 
+/* Benchmark infrastructure: enqueues `launches` launches, one after the other on the stream, of a kernel of
+ * `workgroups` workgroups of 256 threads that does nothing but one 4-byte store per thread into buf (DEVICE,
+ * workgroups * 256 int32). What such a chain costs per launch is the floor under any step built as a chain of
+ * dependent kernels. */
+int tr_profile_chain(void *hip_stream, int32_t *buf, int32_t workgroups, int32_t launches);
+
 const char *tr_last_error(const tr_ctx *ctx);
 
 #ifdef __cplusplus

@@ -708,6 +708,14 @@ void tr_destroy(tr_ctx *ctx)
 
 const char *tr_last_error(const tr_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
+int tr_profile_chain(void *hip_stream, int32_t *buf, int32_t workgroups, int32_t launches)
+{
+    if (!buf || workgroups < 1 || workgroups > 65536 || launches < 1) return TR_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    for (int i = 0; i < launches; ++i) launch_fill_int(s, buf, workgroups * 256, i);   // each launch overwrites what the one before wrote
+    return hipGetLastError() == hipSuccess ? TR_OK : TR_ERR_HIP;
+}
+
 int tr_set_threshold(tr_ctx *ctx, float t)
 {
     if (!ctx) return TR_ERR_INVALID_ARG;

@@ -25,7 +25,7 @@ KERNEL_FAMILIES = ("setup", "prep", "qkv", "attention", "oproj", "gateup", "down
 
 EXPORTS = ["tr_workspace_bytes", "tr_create", "tr_destroy", "tr_prefill", "tr_decode_step", "tr_decode_step_dev", "tr_decode_step_active", "tr_extend", "tr_tail", "tr_tail_noalloc", "tr_set_threshold",
            "tr_set_mode", "tr_seq_len", "tr_seq_truncate", "tr_seq_fork", "tr_seq_load_kv", "tr_counters_ptr", "tr_profile_enable", "tr_profile_select",
-           "tr_profile_read", "tr_last_error"]
+           "tr_profile_read", "tr_profile_chain", "tr_last_error"]
 
 
 class tr_config(C.Structure):
@@ -81,6 +81,7 @@ def load_library():
         L.tr_profile_enable.argtypes = [vp, i32]
         L.tr_profile_select.argtypes = [vp, i32]
         L.tr_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.tr_profile_chain.argtypes = [vp, vp, i32, i32]
         L.tr_last_error.argtypes = [vp]; L.tr_last_error.restype = C.c_char_p
         _lib = L
     return _lib

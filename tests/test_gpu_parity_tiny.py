@@ -511,3 +511,47 @@ def test_one_and_two_row_decode_steps_at_chunk_boundaries(tr, tro, kv_page):
     ex += compare_outputs(go, oo, s.dtype, s.threshold, "one-token segments")
     assert ex <= 1
     assert g.seq_len(0) == 8 and g.seq_len(1) == 134
+
+
+def test_exchanges_between_workgroups_give_the_same_bits_every_time(tr):
+    """The two places where workgroups hand partial results to whichever of them arrives last (attention rows split over
+    several workgroups; the router's hidden units split over the workgroups of a row), each repeated a few hundred times:
+    every repetition must reproduce the first result bit for bit. Stops at the first difference."""
+    REPS = 300
+    # (1) attention: 64 rows of a bf16 model with contexts of up to ~2000 keys, i.e. up to three parts per (row, kv head)
+    s = synth.TINY.with_(dtype=synth.BF16, kv_dtype=synth.BF16)
+    w = synth.make_weights(s, SEED + 9, std=0.05)
+    B, ctx = 64, 2000
+    g = tr.Model(s.asdict(), w, B, ctx + 4)
+    lens = [ctx] + [int(n) for n in synth.prompt_lengths(SEED, "soak.lens", B - 1, 700, ctx)]
+    k, v = synth.kv_fill(SEED, "soak.kv", s, ctx)
+    for b, n in enumerate(lens):
+        g.load_kv(b, tr.to_device(np.ascontiguousarray(k[:, :, :n]), synth.BF16), tr.to_device(np.ascontiguousarray(v[:, :, :n]), synth.BF16))
+    toks = synth.prompt_tokens(SEED, "soak.tok", B, s.vocab)
+    slots = list(range(B))
+    out = g.outputs(B, want_logits=True)
+    first = None
+    for rep in range(REPS):
+        g.decode_step(slots, toks, out)
+        got = (out.logits.clone(), out.hidden.clone(), out.score.clone())
+        for b, n in enumerate(lens):
+            g.seq_truncate(b, n)
+        if first is None:
+            first = got
+        else:
+            same = all(torch.equal(a, b) for a, b in zip(first, got))
+            assert same, f"attention exchange: repetition {rep} differs from the first"
+    # (2) router: 64 rows x 4 workgroups per row on the streaming tail (fp32 model, 256 hidden units)
+    s = synth.TINY.with_(router_hidden=256)
+    w = synth.make_weights(s, SEED + 10, bias_std=0.05)
+    g = tr.Model(s.asdict(), w, 64, 8)
+    x = torch.from_numpy(synth.hidden_rows(SEED, "soak.x", 64, s.d_model, False)).cuda()
+    out = g.outputs(64)
+    first = None
+    for rep in range(REPS):
+        g.tail(x, out)
+        got = (out.score.clone(), out.flag.clone(), out.token.clone(), out.conf.clone())
+        if first is None:
+            first = got
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, got)), f"router exchange: repetition {rep} differs from the first"
