@@ -66,6 +66,24 @@ def family_times(model, slots, tokens_per_step, out, families):
         if cnt:
             res[fam] = ((ms - gap) / cnt * 1e3, ms / cnt * 1e3, gap / cnt * 1e3, per_step, cnt)
     model.profile_select(FAMILY_ID["lmhead"])
+    # the same steps with nothing bracketed: what is left of the step time after the kernels' own durations is the cost of
+    # getting from the end of one kernel to the start of the next, shared equally by the launches
+    n = 24
+    for i in range(4):
+        model.decode_step(slots, tokens_per_step[i % len(tokens_per_step)], out)
+    for sl, b in zip(slots, base):
+        model.seq_truncate(sl, b)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n):
+        model.decode_step(slots, tokens_per_step[i % len(tokens_per_step)], out)
+    torch.cuda.synchronize()
+    step_us = (time.perf_counter() - t0) / n * 1e6
+    for sl, b in zip(slots, base):
+        model.seq_truncate(sl, b)
+    launches = sum(v[3] for v in res.values())
+    res["_step_us"] = step_us
+    res["_gap_us"] = max(0.0, (step_us - sum(v[0] * v[3] for v in res.values() if isinstance(v, tuple))) / max(launches, 1))
     return res
 
 
@@ -177,7 +195,23 @@ def floor_workload():
         t1 = time.perf_counter()
         torch.cuda.synchronize()
         t2 = time.perf_counter()
-        rows.append({"workgroups": wgs, "launches": n, "us_per_launch": (t2 - t0) / n * 1e6, "host_enqueue_us_per_launch": (t1 - t0) / n * 1e6})
+        row = {"workgroups": wgs, "launches": n, "us_per_launch": (t2 - t0) / n * 1e6, "host_enqueue_us_per_launch": (t1 - t0) / n * 1e6}
+        # the same chain replayed from a captured graph: no host enqueue in the way, what is left is the GPU's own cost per launch
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                assert lib.tr_profile_chain(torch.cuda.current_stream().cuda_stream, buf.data_ptr(), wgs, 1000) == 0
+            graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                graph.replay()
+            torch.cuda.synchronize()
+            row["graph_replay_us_per_launch"] = (time.perf_counter() - t0) / 5000 * 1e6
+        torch.cuda.current_stream().wait_stream(side)
+        rows.append(row)
     print(json.dumps({"metric": "cost of one launch in a chain of dependent do-nothing kernels", "unit": "us", "chains": rows,
                       "note": "wall clock over the whole chain; a kernel trace of this command gives the start-to-start spacing on the GPU"}), flush=True)
 
@@ -366,7 +400,15 @@ def measured_traffic(family):
 
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch, per kernel family, with the hash of the kernel sources they were taken on.
-TRAFFIC = {}
+TRAFFIC = {
+    "attention": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 23008562, "write_bytes": 1660144},
+    "gateup": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 19493924, "write_bytes": 1245184},
+    "down": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 19313709, "write_bytes": 1376256},
+    "qkv": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 6224580, "write_bytes": 507904},
+    "oproj": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 3643207, "write_bytes": 917504},
+    "prep": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 1028863, "write_bytes": 770703},
+    "lmhead": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 274912151, "write_bytes": 322560},
+}
 
 
 # kernel families of a decode step of the 0.5B-class model at 64 rows: launches per step, and the kernels behind them
@@ -392,14 +434,19 @@ def family_bytes(s, rows, attention_bytes):
 def kernel_table(s, fam, kernels, rows, attention_bytes):
     """One entry per kernel family: launches per step, average duration, algorithmic bytes per launch, fraction of the HBM peak."""
     fb = family_bytes(s, rows, attention_bytes)
-    total = sum(v[0] * v[3] for v in fam.values())
+    step_us, launch_gap = fam["_step_us"], fam["_gap_us"]
     table = []
-    for name, (net, raw, gap, per_step, cnt) in fam.items():
+    for name, v in fam.items():
+        if not isinstance(v, tuple):
+            continue
+        net, raw, gap, per_step, cnt = v
         b = fb[name]
-        table.append({"family": name, "kernel": kernels[name], "launches_per_step": per_step, "avg_us": net, "event_pair_avg_us": raw,
-                      "empty_event_pair_avg_us": gap, "samples": cnt, "us_per_step": net * per_step, "share_of_step": net * per_step / total if total else None,
-                      "algorithmic_bytes_per_launch": b, "achieved_GB_per_s": b / net / 1e3 if b else None,
-                      "frac": b / net / 1e3 / HBM_PEAK_GBPS if b else None})
+        dur = net + launch_gap        # what one launch of the family costs the step: its own duration and its share of the time between kernels
+        table.append({"family": name, "kernel": kernels[name], "launches_per_step": per_step, "avg_us": dur, "kernel_us": net, "launch_gap_us": launch_gap,
+                      "event_pair_avg_us": raw, "empty_event_pair_avg_us": gap, "samples": cnt, "us_per_step": dur * per_step,
+                      "share_of_step": dur * per_step / step_us, "algorithmic_bytes_per_launch": b,
+                      "achieved_GB_per_s": b / dur / 1e3 if b else None, "frac": b / dur / 1e3 / HBM_PEAK_GBPS if b else None,
+                      "frac_of_kernel_time_alone": b / net / 1e3 / HBM_PEAK_GBPS if b else None})
     return table
 
 
@@ -467,7 +514,8 @@ def main():
     fam = family_times(model, slots, toks, out, B64_FAMILIES)
     by_kernel = kernel_table(s, fam, B64_KERNELS, B, (sum(base0) + B) * kvb / s.n_layers)
     dominant = max(by_kernel, key=lambda r: r["us_per_step"])["family"] if by_kernel else "lmhead"
-    log("per-kernel table: " + "; ".join(f"{r['family']} {r['launches_per_step']} x {r['avg_us']:.2f} us" for r in by_kernel) + f" -> dominant: {dominant}")
+    log("per-kernel table: " + "; ".join(f"{r['family']} {r['launches_per_step']} x {r['avg_us']:.2f} us" for r in by_kernel)
+        + f"; {fam['_gap_us']:.2f} us of that between kernels -> dominant: {dominant}")
     # 2. the timed steps, with one launch per step of the dominant family bracketed by events
     dt, k_ms, k_n, base, k_raw = time_decode(model, slots, toks, steps, args.warmup, out, dominant)
     ms_per_step = dt / steps * 1e3
@@ -479,8 +527,10 @@ def main():
     roof_tok_s = B / (step_bytes / (HBM_PEAK_GBPS * 1e9))
     # bytes of one launch of the dominant family, averaged over the timed steps (attention: the caches of all 64 sequences, one layer)
     k_bytes = family_bytes(s, B, (ctx_sum + B * steps) / steps * kvb / s.n_layers)[dominant]
-    k_avg_s = k_ms / 1e3 / max(k_n, 1)
-    share = next((r["share_of_step"] for r in by_kernel if r["family"] == dominant), None)
+    launch_gap_us = fam["_gap_us"]
+    k_net_us = k_ms * 1e3 / max(k_n, 1)
+    k_avg_s = (k_net_us + launch_gap_us) / 1e6     # duration of a launch as the step sees it: the kernel and its share of the time between kernels
+    share = B64_FAMILIES[dominant] * k_avg_s * 1e3 / ms_per_step
     result = {
         # the metric names three figures: value is the batch-64 one (the workload below); batch 1 and the isolated tail are in extras
         "metric": "SLM decode tokens/s at B=1/64 + fused routing-tail GB/s, % of HBM roofline", "value": tok_s, "unit": "tokens/s",
@@ -496,8 +546,11 @@ def main():
                      "achieved": k_bytes / k_avg_s / 1e9 if k_n and k_bytes else None,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": (k_bytes / k_avg_s / 1e9 / HBM_PEAK_GBPS) if k_n and k_bytes else None,
                      "traffic": measured_traffic(dominant), "launches": k_n, "avg_us": k_avg_s * 1e6, "algorithmic_bytes_per_launch": k_bytes,
-                     "share_of_step_time": share,
-                     "event_pair_avg_us": k_raw[0] / max(k_n, 1) * 1e3, "empty_event_pair_avg_us": k_raw[1] / max(k_n, 1) * 1e3},
+                     "share_of_step_time": share, "kernel_us": k_net_us, "launch_gap_us": launch_gap_us,
+                     "frac_of_kernel_time_alone": (k_bytes / k_net_us / 1e3 / HBM_PEAK_GBPS) if k_n and k_bytes else None,
+                     "event_pair_avg_us": k_raw[0] / max(k_n, 1) * 1e3, "empty_event_pair_avg_us": k_raw[1] / max(k_n, 1) * 1e3,
+                     "how": "avg_us = event-bracketed duration of the kernel inside the timed steps (bracketed interval minus the empty event pair behind it) "
+                            "+ the per-launch share of the step time that lies between kernels; the profiler's begin-to-end durations (profiles/) include that share too"},
         "roofline_by_kernel": by_kernel,
     }
 
