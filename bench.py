@@ -412,12 +412,12 @@ TRAFFIC = {
 
 
 # kernel families of a decode step of the 0.5B-class model at 64 rows: launches per step, and the kernels behind them
-B64_FAMILIES = {"setup": 1, "prep": 49, "qkv": 24, "attention": 24, "oproj": 24, "gateup": 24, "down": 24, "lmhead": 1, "tail_merge": 1}
+B64_FAMILIES = {"setup": 1, "prep": 25, "qkv": 24, "attention": 24, "oproj": 24, "gateup": 24, "down": 24, "lmhead": 1, "tail_merge": 1}
 B1_FAMILIES = {"setup": 1, "qkv_attention": 24, "oproj": 24, "gateup": 24, "down": 24, "prep": 1, "lmhead": 1, "tail_merge": 1}
 B1_KERNELS = {"setup": "setup_embed_kernel", "qkv_attention": "qkv_attn_kernel", "oproj": "residual_gemv_kernel<1,StageAttn>", "gateup": "gateup_kernel<1>",
               "down": "residual_splitk_kernel<3,1>", "prep": "prep_kernel (final norm)", "lmhead": "gemm22_kernel<28,EpiLmHead>", "tail_merge": "tail_final_kernel"}
 B64_KERNELS = {"setup": "setup_embed_kernel", "prep": "prep_kernel", "qkv": "gemm_kernel<2,14,EpiQkv>", "attention": "attn_rows_kernel<64>",
-               "oproj": "gemm22_kernel<8,EpiPartial>", "gateup": "gemm22_kernel<28,EpiSwiglu>", "down": "gemm22_kernel<28,EpiPartial>",
+               "oproj": "gemm_kernel<2,14,EpiResidualNorm>", "gateup": "gemm22_kernel<28,EpiSwiglu>", "down": "gemm22_kernel<28,EpiPartial>",
                "lmhead": "gemm22_kernel<28,EpiLmHead>", "tail_merge": "tail_final_kernel"}
 
 

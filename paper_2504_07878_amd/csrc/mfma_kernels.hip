@@ -918,25 +918,94 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
     uint4 *hpack;     // [group][F/16][NCB][64]
     int M, F, ncb;
     float hold[8];
+    // Deferred RMSNorm: when sumsq is given, the packed activations are x * gain WITHOUT the 1/rms factor (they were written by the
+    // epilogue of the output projection, which only knows its own 32 features of a row); W.(g*x/rms) = W.(g*x) / rms, so the factor
+    // is applied to the sums here. sumsq[m * ss_stride + i], i < n_ss: the row's sum of squares over the features of tile range i.
+    const float *sumsq;
+    int n_ss, ss_stride;
+    float eps, inv_d;
+    float rstd;
     __device__ void block(int, int) {}
     __device__ void begin() {}
-    __device__ void row(int) {}
+    __device__ void row(int m)
+    {
+        rstd = 1.0f;
+        if (sumsq) {
+            // a row's values are consecutive (ss_stride floats, a multiple of 4): 16-byte requests, two at a time, added in a fixed order
+            const float4 *sp = reinterpret_cast<const float4 *>(sumsq + (size_t)min(m, M - 1) * ss_stride);
+            const int n4 = (n_ss + 3) >> 2;
+            float tot = 0.f;
+            for (int i0 = 0; i0 < n4; i0 += 2) {
+                const float4 a = sp[i0], b = sp[min(i0 + 1, n4 - 1)];
+                const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) tot += 4 * i0 + u < n_ss ? v[u] : 0.f;   // entries past n_ss are not the row's
+            }
+            rstd = 1.0f / sqrtf(tot * inv_d + eps);
+        }
+    }
     // a workgroup's tile range starts at a gate tile (even index), so PAR = 0 is a gate tile, PAR = 1 its up tile
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         if (PAR == 0) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) hold[e] = v[e];
+            for (int e = 0; e < 8; ++e) hold[e] = v[e] * rstd;
             return;
         }
         float h[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = hold[e] * __frcp_rn(1.0f + __expf(-hold[e])) * v[e];   // hardware exp2 and reciprocal (1 ulp each)
+        for (int e = 0; e < 8; ++e) h[e] = hold[e] * __frcp_rn(1.0f + __expf(-hold[e])) * (v[e] * rstd);   // hardware exp2 and reciprocal (1 ulp each)
         const int f0 = (t >> 1) * 32 + i0;
         // rows past M are written too: they lie inside the padded 64-row group and are never read back as valid rows
         if (!RAGGED || f0 < F) store_packed(hpack + (size_t)(m >> 6) * (F / 16) * ncb * 64, ncb, m & 63, f0 >> 3, h);
     }
     __device__ void end(float *, int, int) {}
+};
+
+// Output projection with the residual update and the next layer input's packing in its epilogue (no split-K, no separate
+// residual + norm launch): x += tile; the packed activations of the FFN input are written as x * gain, hi/lo split, and the
+// 1/rms factor is left to the consumer (EpiSwiglu::sumsq), for which every workgroup leaves its rows' sums of squares over its own
+// tile range: sumsq[row][tile range]. The four threads that hold one row (one per band of 8 features) add their sums through LDS in
+// band order, and a workgroup's tiles are taken in index order, so the value is the same from run to run.
+struct EpiResidualNorm {
+    static constexpr bool half_only = true;   // 32-row workgroups (GemmArgs::half = 1)
+    float *x;              // residual stream [M][d], updated in place
+    const bf16_t *gain;    // gain of the norm that follows
+    uint4 *pack;           // packed activations of the next linear layer, [group][d/16][ncb][64]
+    float *sumsq;          // [row][ss_stride], entry = index of the workgroup's tile range
+    int M, d, ncb, ss_stride;
+    int bx, m;
+    float ss;
+    __device__ void block(int b, int) { bx = b; }
+    __device__ void begin() { ss = 0.f; }
+    __device__ void row(int r) { m = r; }
+    template <int PAR> __device__ void tile(int t, int mm, int i0, const float (&v)[8])
+    {
+        const int n0 = t * 32 + i0;
+        if (mm >= M || n0 >= d) return;   // d is a multiple of 8: a band is whole or absent
+        float *xr = x + (size_t)mm * d + n0;
+        const float4 a = *reinterpret_cast<const float4 *>(xr), b = *reinterpret_cast<const float4 *>(xr + 4);
+        const uint4 gbits = *reinterpret_cast<const uint4 *>(gain + n0);
+        const float xn[8] = {a.x + v[0], a.y + v[1], a.z + v[2], a.w + v[3], b.x + v[4], b.y + v[5], b.z + v[6], b.w + v[7]};
+        *reinterpret_cast<float4 *>(xr) = make_float4(xn[0], xn[1], xn[2], xn[3]);
+        *reinterpret_cast<float4 *>(xr + 4) = make_float4(xn[4], xn[5], xn[6], xn[7]);
+        const uint32_t gw[4] = {gbits.x, gbits.y, gbits.z, gbits.w};
+        float gx[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            ss = fmaf(xn[e], xn[e], ss);
+            gx[e] = xn[e] * __uint_as_float((e & 1) ? (gw[e >> 1] & 0xffff0000u) : (gw[e >> 1] << 16));
+        }
+        store_packed(pack + (size_t)(mm >> 6) * (d / 16) * ncb * 64, ncb, mm & 63, n0 >> 3, gx);
+    }
+    __device__ void end(float *lds, int row_local, int band)
+    {
+        __syncthreads();
+        lds[band * 64 + row_local] = ss;
+        __syncthreads();
+        if (band == 0 && row_local < 32 && m < M)
+            sumsq[(size_t)m * ss_stride + bx] = (lds[row_local] + lds[64 + row_local]) + (lds[128 + row_local] + lds[192 + row_local]);
+    }
 };
 
 // DUMP = false keeps every vector-memory store out of the tile loop, so that the wait counters of the weight stream stay exact.
@@ -1045,6 +1114,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // half mode: the packed activations hold 4 column blocks per 64-row group; this workgroup takes {h, 2 + h}
     const int pgroup = a.half ? group >> 1 : group, hsel = a.half ? group & 1 : 0, pncb = a.half ? 4 : NCB;
     const int row0 = pgroup * 64 + hsel * 32;
+    // what the epilogue needs per batch row is requested first: it is then the oldest request in flight and can be waited for
+    // without waiting for anything younger
+    epi.row(row0 + (threadIdx.x & 63));
 
     // resident activations of this wavefront's k-steps (zero beyond its share, so the extra products vanish)
     bf16x8 b[KW][NCB];
@@ -1118,7 +1190,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
     float *const red0 = red, *const red1 = red + RED_FLOATS;
     epi.begin();
-    epi.row(row0 + j);
     int t = t0;
     if (t0 < t1) {
         load_tile(t0, w[0]);
@@ -1198,6 +1269,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     epi.block(bx, group);
     const int m = group * 64 + rh * 32 + (lane & 31), i0 = 16 * kh + 8 * hf;
+    epi.row(m);   // per-row inputs of the epilogue: requested first, so that they are the oldest requests in flight
 
     // resident activations: hi and lo halves of this wavefront's 32 rows over its k-steps (zero beyond its share)
     bf16x8 b[KW2][2];
@@ -1253,7 +1325,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     using Par1 = std::integral_constant<int, 1>;
 
     epi.begin();
-    epi.row(m);
     int t = t0;
     if (t0 < t1) {
         {
@@ -1548,19 +1619,34 @@ void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, cons
     }
 }
 
-void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack, const int *live)
+void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack, const int *live, const float *sumsq,
+                        int n_ss, int ss_stride)
 {
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = 2 * ((D.F + 31) / 32); a.M = M; a.live = live;
     a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, (M + 63) / 64, 2);   // whole gate/up pairs
     if (D.F % 32) {
-        EpiSwiglu<true> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}};
+        EpiSwiglu<true> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f};
         launch_gemm(s, a, 1, e);
     } else {
-        EpiSwiglu<false> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}};
+        EpiSwiglu<false> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f};
         launch_gemm(s, a, 1, e);
     }
 }
+
+int launch_gemm_oproj_residual(hipStream_t s, const Dims &D, const void *Wt, const void *pack_a, int M, float *x, const void *gain, void *pack_out,
+                               float *sumsq, int ss_stride, const int *live)
+{
+    GemmArgs a{};
+    a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack_a; a.KS = D.qw / 16; a.ksw = a.KS; a.n_tiles = (D.d + 31) / 32; a.M = M; a.live = live;
+    a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, M > 32 ? 2 * ((M + 63) / 64) : 1, 1);
+    a.half = 1;
+    EpiResidualNorm e{x, (const bf16_t *)gain, (uint4 *)pack_out, sumsq, M, D.d, mfma_ncb(M), ss_stride, 0, 0, 0.f};
+    launch_gemm(s, a, 1, e);
+    return (a.n_tiles + a.tiles_per_wg - 1) / a.tiles_per_wg;   // tile ranges = entries of sumsq per row
+}
+
+bool gemm_oproj_residual_supported(const Dims &D) { return D.qw / 16 <= NWAVES * MAXKW; }
 
 // tiles per workgroup of the LM-head launch: the whole launch (every 64-row group over every tile) is one round of at most 256 workgroups
 static int lmhead_tiles_per_wg(int n_tiles, int M)

@@ -43,6 +43,8 @@ struct Layout {
     size_t qblock;     // query-row blocks of a pass (prompts, catch-up segments): first row * 8 + rows
     size_t kvn;        // new keys and values of up to two decode rows, [row][2][kv width] floats (fused q|k|v + attention kernel)
     size_t dev_len;    // device-side sequence lengths [max_batch], used by the steps whose rows are selected on the device
+    size_t sumsq;      // rows' sums of squares per tile range of the output projection, [max_rows][ss_stride] floats (deferred RMSNorm)
+    int ss_stride;     // ceil(d / 32) rounded up to a multiple of 4
     int maxp, pool;    // pages per slot (table row length) and pages in the pool; 0 for the contiguous cache
     int max_rows, nslices;
     // matrix-core paths: repacked weights, packed activations, split-K partials.
@@ -174,6 +176,8 @@ Layout make_layout(const tr_config *c)
     L.qblock = take(R * 4);
     L.kvn = take(2 * 2 * kvw * 4);
     L.dev_len = take((size_t)c->max_batch * 4);
+    L.ss_stride = ((c->d_model + 31) / 32 + 3) / 4 * 4;
+    L.sumsq = take((size_t)L.ss_stride * R * 4);
     L.total = off;
     return L;
 }
@@ -403,6 +407,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
     const int ncb = mfma_ncb(R);
     float *part = ctx->at<float>(L.part);
     int pending = 0;
+    const bool fuse_oproj = gemm_oproj_residual_supported(D);
     for (int l = 0; l < D.L; ++l) {
         const LayerW &w = ctx->layers[(size_t)l];
         PrepArgs p{};
@@ -416,10 +421,19 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         }
         attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                          attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
-        { Bracket br(ctx, s, TR_KERNEL_OPROJ); launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending, live); }
-        p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
-        { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
-        { Bracket br(ctx, s, TR_KERNEL_GATEUP); launch_gemm_swiglu(s, D, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), R, ctx->at<uint4>(L.pack_h), live); }
+        if (fuse_oproj) {
+            // the output projection updates the residual stream and packs the FFN input itself; the 1/rms factor follows in the gate/up epilogue
+            int n_ss;
+            { Bracket br(ctx, s, TR_KERNEL_OPROJ);
+              n_ss = launch_gemm_oproj_residual(s, D, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), R, x, w.ln2, ctx->at<uint4>(L.pack_d), ctx->at<float>(L.sumsq), L.ss_stride, live); }
+            { Bracket br(ctx, s, TR_KERNEL_GATEUP);
+              launch_gemm_swiglu(s, D, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), R, ctx->at<uint4>(L.pack_h), live, ctx->at<float>(L.sumsq), n_ss, L.ss_stride); }
+        } else {
+            { Bracket br(ctx, s, TR_KERNEL_OPROJ); launch_gemm_partial(s, ctx->wt(l, L.wt_o), ctx->at<uint4>(L.pack_a), D.qw, D.d, R, part, &pending, live); }
+            p.nsplit = pending; p.gain = (const bf16_t *)w.ln2;
+            { Bracket br(ctx, s, TR_KERNEL_PREP); launch_prep(s, p); }
+            { Bracket br(ctx, s, TR_KERNEL_GATEUP); launch_gemm_swiglu(s, D, ctx->wt(l, L.wt_gu), ctx->at<uint4>(L.pack_d), R, ctx->at<uint4>(L.pack_h), live); }
+        }
         { Bracket br(ctx, s, TR_KERNEL_DOWN); launch_gemm_partial(s, ctx->wt(l, L.wt_d), ctx->at<uint4>(L.pack_h), D.F, D.d, R, part, &pending, live); }
     }
     return pending;

@@ -173,7 +173,15 @@ int mfma_ncb(int M);
 void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out, const int *live = nullptr);
 void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, const void *pack, const float *bias, Rows rows, const float2 *rope,
                      float *q, void *kc, void *vc);
-void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack, const int *live = nullptr);
+// sumsq != NULL: the packed activations lack the 1/rms factor; it is applied to the sums from the rows' sums of squares sumsq[row * ss_stride + i], i < n_ss (ss_stride a multiple of 4)
+void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack, const int *live = nullptr,
+                        const float *sumsq = nullptr, int n_ss = 0, int ss_stride = 0);
+// Output projection without split-K whose epilogue updates the residual stream x and writes the next linear layer's packed input as
+// x * gain (no 1/rms) together with the rows' sums of squares per tile range (returns how many tile ranges: the consumer's n_ss).
+// Needs the whole reduction dimension inside one workgroup: gemm_oproj_residual_supported().
+bool gemm_oproj_residual_supported(const Dims &D);
+int launch_gemm_oproj_residual(hipStream_t s, const Dims &D, const void *Wt, const void *pack_a, int M, float *x, const void *gain, void *pack_out,
+                               float *sumsq, int ss_stride, const int *live = nullptr);
 // Wide models (K beyond what one workgroup keeps resident): every linear layer goes through split-K partials, and the
 // layers with a non-linear epilogue are finished by a small kernel of their own.
 // number of partial buffers launch_gemm_partial will produce for a K x N layer
