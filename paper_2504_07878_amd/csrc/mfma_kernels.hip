@@ -823,6 +823,7 @@ struct EpiPartial {   // split-K partial sums: part[split][m][n]
     __device__ void block(int, int) {}
     __device__ void begin() {}
     __device__ void row(int) {}
+    __device__ void row_ready() {}
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         const int n = t * 32 + i0;
@@ -857,6 +858,7 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
         if (page) { runit = ptab[(size_t)runit * maxp + rpos / page]; rupos = rpos % page; }
         if (live) M = min(M, *live);
     }
+    __device__ void row_ready() {}
     // v: tile rows i0..i0+7 = the pairs (j, j + dh/2), j = 16*sub + i0/2 .. +3, as (first, partner) x 4
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
@@ -927,19 +929,27 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
     float rstd;
     __device__ void block(int, int) {}
     __device__ void begin() {}
+    static constexpr int SS4 = 7;   // 16-byte pieces of a row's sums of squares: up to 28 tile ranges (d <= 896)
+    float4 raw[SS4];
+    // requests only: the values are used in row_ready(), after the kernel has requested its activations, so that nothing waits here
     __device__ void row(int m)
+    {
+        if (sumsq) {
+            const float4 *sp = reinterpret_cast<const float4 *>(sumsq + (size_t)min(m, M - 1) * ss_stride);   // a row's values are consecutive
+            const int n4 = (n_ss + 3) >> 2;
+#pragma unroll
+            for (int i = 0; i < SS4; ++i) raw[i] = sp[min(i, n4 - 1)];
+        }
+    }
+    __device__ void row_ready()
     {
         rstd = 1.0f;
         if (sumsq) {
-            // a row's values are consecutive (ss_stride floats, a multiple of 4): 16-byte requests, two at a time, added in a fixed order
-            const float4 *sp = reinterpret_cast<const float4 *>(sumsq + (size_t)min(m, M - 1) * ss_stride);
-            const int n4 = (n_ss + 3) >> 2;
             float tot = 0.f;
-            for (int i0 = 0; i0 < n4; i0 += 2) {
-                const float4 a = sp[i0], b = sp[min(i0 + 1, n4 - 1)];
-                const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
-                for (int u = 0; u < 8; ++u) tot += 4 * i0 + u < n_ss ? v[u] : 0.f;   // entries past n_ss are not the row's
+            for (int i = 0; i < SS4; ++i) {   // fixed order; entries past n_ss are not the row's
+                tot += 4 * i < n_ss ? raw[i].x : 0.f; tot += 4 * i + 1 < n_ss ? raw[i].y : 0.f;
+                tot += 4 * i + 2 < n_ss ? raw[i].z : 0.f; tot += 4 * i + 3 < n_ss ? raw[i].w : 0.f;
             }
             rstd = 1.0f / sqrtf(tot * inv_d + eps);
         }
@@ -979,6 +989,7 @@ struct EpiResidualNorm {
     __device__ void block(int b, int) { bx = b; }
     __device__ void begin() { ss = 0.f; }
     __device__ void row(int r) { m = r; }
+    __device__ void row_ready() {}
     template <int PAR> __device__ void tile(int t, int mm, int i0, const float (&v)[8])
     {
         const int n0 = t * 32 + i0;
@@ -1026,6 +1037,7 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     __device__ void block(int b, int g) { bx = b; grp = g; }
     __device__ void begin() { mx = -INFINITY; sum = 0.f; idx = 0x7fffffff; }
     __device__ void row(int) {}
+    __device__ void row_ready() {}
     // Branch-free: rows past M have all-zero activations, so their statistics are finite and simply never written.
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&vin)[8])
     {
@@ -1132,6 +1144,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     }
 
+    epi.row_ready();
     const int t0 = min(bx * a.tiles_per_wg, a.n_tiles), t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
     const size_t tile_stride = (size_t)a.KS * 64;
     uint4 w[2][KW];
@@ -1285,6 +1298,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     }
 
+    epi.row_ready();
     const int t0 = min(bx * a.tiles_per_wg, a.n_tiles), t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
     const size_t tile_stride = (size_t)a.KS * 64;
     uint4 w[KW2];
@@ -1626,10 +1640,10 @@ void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = 2 * ((D.F + 31) / 32); a.M = M; a.live = live;
     a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, (M + 63) / 64, 2);   // whole gate/up pairs
     if (D.F % 32) {
-        EpiSwiglu<true> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f};
+        EpiSwiglu<true> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f, {}};
         launch_gemm(s, a, 1, e);
     } else {
-        EpiSwiglu<false> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f};
+        EpiSwiglu<false> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f, {}};
         launch_gemm(s, a, 1, e);
     }
 }
