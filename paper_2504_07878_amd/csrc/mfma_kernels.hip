@@ -369,7 +369,7 @@ __device__ __forceinline__ void to_hi_lo(const float (&v)[8], bf16x8 &hi, bf16x8
 // MULTI: the 32 accumulator columns hold the heads of nq <= 32/G consecutive query rows of one sequence (column c = row c/G,
 // head c%G) instead of one row's heads in the first G columns: the keys and values of the context are fetched once for all of
 // them (the rows of a prompt). qrow is then the first of these rows, j1 the context of the LAST one; row i sees j1 - (nq-1) + i keys.
-template <int DH, bool PAGED, bool MULTI = false>
+template <int DH, bool PAGED, bool MULTI = false, int NBLK = (DH == 64 ? 2 : 1)>
 struct AttnWave {
     static constexpr int KSQ = DH / 16, DB = DH / 32;
     float m, l;
@@ -407,8 +407,9 @@ struct AttnWave {
 #pragma unroll
             for (int rr = 0; rr < 16; ++rr) o[db][rr] = 0.f;
 
-        // NB blocks of 32 keys are requested together (64-wide heads: 64 keys in flight at once)
-        constexpr int NB = DH == 64 ? 2 : 1;
+        // NB blocks of 32 keys are requested together (64-wide heads: 64 keys in flight at once; three or four at once measured no faster:
+        // a compute unit's requests in flight are limited well below what one wavefront can ask for)
+        constexpr int NB = NBLK;
         for (int t0 = t_begin; t0 < j1; t0 += NB * t_step) {
             uint4 ka[NB][KSQ], va[NB][2][DB];
 #pragma unroll
@@ -424,6 +425,7 @@ struct AttnWave {
                     tv = t % D.page;
                     kp = Kb + (size_t)(tv + min(krow, j1 - 1 - t)) * DH + hf * 8;
                 } else {                    // rows are clamped, V^T rows are padded to 32
+                    t = min(t, t_last);     // a block past the context: its requests repeat the row's last block and are not used
                     kp = Kb + (size_t)min(t + krow, j1 - 1) * DH + hf * 8;
                     tv = min(t, D.vts - 32);
                 }
@@ -822,8 +824,8 @@ struct EpiPartial {   // split-K partial sums: part[split][m][n]
     int N, M;
     __device__ void block(int, int) {}
     __device__ void begin() {}
-    __device__ void row(int) {}
-    __device__ void row_ready() {}
+    __device__ void row(int, int) {}
+    __device__ void row_ready(float *, int, int) {}
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
         const int n = t * 32 + i0;
@@ -852,13 +854,13 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
     const int *live;          // device-side row count or NULL: rows from *live on are padding and store nothing
     __device__ void block(int, int) {}
     __device__ void begin() {}
-    __device__ void row(int m)
+    __device__ void row(int m, int)
     {
         rpos = pos[min(m, M - 1)]; runit = slot[min(m, M - 1)]; rupos = rpos;
         if (page) { runit = ptab[(size_t)runit * maxp + rpos / page]; rupos = rpos % page; }
         if (live) M = min(M, *live);
     }
-    __device__ void row_ready() {}
+    __device__ void row_ready(float *, int, int) {}
     // v: tile rows i0..i0+7 = the pairs (j, j + dh/2), j = 16*sub + i0/2 .. +3, as (first, partner) x 4
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&v)[8])
     {
@@ -913,44 +915,44 @@ struct EpiQkv {       // bias, rotary embedding, q out, cache append; tiles hold
     __device__ void end(float *, int, int) {}
 };
 
-// RAGGED: F is not a multiple of 32, the last tile pair is partly empty
-template <bool RAGGED>
+// RAGGED: F is not a multiple of 32, the last tile pair is partly empty.
+// DEFER: deferred RMSNorm. The packed activations are x * gain WITHOUT the 1/rms factor (they were written by the epilogue of the
+// output projection, which only knows its own 32 features of a row); W.(g*x/rms) = W.(g*x) / rms, so the factor is applied to the
+// sums here. sumsq[m * ss_stride + i], i < n_ss <= 32: the row's sum of squares over the features of tile range i (ss_stride >= 32, a
+// multiple of 4). The four threads that finish a row (one per band of 8 features) each fetch a quarter of the row's values and add
+// them through LDS in band order: 8 registers per thread while the resident activations are being requested, not 32.
+template <bool RAGGED, bool DEFER>
 struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written as packed activations of the down projection
     static constexpr bool half_only = false;
     uint4 *hpack;     // [group][F/16][NCB][64]
     int M, F, ncb;
     float hold[8];
-    // Deferred RMSNorm: when sumsq is given, the packed activations are x * gain WITHOUT the 1/rms factor (they were written by the
-    // epilogue of the output projection, which only knows its own 32 features of a row); W.(g*x/rms) = W.(g*x) / rms, so the factor
-    // is applied to the sums here. sumsq[m * ss_stride + i], i < n_ss: the row's sum of squares over the features of tile range i.
     const float *sumsq;
     int n_ss, ss_stride;
     float eps, inv_d;
     float rstd;
+    float4 raw[2];
     __device__ void block(int, int) {}
     __device__ void begin() {}
-    static constexpr int SS4 = 7;   // 16-byte pieces of a row's sums of squares: up to 28 tile ranges (d <= 896)
-    float4 raw[SS4];
     // requests only: the values are used in row_ready(), after the kernel has requested its activations, so that nothing waits here
-    __device__ void row(int m)
+    __device__ void row(int m, int band)
     {
-        if (sumsq) {
-            const float4 *sp = reinterpret_cast<const float4 *>(sumsq + (size_t)min(m, M - 1) * ss_stride);   // a row's values are consecutive
-            const int n4 = (n_ss + 3) >> 2;
-#pragma unroll
-            for (int i = 0; i < SS4; ++i) raw[i] = sp[min(i, n4 - 1)];
+        if (DEFER) {
+            const float4 *sp = reinterpret_cast<const float4 *>(sumsq + (size_t)min(m, M - 1) * ss_stride) + 2 * band;
+            raw[0] = sp[0]; raw[1] = sp[1];
         }
     }
-    __device__ void row_ready()
+    // lds: 256 floats that nothing else uses before the workgroup's next barrier; every thread of the workgroup calls this
+    __device__ void row_ready(float *lds, int row_local, int band)
     {
-        rstd = 1.0f;
-        if (sumsq) {
-            float tot = 0.f;
-#pragma unroll
-            for (int i = 0; i < SS4; ++i) {   // fixed order; entries past n_ss are not the row's
-                tot += 4 * i < n_ss ? raw[i].x : 0.f; tot += 4 * i + 1 < n_ss ? raw[i].y : 0.f;
-                tot += 4 * i + 2 < n_ss ? raw[i].z : 0.f; tot += 4 * i + 3 < n_ss ? raw[i].w : 0.f;
-            }
+        if (DEFER) {
+            const int i = 8 * band;   // entries past n_ss are not the row's
+            float p = i < n_ss ? raw[0].x : 0.f;
+            p += i + 1 < n_ss ? raw[0].y : 0.f; p += i + 2 < n_ss ? raw[0].z : 0.f; p += i + 3 < n_ss ? raw[0].w : 0.f;
+            p += i + 4 < n_ss ? raw[1].x : 0.f; p += i + 5 < n_ss ? raw[1].y : 0.f; p += i + 6 < n_ss ? raw[1].z : 0.f; p += i + 7 < n_ss ? raw[1].w : 0.f;
+            lds[band * 64 + row_local] = p;
+            __syncthreads();
+            const float tot = (lds[row_local] + lds[64 + row_local]) + (lds[128 + row_local] + lds[192 + row_local]);
             rstd = 1.0f / sqrtf(tot * inv_d + eps);
         }
     }
@@ -959,12 +961,12 @@ struct EpiSwiglu {    // tiles alternate gate, up; h = silu(gate) * up, written 
     {
         if (PAR == 0) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) hold[e] = v[e] * rstd;
+            for (int e = 0; e < 8; ++e) hold[e] = DEFER ? v[e] * rstd : v[e];
             return;
         }
         float h[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) h[e] = hold[e] * __frcp_rn(1.0f + __expf(-hold[e])) * (v[e] * rstd);   // hardware exp2 and reciprocal (1 ulp each)
+        for (int e = 0; e < 8; ++e) h[e] = hold[e] * __frcp_rn(1.0f + __expf(-hold[e])) * (DEFER ? v[e] * rstd : v[e]);   // hardware exp2 and reciprocal (1 ulp each)
         const int f0 = (t >> 1) * 32 + i0;
         // rows past M are written too: they lie inside the padded 64-row group and are never read back as valid rows
         if (!RAGGED || f0 < F) store_packed(hpack + (size_t)(m >> 6) * (F / 16) * ncb * 64, ncb, m & 63, f0 >> 3, h);
@@ -988,8 +990,8 @@ struct EpiResidualNorm {
     float ss;
     __device__ void block(int b, int) { bx = b; }
     __device__ void begin() { ss = 0.f; }
-    __device__ void row(int r) { m = r; }
-    __device__ void row_ready() {}
+    __device__ void row(int r, int) { m = r; }
+    __device__ void row_ready(float *, int, int) {}
     template <int PAR> __device__ void tile(int t, int mm, int i0, const float (&v)[8])
     {
         const int n0 = t * 32 + i0;
@@ -1036,8 +1038,8 @@ struct EpiLmHead {    // running softmax statistics per batch row; logits option
     int vt, r1_stride;
     __device__ void block(int b, int g) { bx = b; grp = g; }
     __device__ void begin() { mx = -INFINITY; sum = 0.f; idx = 0x7fffffff; }
-    __device__ void row(int) {}
-    __device__ void row_ready() {}
+    __device__ void row(int, int) {}
+    __device__ void row_ready(float *, int, int) {}
     // Branch-free: rows past M have all-zero activations, so their statistics are finite and simply never written.
     template <int PAR> __device__ void tile(int t, int m, int i0, const float (&vin)[8])
     {
@@ -1128,7 +1130,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int row0 = pgroup * 64 + hsel * 32;
     // what the epilogue needs per batch row is requested first: it is then the oldest request in flight and can be waited for
     // without waiting for anything younger
-    epi.row(row0 + (threadIdx.x & 63));
+    epi.row(row0 + (threadIdx.x & 63), threadIdx.x >> 6);
 
     // resident activations of this wavefront's k-steps (zero beyond its share, so the extra products vanish)
     bf16x8 b[KW][NCB];
@@ -1144,7 +1146,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     }
 
-    epi.row_ready();
     const int t0 = min(bx * a.tiles_per_wg, a.n_tiles), t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
     const size_t tile_stride = (size_t)a.KS * 64;
     uint4 w[2][KW];
@@ -1207,6 +1208,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     if (t0 < t1) {
         load_tile(t0, w[0]);
         if (t0 + 1 < t1) load_tile(t0 + 1, w[1]);
+        // per-row inputs: they were requested before everything else, and nothing younger is waited for here.
+        // The second LDS buffer is first written after the tile loop's first barrier.
+        epi.row_ready(red1, threadIdx.x & 63, threadIdx.x >> 6);
         mfma_tile(w[0]);
         if (t0 + 2 < t1) load_tile(t0 + 2, w[0]);
         // from here on: acc = sums of tile t, w[1] = tile t + 1, w[0] = tile t + 2 (where they exist).
@@ -1282,7 +1286,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
     epi.block(bx, group);
     const int m = group * 64 + rh * 32 + (lane & 31), i0 = 16 * kh + 8 * hf;
-    epi.row(m);   // per-row inputs of the epilogue: requested first, so that they are the oldest requests in flight
+    epi.row(m, 2 * kh + hf);   // per-row inputs of the epilogue: requested first, so that they are the oldest requests in flight
 
     // resident activations: hi and lo halves of this wavefront's 32 rows over its k-steps (zero beyond its share)
     bf16x8 b[KW2][2];
@@ -1298,7 +1302,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
     }
 
-    epi.row_ready();
     const int t0 = min(bx * a.tiles_per_wg, a.n_tiles), t1 = min(a.n_tiles, t0 + a.tiles_per_wg);
     const size_t tile_stride = (size_t)a.KS * 64;
     uint4 w[KW2];
@@ -1346,6 +1349,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
             for (int kk = 0; kk < KW2; ++kk) w[kk] = wp[(size_t)koff[kk] * 64];
         }
+        // per-row inputs: they were requested before everything else, and nothing younger is waited for here.
+        // The second exchange buffer is first written after the tile loop's first barrier.
+        epi.row_ready(reinterpret_cast<float *>(&xb[1][0][0][0]), rh * 32 + (lane & 31), 2 * kh + hf);
         if (t0 + 1 < t1) mfma_tile(Yes{}, t0 + 1); else mfma_tile(No{}, t0);
         // from here on: the accumulators hold tile t, the ring holds tile t + 1 (where it exists).
         // Long tile ranges: nothing conditional inside, so the compiler can wait for exactly the registers it needs.
@@ -1639,13 +1645,13 @@ void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void
     GemmArgs a{};
     a.Wt = (const uint4 *)Wt; a.pack = (const uint4 *)pack; a.KS = D.d / 16; a.ksw = a.KS; a.n_tiles = 2 * ((D.F + 31) / 32); a.M = M; a.live = live;
     a.tiles_per_wg = tiles_per_workgroup(a.n_tiles, (M + 63) / 64, 2);   // whole gate/up pairs
-    if (D.F % 32) {
-        EpiSwiglu<true> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f, {}};
+    auto go = [&](auto e) {
+        e.hpack = (uint4 *)hpack; e.M = M; e.F = D.F; e.ncb = mfma_ncb(M);
+        e.sumsq = sumsq; e.n_ss = n_ss; e.ss_stride = ss_stride; e.eps = D.eps; e.inv_d = 1.0f / (float)D.d; e.rstd = 1.0f;
         launch_gemm(s, a, 1, e);
-    } else {
-        EpiSwiglu<false> e{(uint4 *)hpack, M, D.F, mfma_ncb(M), {}, sumsq, n_ss, ss_stride, D.eps, 1.0f / (float)D.d, 1.0f, {}};
-        launch_gemm(s, a, 1, e);
-    }
+    };
+    if (sumsq) { if (D.F % 32) go(EpiSwiglu<true, true>{}); else go(EpiSwiglu<false, true>{}); }
+    else { if (D.F % 32) go(EpiSwiglu<true, false>{}); else go(EpiSwiglu<false, false>{}); }
 }
 
 int launch_gemm_oproj_residual(hipStream_t s, const Dims &D, const void *Wt, const void *pack_a, int M, float *x, const void *gain, void *pack_out,
@@ -1660,7 +1666,7 @@ int launch_gemm_oproj_residual(hipStream_t s, const Dims &D, const void *Wt, con
     return (a.n_tiles + a.tiles_per_wg - 1) / a.tiles_per_wg;   // tile ranges = entries of sumsq per row
 }
 
-bool gemm_oproj_residual_supported(const Dims &D) { return D.qw / 16 <= NWAVES * MAXKW; }
+bool gemm_oproj_residual_supported(const Dims &D) { return D.qw / 16 <= NWAVES * MAXKW && (D.d + 31) / 32 <= 32; }   // one workgroup spans K; at most 32 tile ranges per row
 
 // tiles per workgroup of the LM-head launch: the whole launch (every 64-row group over every tile) is one round of at most 256 workgroups
 static int lmhead_tiles_per_wg(int n_tiles, int M)

@@ -44,7 +44,7 @@ struct Layout {
     size_t kvn;        // new keys and values of up to two decode rows, [row][2][kv width] floats (fused q|k|v + attention kernel)
     size_t dev_len;    // device-side sequence lengths [max_batch], used by the steps whose rows are selected on the device
     size_t sumsq;      // rows' sums of squares per tile range of the output projection, [max_rows][ss_stride] floats (deferred RMSNorm)
-    int ss_stride;     // ceil(d / 32) rounded up to a multiple of 4
+    int ss_stride;     // floats per row: 32, the most tile ranges the fused output projection has (one cache line per row)
     int maxp, pool;    // pages per slot (table row length) and pages in the pool; 0 for the contiguous cache
     int max_rows, nslices;
     // matrix-core paths: repacked weights, packed activations, split-K partials.
@@ -176,7 +176,7 @@ Layout make_layout(const tr_config *c)
     L.qblock = take(R * 4);
     L.kvn = take(2 * 2 * kvw * 4);
     L.dev_len = take((size_t)c->max_batch * 4);
-    L.ss_stride = ((c->d_model + 31) / 32 + 3) / 4 * 4;
+    L.ss_stride = 32;
     L.sumsq = take((size_t)L.ss_stride * R * 4);
     L.total = off;
     return L;

@@ -173,7 +173,7 @@ int mfma_ncb(int M);
 void launch_gemm_partial(hipStream_t s, const void *Wt, const void *pack, int K, int N, int M, float *part, int *nsplit_out, const int *live = nullptr);
 void launch_gemm_qkv(hipStream_t s, int kdt, const Dims &D, const void *Wt, const void *pack, const float *bias, Rows rows, const float2 *rope,
                      float *q, void *kc, void *vc);
-// sumsq != NULL: the packed activations lack the 1/rms factor; it is applied to the sums from the rows' sums of squares sumsq[row * ss_stride + i], i < n_ss (ss_stride a multiple of 4)
+// sumsq != NULL: the packed activations lack the 1/rms factor; it is applied to the sums from the rows' sums of squares sumsq[row * ss_stride + i], i < n_ss <= 32 <= ss_stride (a multiple of 4: every thread reads 8 consecutive floats of its row's first 32)
 void launch_gemm_swiglu(hipStream_t s, const Dims &D, const void *Wt, const void *pack, int M, void *hpack, const int *live = nullptr,
                         const float *sumsq = nullptr, int n_ss = 0, int ss_stride = 0);
 // Output projection without split-K whose epilogue updates the residual stream x and writes the next linear layer's packed input as
