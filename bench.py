@@ -401,13 +401,13 @@ def measured_traffic(family):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch, per kernel family, with the hash of the kernel sources they were taken on.
 TRAFFIC = {
-    "attention": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 23008562, "write_bytes": 1660144},
-    "gateup": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 19493924, "write_bytes": 1245184},
-    "down": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 19313709, "write_bytes": 1376256},
-    "qkv": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 6224580, "write_bytes": 507904},
-    "oproj": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 3643207, "write_bytes": 917504},
-    "prep": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 1028863, "write_bytes": 770703},
-    "lmhead": {"source_sha256": "672166dc6457d4ec2be8d8c99db5a9925d2e862d3ba2b61a28101712e792f704", "fetch_bytes": 274912151, "write_bytes": 322560},
+    "attention": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 20754998, "write_bytes": 1660144},
+    "gateup": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 19572754, "write_bytes": 1245184},
+    "down": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 19317791, "write_bytes": 1376256},
+    "qkv": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 6232768, "write_bytes": 507904},
+    "oproj": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 5444328, "write_bytes": 516096},
+    "prep": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 946609, "write_bytes": 809562},
+    "lmhead": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 274908528, "write_bytes": 322560},
 }
 
 
