@@ -478,6 +478,45 @@ def test_decode_steps_fed_from_device_memory(tr, tro, tiny_weights, dtype):
     assert np.array_equal(ya.logits, yb.logits)
 
 
+@pytest.mark.parametrize("B", [2, 8])
+def test_decode_step_replayed_from_a_captured_graph(tr, B):
+    """A device-fed decode step enqueues kernels only (no allocation, no host copy, no memset), so it can be captured into a
+    HIP graph. Every replay, with eager work of the same model and synchronisations in between, must give the bits of the
+    eager step it was captured from (2 rows: the streaming kernels; 8 rows: the matrix-core path with its exchange counters)."""
+    s = synth.TINY.with_(name="graph", dtype=synth.BF16, kv_dtype=synth.BF16, vocab=5003)
+    w = synth.make_weights(s, SEED + 41, std=0.05, bias_std=0.05, gain_std=0.1)
+    g = tr.Model(s.asdict(), w, B, 1200)
+    prompts = [synth.prompt_tokens(SEED, f"graph.p{i}", 900 + 37 * i if i == 0 else 5 + 23 * i, s.vocab) for i in range(B)]   # one row long enough for several attention parts
+    slots = list(range(B))
+    base = [len(p) for p in prompts]
+    g.prefill(slots, prompts)
+    toks = torch.from_numpy(synth.prompt_tokens(SEED, "graph.t", B, s.vocab)).cuda()
+    other = torch.from_numpy(synth.prompt_tokens(SEED, "graph.o", B, s.vocab)).cuda()
+    eager = g.decode_step_dev(slots, toks, want_logits=True).cpu()
+    for sl, n in zip(slots, base):
+        g.seq_truncate(sl, n)
+    out = g.outputs(B, want_logits=True)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        g.decode_step_dev(slots, toks, out)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for f in (out.token, out.flag, out.conf, out.score, out.logits, out.hidden):
+            f.fill_(0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = out.cpu()
+        for name in ("token", "flag", "conf", "score", "logits", "hidden"):
+            assert np.array_equal(getattr(got, name), getattr(eager, name)), f"replay {rep}: {name}"
+        # eager work of the same model between the replays: a step on the next position with other tokens, rolled back again
+        g.decode_step_dev(slots, other, want_logits=True)
+        torch.cuda.synchronize()
+        for sl, n in zip(slots, base):
+            g.seq_truncate(sl, n + 1)
+
+
 @pytest.mark.parametrize("kv_page", [0, 32])
 def test_one_and_two_row_decode_steps_at_chunk_boundaries(tr, tro, kv_page):
     """Decode steps of one or two sequences with bf16 weights and cache run the projection and the attention over the cached
