@@ -1293,8 +1293,12 @@ static void launch_residual_gemv(hipStream_t s, const void *W, const Stage &in, 
     else hipLaunchKernelGGL((residual_gemv_kernel<WT, 4, Stage>), dim3(gx, (R + 3) / 4), dim3(256), 0, s, (const WT *)W, in, R, N, K, x);
 }
 
+// x += W in for 2 to 4 plain rows of a wide bf16 matrix, with the rows kept in registers (down_rows_kernel below); false: not served
+static bool launch_residual_rows(hipStream_t s, int wdt, const void *W, const float *in, int R, int N, int K, float *x);
+
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x)
 {
+    if (pend.nchunks == 0 && launch_residual_rows(s, wdt, wo, att, R, D.d, D.qw, x)) return;
     if (pend.nchunks > 0) {
         const StageAttn st{pend, D.Hq, D.dh, 0};
         if (wdt == DT_F32) launch_residual_gemv<float>(s, wo, st, R, D.d, D.qw, x);
@@ -1304,13 +1308,6 @@ void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const f
     const StageRows st{att, (size_t)D.qw};
     if (wdt == DT_F32) { if (!launch_residual_splitk<float>(s, wo, att, R, D.d, D.qw, x)) launch_residual_gemv<float>(s, wo, st, R, D.d, D.qw, x); }
     else if (!launch_residual_splitk<bf16_t>(s, wo, att, R, D.d, D.qw, x)) launch_residual_gemv<bf16_t>(s, wo, st, R, D.d, D.qw, x);
-}
-
-void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x)
-{
-    const StageRows st{h, (size_t)D.F};
-    if (wdt == DT_F32) { if (!launch_residual_splitk<float>(s, wd, h, R, D.d, D.F, x)) launch_residual_gemv<float>(s, wd, st, R, D.d, D.F, x); }
-    else if (!launch_residual_splitk<bf16_t>(s, wd, h, R, D.d, D.F, x)) launch_residual_gemv<bf16_t>(s, wd, st, R, D.d, D.F, x);
 }
 
 // ------------------------------------------------------------------ FFN input: h = silu(Wg n) * (Wu n), n = RMSNorm(x; ln2)
@@ -1335,6 +1332,281 @@ __global__ __launch_bounds__(256) void gateup_kernel(Dims D, const WT *wg, const
         }
 }
 
+// ------------------------------------------------------------------ wide models, up to 4 rows: FFN with the activations in registers
+// The kernels above stage the activation rows in LDS once per workgroup of 4 output features; with thousands of such
+// workgroups and rows of 3584 to 18944 columns the staging traffic and the LDS reads per weight (32 bytes per row and
+// 16-byte weight load) cost as much as the weight stream itself from two rows on. Here a launch has ONE workgroup per compute
+// unit, whose wavefronts keep their share of the activation columns in registers for the whole launch and walk the output
+// features; per feature a wavefront only streams its share of the weight row (several features in flight) and adds across its
+// lanes. Reductions have a fixed shape (lanes: a fixed tree; wavefronts: in index order), so results are the same from run to run.
+
+// Sums each of v[0..NV) over the 64 lanes. Halving steps first (lanes whose bit `mask` is set keep the upper half of the values
+// and hand the lower half to their partner), so NV values cost NV - 1 + log2(64 / NV) exchanges instead of 6 NV. Returns the
+// total of value `idx`, which differs by lane: idx = the top log2(NV) bits of the lane index.
+template <int N, int NV>
+__device__ __forceinline__ void lanes_halve(float (&v)[NV], int lane, int mask, int &idx)
+{
+    const bool up = (lane & mask) != 0;
+#pragma unroll
+    for (int i = 0; i < N / 2; ++i) {
+        const float keep = up ? v[N / 2 + i] : v[i], send = up ? v[i] : v[N / 2 + i];
+        v[i] = keep + __shfl_xor(send, mask, 64);
+    }
+    idx = 2 * idx + (up ? 1 : 0);
+}
+
+template <int NV>
+__device__ __forceinline__ float lanes_sum_scatter(float (&v)[NV], int lane, int &idx)
+{
+    static_assert(NV == 1 || NV == 2 || NV == 4 || NV == 8, "power of two");
+    int mask = 32;
+    idx = 0;
+    if constexpr (NV == 8) { lanes_halve<8>(v, lane, 32, idx); lanes_halve<4>(v, lane, 16, idx); lanes_halve<2>(v, lane, 8, idx); mask = 4; }
+    else if constexpr (NV == 4) { lanes_halve<4>(v, lane, 32, idx); lanes_halve<2>(v, lane, 16, idx); mask = 8; }
+    else if constexpr (NV == 2) { lanes_halve<2>(v, lane, 32, idx); mask = 16; }
+    float r = v[0];
+    for (; mask > 0; mask >>= 1) r += __shfl_xor(r, mask, 64);
+    return r;
+}
+
+constexpr int ROWS_WAVES = 8;        // wavefronts per workgroup
+constexpr int GU_MAX_FEATURES = 64;  // output features a pair of wavefronts may own (LDS for their partial sums)
+
+// h = silu(Wg n) * (Wu n), n = RMSNorm(x; gain), for R <= MB rows. The 8 wavefronts form 4 pairs; the two wavefronts of a pair
+// split the columns (512-column chunks: the first NCH to one, the rest to the other) and pair p of workgroup b owns the
+// features 4 b + p, + 4 gridDim.x, ... . K <= 2 * NCH * 512, K % 8 == 0.
+template <int MB, int NCH>
+__global__ __launch_bounds__(64 * ROWS_WAVES) void gateup_rows_kernel(Dims D, const bf16_t *wg, const bf16_t *wu, const bf16_t *gain, const float *x, int R,
+                                                                        float *h)
+{
+    constexpr int NV = 2 * MB;
+    __shared__ float s_ss[ROWS_WAVES][MB];
+    __shared__ float s_part[ROWS_WAVES][GU_MAX_FEATURES][NV];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, pair = wave >> 1, half = wave & 1;
+    const int K = D.d, F = D.F;
+    // this wavefront's columns: chunk c covers 512 c + 8 lane .. + 7
+    int kcol[NCH];
+    bool klive[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int k = (half * NCH + c) * 512 + lane * 8;
+        klive[c] = k < K;
+        kcol[c] = klive[c] ? k : K - 8;   // a column group past the row: its activations are zero, its weight requests repeat the row's last 16 bytes
+    }
+    const int stride = gridDim.x * 4, f0 = blockIdx.x * 4 + pair;
+    const int nf = f0 < F ? (F - f0 + stride - 1) / stride : 0;   // features of this pair (<= GU_MAX_FEATURES: the launcher sees to it)
+    uint4 w[3][2][NCH];
+    auto request = [&](int i, uint4 (&ws)[2][NCH]) {   // unconditional: past the last feature the last one is requested again
+        const size_t f = (size_t)(f0 + min(i, nf - 1) * stride);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            ws[0][c] = *reinterpret_cast<const uint4 *>(wg + f * K + kcol[c]);
+            ws[1][c] = *reinterpret_cast<const uint4 *>(wu + f * K + kcol[c]);
+        }
+    };
+    // the first weight rows are requested before the activations: their addresses do not depend on them
+    if (nf > 0) {
+        request(0, w[0]);
+        request(1, w[1]);
+    }
+    float xa[NCH][8][MB];
+    float ss[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) ss[m] = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        float g[8];
+        load8(gain + kcol[c], g);
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = 0.f;
+            if (klive[c] && m < R) load8(x + (size_t)m * K + kcol[c], v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { ss[m] = fmaf(v[e], v[e], ss[m]); xa[c][e][m] = v[e] * g[e]; }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const float t = wave_sum(ss[m]);
+        if (lane == 0) s_ss[wave][m] = t;
+    }
+    auto consume = [&](int i, const uint4 (&ws)[2][NCH]) {
+        float acc[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) acc[j] = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const uint32_t u[4] = {ws[r][c].x, ws[r][c].y, ws[r][c].z, ws[r][c].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float wv = __uint_as_float((e & 1) ? (u[e >> 1] & 0xffff0000u) : (u[e >> 1] << 16));
+#pragma unroll
+                    for (int m = 0; m < MB; ++m) acc[r * MB + m] = fmaf(wv, xa[c][e][m], acc[r * MB + m]);
+                }
+            }
+        int idx;
+        const float t = lanes_sum_scatter<NV>(acc, lane, idx);
+        if ((lane & (64 / NV - 1)) == 0) s_part[wave][i][idx] = t;
+    };
+    if (nf > 0) {
+        for (int i = 0; i < nf; i += 3) {   // two features are in flight while one is multiplied
+            request(i + 2, w[2]);
+            consume(i, w[0]);
+            if (i + 1 >= nf) break;
+            request(i + 3, w[0]);
+            consume(i + 1, w[1]);
+            if (i + 2 >= nf) break;
+            request(i + 4, w[1]);
+            consume(i + 2, w[2]);
+        }
+    }
+    __syncthreads();
+    // (pair, feature, row): the halves are added in index order, then 1/rms, SiLU and the product
+    for (int t = threadIdx.x; t < 4 * GU_MAX_FEATURES * MB; t += blockDim.x) {
+        const int m = t % MB, i = (t / MB) % GU_MAX_FEATURES, p = t / (MB * GU_MAX_FEATURES);
+        const int f = blockIdx.x * 4 + p + i * stride;
+        if (m >= R || f >= F) continue;
+        const float tot = s_ss[0][m] + s_ss[1][m];   // every pair saw the whole row: the two halves of pair 0
+        const float rstd = 1.0f / sqrtf(tot / (float)K + D.eps);
+        const float gt = (s_part[2 * p][i][m] + s_part[2 * p + 1][i][m]) * rstd, up = (s_part[2 * p][i][MB + m] + s_part[2 * p + 1][i][MB + m]) * rstd;
+        h[(size_t)m * F + f] = gt / (1.0f + expf(-gt)) * up;
+    }
+}
+
+constexpr int DOWN_MAX_FEATURES = 32;   // output features a workgroup may own
+
+// x[m] += Wd h[m] for R <= MB rows. The 8 wavefronts split the columns (512-column chunk c goes to wavefront c % 8, NCH chunks
+// each at most) and the workgroup owns the features blockIdx.x, + gridDim.x, ... . K <= 8 * NCH * 512, K % 8 == 0.
+template <int MB, int NCH>
+__global__ __launch_bounds__(64 * ROWS_WAVES) void down_rows_kernel(const bf16_t *wd, const float *hin, int R, int N, int K, float *x)
+{
+    constexpr int DEPTH = 3;   // two features in flight while one is multiplied (twelve, for wavefronts that own one chunk, measured slower)
+    __shared__ float s_part[ROWS_WAVES][DOWN_MAX_FEATURES][MB];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int kcol[NCH];
+    bool klive[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int k = (c * ROWS_WAVES + wave) * 512 + lane * 8;
+        klive[c] = k < K;
+        kcol[c] = klive[c] ? k : K - 8;
+    }
+    const int stride = gridDim.x, f0 = blockIdx.x;
+    const int nf = f0 < N ? (N - f0 + stride - 1) / stride : 0;   // <= DOWN_MAX_FEATURES: the launcher sees to it
+    uint4 w[DEPTH][NCH];
+    // unconditional, so that the number of requests in flight is known at compile time and a feature can be waited for alone (requests
+    // under a condition measured 6.1-7.1 -> 7.5 us on the 7B-class output projection); past the last feature the last one is requested again
+    auto request = [&](int i, uint4 (&ws)[NCH]) {
+        const size_t f = (size_t)(f0 + min(i, nf - 1) * stride);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) ws[c] = *reinterpret_cast<const uint4 *>(wd + f * K + kcol[c]);
+    };
+    if (nf > 0) {   // before the activations: the addresses do not depend on them
+#pragma unroll
+        for (int d = 0; d < DEPTH - 1; ++d) request(d, w[d]);
+    }
+    float xa[NCH][8][MB];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = 0.f;
+            if (klive[c] && m < R) load8(hin + (size_t)m * K + kcol[c], v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xa[c][e][m] = v[e];
+        }
+    auto consume = [&](int i, const uint4 (&ws)[NCH]) {
+        float acc[MB];
+#pragma unroll
+        for (int m = 0; m < MB; ++m) acc[m] = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const uint32_t u[4] = {ws[c].x, ws[c].y, ws[c].z, ws[c].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float wv = __uint_as_float((e & 1) ? (u[e >> 1] & 0xffff0000u) : (u[e >> 1] << 16));
+#pragma unroll
+                for (int m = 0; m < MB; ++m) acc[m] = fmaf(wv, xa[c][e][m], acc[m]);
+            }
+        }
+        int idx;
+        const float t = lanes_sum_scatter<MB>(acc, lane, idx);
+        if ((lane & (64 / MB - 1)) == 0) s_part[wave][i][idx] = t;
+    };
+    for (int i = 0; i < nf; i += DEPTH) {   // DEPTH - 1 features are in flight while one is multiplied
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (i + d >= nf) break;
+            request(i + d + DEPTH - 1, w[(d + DEPTH - 1) % DEPTH]);
+            consume(i + d, w[d]);
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < DOWN_MAX_FEATURES * MB; t += blockDim.x) {
+        const int m = t % MB, i = t / MB, f = f0 + i * stride;
+        if (m >= R || i >= nf) continue;
+        float tot = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < ROWS_WAVES; ++wv) tot += s_part[wv][i][m];   // wavefronts in index order
+        x[(size_t)m * N + f] += tot;
+    }
+}
+
+// The two kernels above serve bf16 models wider than 1024 columns at 2 to 4 rows, within the column counts their register
+// arrays are built for (7B-class FFN, kernel time at 1 / 2 / 4 rows: gate/up 44.0 / 44.8 / 50.3 us against 43.4 / 48.4 / 69 us for the
+// kernel that stages the rows in LDS, down 22.9 / 23.6 / 26.9 against 23.3 / 28.3 / 41 us: one row stays where it was).
+bool ffn_rows_supported(int wdt, const Dims &D, int R)
+{
+    return wdt == DT_BF16 && R >= 2 && R <= 4 && D.d > 1024 && D.d <= 4096 && D.d % 8 == 0 && D.F % 8 == 0 && D.F <= 5 * ROWS_WAVES * 512 &&
+           D.F <= GU_MAX_FEATURES * 1024 && D.d <= DOWN_MAX_FEATURES * 256 && D.qw > 1024 && D.qw % 8 == 0 && D.qw <= 5 * ROWS_WAVES * 512;   // (the output projection too)
+}
+
+template <int MB>
+static void launch_gateup_rows(hipStream_t s, const Dims &D, const LayerW &w, const float *x, int R, float *h)
+{
+    const int grid = std::min(256, (D.F + 3) / 4);   // one workgroup per compute unit; every pair then owns at most F / 1024 features (rounded up)
+    const bf16_t *wg = (const bf16_t *)w.wg, *wu = (const bf16_t *)w.wu, *ln = (const bf16_t *)w.ln2;
+    const int chunks = (D.d + 511) / 512;
+    if (chunks <= 4) hipLaunchKernelGGL((gateup_rows_kernel<MB, 2>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, D, wg, wu, ln, x, R, h);
+    else if (chunks <= 6) hipLaunchKernelGGL((gateup_rows_kernel<MB, 3>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, D, wg, wu, ln, x, R, h);
+    else hipLaunchKernelGGL((gateup_rows_kernel<MB, 4>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, D, wg, wu, ln, x, R, h);
+}
+
+template <int MB>
+static void launch_residual_rows_mb(hipStream_t s, const void *W, const float *in, int R, int N, int K, float *x)
+{
+    const int grid = std::min(256, N);
+    const int per = ((K + 511) / 512 + ROWS_WAVES - 1) / ROWS_WAVES;   // chunks per wavefront
+    const bf16_t *w = (const bf16_t *)W;
+    if (per <= 1) hipLaunchKernelGGL((down_rows_kernel<MB, 1>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, w, in, R, N, K, x);
+    else if (per <= 2) hipLaunchKernelGGL((down_rows_kernel<MB, 2>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, w, in, R, N, K, x);
+    else if (per <= 3) hipLaunchKernelGGL((down_rows_kernel<MB, 3>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, w, in, R, N, K, x);
+    else if (per <= 4) hipLaunchKernelGGL((down_rows_kernel<MB, 4>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, w, in, R, N, K, x);
+    else hipLaunchKernelGGL((down_rows_kernel<MB, 5>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, w, in, R, N, K, x);
+}
+
+static bool launch_residual_rows(hipStream_t s, int wdt, const void *W, const float *in, int R, int N, int K, float *x)
+{
+    if (wdt != DT_BF16 || R < 2 || R > 4 || K <= 1024 || K % 8 || K > 5 * ROWS_WAVES * 512 || N > DOWN_MAX_FEATURES * 256) return false;
+    if (R == 2) launch_residual_rows_mb<2>(s, W, in, R, N, K, x);
+    else launch_residual_rows_mb<4>(s, W, in, R, N, K, x);
+    return true;
+}
+
+void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x)
+{
+    if (ffn_rows_supported(wdt, D, R) && launch_residual_rows(s, wdt, wd, h, R, D.d, D.F, x)) return;
+    const StageRows st{h, (size_t)D.F};
+    if (wdt == DT_F32) { if (!launch_residual_splitk<float>(s, wd, h, R, D.d, D.F, x)) launch_residual_gemv<float>(s, wd, st, R, D.d, D.F, x); }
+    else if (!launch_residual_splitk<bf16_t>(s, wd, h, R, D.d, D.F, x)) launch_residual_gemv<bf16_t>(s, wd, st, R, D.d, D.F, x);
+}
+
 template <typename WT>
 static void launch_gateup_t(hipStream_t s, const Dims &D, const LayerW &w, const float *x, int R, float *h)
 {
@@ -1347,6 +1619,12 @@ static void launch_gateup_t(hipStream_t s, const Dims &D, const LayerW &w, const
 
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h)
 {
+    if (ffn_rows_supported(wdt, D, R)) {
+        if (R == 1) launch_gateup_rows<1>(s, D, w, x, R, h);
+        else if (R == 2) launch_gateup_rows<2>(s, D, w, x, R, h);
+        else launch_gateup_rows<4>(s, D, w, x, R, h);
+        return;
+    }
     if (wdt == DT_F32) launch_gateup_t<float>(s, D, w, x, R, h);
     else launch_gateup_t<bf16_t>(s, D, w, x, R, h);
 }

@@ -357,6 +357,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         const int ncb = mfma_ncb(R);
         float *part = ctx->at<float>(L.part);
         int pending = 0, ns = 0;
+        const bool ffn_rows = !live && ffn_rows_supported(ctx->c.dtype, D, R);
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
             PrepArgs p{};
@@ -367,6 +368,16 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
                 Bracket br(ctx, s, TR_KERNEL_QKV);
                 launch_gemm_partial(s, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), D.d, D.qw + 2 * D.kvw, R, part, &ns, live);
                 launch_qkv_finish(s, ctx->c.kv_dtype, D, part, ns, ctx->bias(l), rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
+            }
+            if (ffn_rows) {
+                // up to 4 rows: the output projection and the FFN run on the streaming kernels that keep the rows in registers (norm, SwiGLU
+                // and the residual updates inside them): attention leaves plain rows, nothing is packed or left as partials
+                attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part), attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, nullptr);
+                { Bracket br(ctx, s, TR_KERNEL_OPROJ); launch_oproj(s, ctx->c.dtype, D, w.wo, att, AttnPending{}, R, x); }
+                { Bracket br(ctx, s, TR_KERNEL_GATEUP); launch_gateup(s, ctx->c.dtype, D, w, x, R, h); }
+                { Bracket br(ctx, s, TR_KERNEL_DOWN); launch_down(s, ctx->c.dtype, D, w.wd, h, R, x); }
+                pending = 0;
+                continue;
             }
             attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                              attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);

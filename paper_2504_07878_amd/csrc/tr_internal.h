@@ -143,6 +143,9 @@ void launch_attention_mfma(hipStream_t s, const Dims &D, const float *q, const v
                            size_t part_floats, int *cnt, float *att, void *pack, int ncb, AttnPending *defer);
 void launch_attn_merge(hipStream_t s, const Dims &D, const float *part, int nchunks, Rows rows, int chunk, float *att, void *pack, int ncb);
 void launch_oproj(hipStream_t s, int wdt, const Dims &D, const void *wo, const float *att, const AttnPending &pend, int R, float *x);
+// bf16 models wider than 1024 columns, up to 4 rows: launch_gateup / launch_down run kernels that keep the activations in registers
+// (one workgroup per compute unit walks the output features) instead of staging them in LDS per group of features
+bool ffn_rows_supported(int wdt, const Dims &D, int R);
 void launch_gateup(hipStream_t s, int wdt, const Dims &D, const LayerW &w, const float *x, int R, float *h);
 void launch_down(hipStream_t s, int wdt, const Dims &D, const void *wd, const float *h, int R, float *x);
 void launch_tail(hipStream_t s, int wdt, const Dims &D, const TailArgs &t);
