@@ -544,9 +544,14 @@ static void launch_qkv_t(hipStream_t s, const Dims &D, const LayerW &w, const fl
         hipLaunchKernelGGL((qkv_kernel<WT, KT, 4>), dim3(gx, (rows.n + 3) / 4), dim3(256), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
 }
 
+// 2 to 4 rows of a wide bf16 model, rows kept in registers (qkv_rows_kernel below); false: not served
+static bool launch_qkv_rows(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q,
+                            void *kc, void *vc);
+
 void launch_qkv(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q,
                 void *kc, void *vc)
 {
+    if (launch_qkv_rows(s, wdt, kdt, D, w, x, rows, rope, q, kc, vc)) return;
     if (wdt == DT_F32 && kdt == DT_F32) launch_qkv_t<float, float>(s, D, w, x, rows, rope, q, kc, vc);
     else if (wdt == DT_F32) launch_qkv_t<float, bf16_t>(s, D, w, x, rows, rope, q, kc, vc);
     else if (kdt == DT_F32) launch_qkv_t<bf16_t, float>(s, D, w, x, rows, rope, q, kc, vc);
@@ -1475,6 +1480,167 @@ __global__ __launch_bounds__(64 * ROWS_WAVES) void gateup_rows_kernel(Dims D, co
         const float gt = (s_part[2 * p][i][m] + s_part[2 * p + 1][i][m]) * rstd, up = (s_part[2 * p][i][MB + m] + s_part[2 * p + 1][i][MB + m]) * rstd;
         h[(size_t)m * F + f] = gt / (1.0f + expf(-gt)) * up;
     }
+}
+
+constexpr int QKV_MAX_PAIRS = 16;   // rotary pairs a group of four wavefronts may own
+
+// [q|k|v] = W n + b, n = RMSNorm(x; gain), rotation of q and k at the row's position, k and v appended to the cache, for R <= MB
+// rows. As in the kernel above, with the two output rows (j, j + dh/2) of a head that the rotation pairs up in place of (gate, up),
+// and four wavefronts per pair of rows (two groups per workgroup; wavefront g of a group owns the 512-column chunks g NCH .. g NCH + NCH - 1):
+// there are fewer output rows here, and a finer share per wavefront spreads them more evenly. K <= 4 * NCH * 512, K % 8 == 0.
+template <typename KT, int MB, int NCH>
+__global__ __launch_bounds__(64 * ROWS_WAVES) void qkv_rows_kernel(Dims D, LayerW lw, const float *x, Rows rows, const float2 *rope, float *q, KT *kc, KT *vc)
+{
+    constexpr int NV = 2 * MB;
+    __shared__ float s_ss[ROWS_WAVES][MB];
+    __shared__ float s_part[ROWS_WAVES][QKV_MAX_PAIRS][NV];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, group = wave >> 2, part = wave & 3;
+    const int K = D.d, R = rows.n, half = D.dh / 2, npairs = (D.Hq + 2 * D.Hkv) * half;
+    int kcol[NCH];
+    bool klive[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int k = (part * NCH + c) * 512 + lane * 8;
+        klive[c] = k < K;
+        kcol[c] = klive[c] ? k : K - 8;
+    }
+    const int stride = gridDim.x * 2, p0 = blockIdx.x * 2 + group;
+    const int nf = p0 < npairs ? (npairs - p0 + stride - 1) / stride : 0;   // <= QKV_MAX_PAIRS: the launcher sees to it
+    // the two weight rows of pair index pi
+    auto pair_rows = [&](int pi, const bf16_t *&r1, const bf16_t *&r2) {
+        const int hh = pi / half, j = pi % half;
+        const bf16_t *W = hh < D.Hq ? (const bf16_t *)lw.wq : hh < D.Hq + D.Hkv ? (const bf16_t *)lw.wk : (const bf16_t *)lw.wv;
+        const int head = hh < D.Hq ? hh : hh < D.Hq + D.Hkv ? hh - D.Hq : hh - D.Hq - D.Hkv;
+        r1 = W + (size_t)(head * D.dh + j) * K;
+        r2 = r1 + (size_t)half * K;
+    };
+    uint4 w[3][2][NCH];
+    auto request = [&](int i, uint4 (&ws)[2][NCH]) {   // unconditional: past the last pair the last one is requested again
+        const bf16_t *r1, *r2;
+        pair_rows(p0 + min(i, nf - 1) * stride, r1, r2);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            ws[0][c] = *reinterpret_cast<const uint4 *>(r1 + kcol[c]);
+            ws[1][c] = *reinterpret_cast<const uint4 *>(r2 + kcol[c]);
+        }
+    };
+    if (nf > 0) {   // before the activations: the addresses do not depend on them
+        request(0, w[0]);
+        request(1, w[1]);
+    }
+    float xa[NCH][8][MB];
+    float ss[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m) ss[m] = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        float g[8];
+        load8((const bf16_t *)lw.ln1 + kcol[c], g);
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = 0.f;
+            if (klive[c] && m < R) load8(x + (size_t)m * K + kcol[c], v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { ss[m] = fmaf(v[e], v[e], ss[m]); xa[c][e][m] = v[e] * g[e]; }
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const float t = wave_sum(ss[m]);
+        if (lane == 0) s_ss[wave][m] = t;
+    }
+    auto consume = [&](int i, const uint4 (&ws)[2][NCH]) {
+        float acc[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) acc[j] = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const uint32_t u[4] = {ws[r][c].x, ws[r][c].y, ws[r][c].z, ws[r][c].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float wv = __uint_as_float((e & 1) ? (u[e >> 1] & 0xffff0000u) : (u[e >> 1] << 16));
+#pragma unroll
+                    for (int m = 0; m < MB; ++m) acc[r * MB + m] = fmaf(wv, xa[c][e][m], acc[r * MB + m]);
+                }
+            }
+        int idx;
+        const float t = lanes_sum_scatter<NV>(acc, lane, idx);
+        if ((lane & (64 / NV - 1)) == 0) s_part[wave][i][idx] = t;
+    };
+    for (int i = 0; i < nf; i += 3) {   // two pairs are in flight while one is multiplied
+        request(i + 2, w[2]);
+        consume(i, w[0]);
+        if (i + 1 >= nf) break;
+        request(i + 3, w[0]);
+        consume(i + 1, w[1]);
+        if (i + 2 >= nf) break;
+        request(i + 4, w[1]);
+        consume(i + 2, w[2]);
+    }
+    __syncthreads();
+    // (group, pair, row): the four column shares are added in index order, then 1/rms, bias, rotation, and the stores
+    for (int t = threadIdx.x; t < 2 * QKV_MAX_PAIRS * MB; t += blockDim.x) {
+        const int m = t % MB, i = (t / MB) % QKV_MAX_PAIRS, g = t / (MB * QKV_MAX_PAIRS);
+        const int pi = blockIdx.x * 2 + g + i * stride;
+        if (m >= R || pi >= npairs) continue;
+        const int hh = pi / half, j = pi % half;
+        const float tot = (s_ss[0][m] + s_ss[1][m]) + (s_ss[2][m] + s_ss[3][m]);   // the four shares of group 0: the whole row
+        const float rstd = 1.0f / sqrtf(tot / (float)K + D.eps);
+        const float a1 = (s_part[4 * g][i][m] + s_part[4 * g + 1][i][m]) + (s_part[4 * g + 2][i][m] + s_part[4 * g + 3][i][m]);
+        const float a2 = (s_part[4 * g][i][MB + m] + s_part[4 * g + 1][i][MB + m]) + (s_part[4 * g + 2][i][MB + m] + s_part[4 * g + 3][i][MB + m]);
+        const bf16_t *bias = hh < D.Hq ? (const bf16_t *)lw.bq : hh < D.Hq + D.Hkv ? (const bf16_t *)lw.bk : (const bf16_t *)lw.bv;
+        const int head = hh < D.Hq ? hh : hh < D.Hq + D.Hkv ? hh - D.Hq : hh - D.Hq - D.Hkv;
+        const int n1 = head * D.dh + j, n2 = n1 + half;
+        float y1 = a1 * rstd + (bias ? widen(bias, n1) : 0.f), y2 = a2 * rstd + (bias ? widen(bias, n2) : 0.f);
+        const int pos = rows.pos[m];
+        if (hh < D.Hq + D.Hkv) {
+            const float2 cs = rope[(size_t)pos * half + j];
+            const float o1 = y1 * cs.x - y2 * cs.y, o2 = y2 * cs.x + y1 * cs.y;
+            y1 = o1; y2 = o2;
+        }
+        if (hh < D.Hq) {
+            q[(size_t)m * D.qw + n1] = y1;
+            q[(size_t)m * D.qw + n2] = y2;
+        } else {
+            const KvPlace place = kv_place(D, rows.slot[m], pos);
+            if (hh < D.Hq + D.Hkv) {
+                KT *dst = kc + k_offset(D, place.unit, head, place.pos, 0);
+                store_kv(dst + j, y1);
+                store_kv(dst + j + half, y2);
+            } else {
+                store_kv(vc + v_offset(D, place.unit, head, place.pos, j), y1);
+                store_kv(vc + v_offset(D, place.unit, head, place.pos, j + half), y2);
+            }
+        }
+    }
+}
+
+template <typename KT, int MB>
+static void launch_qkv_rows_mb(hipStream_t s, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q, void *kc, void *vc)
+{
+    const int npairs = (D.Hq + 2 * D.Hkv) * (D.dh / 2), grid = std::min(256, (npairs + 1) / 2);
+    const int chunks = (D.d + 511) / 512;
+    if (chunks <= 4) hipLaunchKernelGGL((qkv_rows_kernel<KT, MB, 1>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
+    else hipLaunchKernelGGL((qkv_rows_kernel<KT, MB, 2>), dim3(grid), dim3(64 * ROWS_WAVES), 0, s, D, w, x, rows, rope, q, (KT *)kc, (KT *)vc);
+}
+
+static bool launch_qkv_rows(hipStream_t s, int wdt, int kdt, const Dims &D, const LayerW &w, const float *x, Rows rows, const float2 *rope, float *q,
+                            void *kc, void *vc)
+{
+    const int npairs = (D.Hq + 2 * D.Hkv) * (D.dh / 2);
+    if (wdt != DT_BF16 || rows.n < 1 || rows.n > 4 || rows.live || D.d <= 1024 || D.d > 4096 || D.d % 8 || npairs > QKV_MAX_PAIRS * 512) return false;
+    auto go = [&](auto kt) {
+        using KT = decltype(kt);
+        if (rows.n == 1) launch_qkv_rows_mb<KT, 1>(s, D, w, x, rows, rope, q, kc, vc);
+        else if (rows.n == 2) launch_qkv_rows_mb<KT, 2>(s, D, w, x, rows, rope, q, kc, vc);
+        else launch_qkv_rows_mb<KT, 4>(s, D, w, x, rows, rope, q, kc, vc);
+    };
+    if (kdt == DT_F32) go(float{}); else go(bf16_t{});
+    return true;
 }
 
 constexpr int DOWN_MAX_FEATURES = 32;   // output features a workgroup may own

@@ -243,8 +243,9 @@ struct tr_ctx {
     char *wt(int l, size_t which) const { return ws + lay.wt_layers + (size_t)l * lay.wt_layer_stride + which; }
     float *bias(int l) const { return reinterpret_cast<float *>(ws + lay.bias + (size_t)l * lay.bias_stride); }
     bool use_mfma(int rows) const { return lay.mfma && rows > GEMV_MAX_ROWS; }
-    // wide models: the streaming kernels slow down with the rows (7B-class gate/up: 46 us at 1 row, 52 at 2, 69 at 4) while the
-    // matrix-core path is nearly flat in them; measured on the 7B-class model it wins from 3 rows on
+    // wide models: the streaming kernels that stage the rows in LDS slow down with the rows (7B-class gate/up: 46 us at 1 row, 52 at 2,
+    // 69 at 4) while the matrix-core path is nearly flat in them: it takes over from 3 rows on, except where run_layers finds the
+    // register-resident streaming kernels usable (2 to 4 rows)
     bool use_split(int rows) const { return lay.split && rows > 2; }
 };
 
@@ -352,12 +353,14 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
             launch_attention(s, ctx->c.kv_dtype, D, q_, ctx->kc_layer(l), ctx->vc_layer(l), rows_, max_ctx_, part_, part_floats_, cnt_, att_, pack_, ncb_, defer_);
         }
     };
-    if (ctx->use_split(R)) {
+    // Wide model, 3 and 4 rows whose count the host knows: the streaming kernels that keep the rows in registers (the last branch below)
+    // take fewer launches than the matrix-core path with its partials and finishing kernels (7B-class step at 3 rows: 3.9 -> 3.5 ms).
+    const bool rows_kernels = !live && ffn_rows_supported(ctx->c.dtype, D, R);
+    if (ctx->use_split(R) && !rows_kernels) {
         // wide model: every linear layer leaves split-K partials; rotary/cache append and SwiGLU are finished by kernels of their own
         const int ncb = mfma_ncb(R);
         float *part = ctx->at<float>(L.part);
         int pending = 0, ns = 0;
-        const bool ffn_rows = !live && ffn_rows_supported(ctx->c.dtype, D, R);
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
             PrepArgs p{};
@@ -368,16 +371,6 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
                 Bracket br(ctx, s, TR_KERNEL_QKV);
                 launch_gemm_partial(s, ctx->wt(l, L.wt_qkv), ctx->at<uint4>(L.pack_d), D.d, D.qw + 2 * D.kvw, R, part, &ns, live);
                 launch_qkv_finish(s, ctx->c.kv_dtype, D, part, ns, ctx->bias(l), rows, ctx->at<float2>(L.rope), q, ctx->kc_layer(l), ctx->vc_layer(l));
-            }
-            if (ffn_rows) {
-                // up to 4 rows: the output projection and the FFN run on the streaming kernels that keep the rows in registers (norm, SwiGLU
-                // and the residual updates inside them): attention leaves plain rows, nothing is packed or left as partials
-                attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part), attn_part_floats, ctx->at<int>(L.attn_cnt), att, nullptr, 0, nullptr);
-                { Bracket br(ctx, s, TR_KERNEL_OPROJ); launch_oproj(s, ctx->c.dtype, D, w.wo, att, AttnPending{}, R, x); }
-                { Bracket br(ctx, s, TR_KERNEL_GATEUP); launch_gateup(s, ctx->c.dtype, D, w, x, R, h); }
-                { Bracket br(ctx, s, TR_KERNEL_DOWN); launch_down(s, ctx->c.dtype, D, w.wd, h, R, x); }
-                pending = 0;
-                continue;
             }
             attend(l, q, rows, max_ctx, ctx->at<float>(L.attn_part),
                              attn_part_floats, ctx->at<int>(L.attn_cnt), att, ctx->at<uint4>(L.pack_a), ncb, nullptr);
@@ -393,7 +386,7 @@ int run_layers(tr_ctx *ctx, hipStream_t s, int R, int max_ctx, bool embed = true
         }
         return pending;
     }
-    if (!ctx->use_mfma(R)) {
+    if (!ctx->use_mfma(R) || rows_kernels) {
         AttnPending pend{};
         for (int l = 0; l < D.L; ++l) {
             const LayerW &w = ctx->layers[(size_t)l];
