@@ -372,6 +372,44 @@ def test_wide_bf16_model_on_the_split_k_path(tr, tro, B):
         assert g.seq_len(slot) == lens[i] + 3 + len(segs[i]) and tuple(cnt[slot]) == o.counters(slot)
 
 
+ROWS_SHAPES = {
+    # gate/up and q|k|v with a ragged last 512-column chunk, down projection over two chunks per wavefront, fp32 cache
+    "d2560": dict(d_model=2560, n_q_heads=10, n_kv_heads=2, head_dim=128, d_ffn=6152, vocab=3001, router_hidden=0, tie_lm_head=0, kv_dtype=synth.F32),
+    # three and four chunks per wavefront in the down projection, q width different from d, 64-wide heads
+    "d1536": dict(d_model=1536, n_q_heads=20, n_kv_heads=4, head_dim=64, d_ffn=12296, vocab=3001, router_hidden=40),
+    # the widest rows the kernels take: every register array full
+    "d4096": dict(d_model=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ffn=20480, vocab=2003, router_hidden=0, tie_lm_head=0),
+}
+
+
+@pytest.mark.parametrize("name,kv_page", [("d2560", 0), ("d1536", 32), ("d4096", 0)])
+def test_wide_models_with_the_rows_in_registers(tr, tro, name, kv_page):
+    """bf16 models of 1025 to 4096 columns at 1 to 4 rows: the q|k|v projection, the output projection and the FFN run on the
+    kernels that keep the rows' columns in registers (every chunk count the kernels are built for, ragged last chunks, fp32 and
+    paged caches); 5 rows take the matrix-core path. Decode steps at each row count and a short catch-up step against the oracle."""
+    s = synth.TINY.with_(name=name, n_layers=2, dtype=synth.BF16, **{"kv_dtype": synth.BF16, **ROWS_SHAPES[name]})
+    w = synth.make_weights(s, SEED + 17, std=0.02, bias_std=0.05, gain_std=0.1)
+    B, max_seq = 5, 96
+    kw = dict(kv_page=kv_page) if kv_page else {}
+    g = tr.Model(s.asdict(), w, B, max_seq, **kw); o = tro.Model(s.asdict(), w, B, max_seq)
+    prompts = [synth.prompt_tokens(SEED, f"rows.{name}.{i}", 3 + 9 * i, s.vocab) for i in range(B)]
+    slots = list(range(B))
+    go = g.prefill(slots, prompts, want_logits=True).cpu(); oo = o.prefill(slots, prompts, want_logits=True)
+    ex = compare_outputs(go, oo, s.dtype, s.threshold, f"{name} prefill", joint=s.router_hidden > 0)
+    toks = oo.token.copy()
+    for n in (1, 2, 3, 4, 5, 4, 2):                                   # rows of each step: the first n sequences
+        go = g.decode_step(slots[:n], toks[:n], want_logits=True).cpu(); oo = o.decode_step(slots[:n], toks[:n], want_logits=True)
+        ex += compare_outputs(go, oo, s.dtype, s.threshold, f"{name} step of {n} rows", joint=s.router_hidden > 0)
+        toks[:n] = oo.token
+    segs = [synth.prompt_tokens(SEED, f"rows.{name}.seg{i}", 1 + i, s.vocab) for i in range(2)]      # 3 rows: one and two tokens
+    go = g.extend(slots[:2], segs, want_logits=True).cpu(); oo = o.extend(slots[:2], segs, want_logits=True)
+    ex += compare_outputs(go, oo, s.dtype, s.threshold, f"{name} catch-up", joint=s.router_hidden > 0)
+    assert ex <= 2
+    cnt = g.counters()
+    for b in range(B):
+        assert g.seq_len(b) == o.seq_len(b) and tuple(cnt[b]) == o.counters(b)
+
+
 @pytest.mark.parametrize("dtype", [synth.F32, synth.BF16])
 def test_fork_of_a_sequence(tr, tro, dtype):
     """tr_seq_fork against the oracle: the copy and the original continue independently and each matches the oracle's
