@@ -401,13 +401,13 @@ def measured_traffic(family):
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --workload counters`, scaled by the 1 GiB copy kernel of the same
 # run (see profiles/); bytes per launch, per kernel family, with the hash of the kernel sources they were taken on.
 TRAFFIC = {
-    "attention": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 20754998, "write_bytes": 1660144},
-    "gateup": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 19572754, "write_bytes": 1245184},
-    "down": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 19317791, "write_bytes": 1376256},
-    "qkv": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 6232768, "write_bytes": 507904},
-    "oproj": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 5444328, "write_bytes": 516096},
-    "prep": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 946609, "write_bytes": 809562},
-    "lmhead": {"source_sha256": "7d12fc58ae718d864a0d8f28403736085acf2dc3066dcdcff0255b0e200923b6", "fetch_bytes": 274908528, "write_bytes": 322560},
+    "attention": {"source_sha256": "3c3c251f49f4dae610eb9c84ca2080ead685e0ede0a9a81077ff54542a8f159d", "fetch_bytes": 20754989, "write_bytes": 1660144},
+    "gateup": {"source_sha256": "3c3c251f49f4dae610eb9c84ca2080ead685e0ede0a9a81077ff54542a8f159d", "fetch_bytes": 19572731, "write_bytes": 1245184},
+    "down": {"source_sha256": "3c3c251f49f4dae610eb9c84ca2080ead685e0ede0a9a81077ff54542a8f159d", "fetch_bytes": 19317768, "write_bytes": 1376256},
+    "qkv": {"source_sha256": "3c3c251f49f4dae610eb9c84ca2080ead685e0ede0a9a81077ff54542a8f159d", "fetch_bytes": 6232760, "write_bytes": 507904},
+    "oproj": {"source_sha256": "3c3c251f49f4dae610eb9c84ca2080ead685e0ede0a9a81077ff54542a8f159d", "fetch_bytes": 5444322, "write_bytes": 516096},
+    "prep": {"source_sha256": "3c3c251f49f4dae610eb9c84ca2080ead685e0ede0a9a81077ff54542a8f159d", "fetch_bytes": 946608, "write_bytes": 809562},
+    "lmhead": {"source_sha256": "3c3c251f49f4dae610eb9c84ca2080ead685e0ede0a9a81077ff54542a8f159d", "fetch_bytes": 274908243, "write_bytes": 322567},
 }
 
 
